@@ -1,0 +1,253 @@
+"""CPU oracle for one FastVAR pruned decoding step (TEST INFRASTRUCTURE ONLY).
+
+A plain, slow, fp64 NumPy statement of what the hot path computes, written
+from the paper (FastVAR, arXiv 2503.23367): pivotal token selection (Sec. 3.3,
+Eq. 4-5, Alg. 1 first function), one pre-LayerNorm transformer block on the
+kept tokens attending to the multi-scale KV cache (Sec. 3.1 KV-cache remark,
+Sec. 3.3: only kept tokens enter the cache), and cached token
+restoration (Sec. 3.3, Eq. 6, Alg. 1 second function).
+
+It is the checker, not the product: only tests, the smoke entry and the
+benchmark's cpu_baseline leg may import it.  It shares no code with the HIP
+path and imports nothing from it.
+
+Pins (tests/test_oracle_*.py): brute-force loops and exhaustive sorts on tiny
+maps, closed forms (variance identity, shift invariance, constant maps,
+half-pixel bilinear weights), keep-ratio 1.0 == dense block, library routines
+of torch-CPU for LayerNorm / attention / GELU / bilinear interpolation, and a
+hand-worked fixture under tests/golden/.  The paper prints no worked numeric
+example of a whole step, so `step` as a composition is pinned only through its
+parts: whole-step values are "parity unpinned" against the paper itself.
+
+Readings taken where the paper is silent or inconsistent (also listed in the
+design notes):
+  * score is the squared L2 distance (Alg. 1) -- same ordering as Eq. 5's norm;
+  * the top-k decision is taken on the score rounded to fp32, ties go to the
+    lowest token index, the index set is emitted ascending;
+  * `interpolate` is bilinear with half-pixel centres, edges clamped;
+  * one select/restore pair wraps the whole block (Fig. 2(b) wraps each
+    sub-layer; that finer wiring is not built here);
+  * the cached map and the block output are post-residual hidden states;
+  * block internals (pre-LN, eps, 1/sqrt(dh), erf-GELU, biases) come from the
+    workload definition, not the paper;
+  * nothing is masked at decode time: queries of the current scale see every
+    cached key of earlier scales and every kept key of the current scale.
+"""
+from __future__ import annotations
+
+import math
+from typing import Dict, Optional, Tuple
+
+import numpy as np
+from scipy.special import erf as _erf
+
+F64 = np.float64
+
+
+# ---------------------------------------------------------------------------
+# ratio -> count  (Sec. 4.1 gives pruning ratios; keep = 1 - prune)
+# ---------------------------------------------------------------------------
+
+def keep_count(N: int, keep_ratio: float) -> int:
+    """Number of kept tokens for a keep ratio: round-half-up of keep*N, clamped."""
+    k = int(math.floor(float(keep_ratio) * N + 0.5))
+    return max(0, min(N, k))
+
+
+# ---------------------------------------------------------------------------
+# Pivotal Token Selection  (Sec. 3.3, Eq. 4, Eq. 5)
+# ---------------------------------------------------------------------------
+
+def dc_component(x: np.ndarray) -> np.ndarray:
+    """Eq. 4: per-sample, per-channel mean over the h*w token positions.
+
+    x [B, N, D] -> [B, D] (fp64).
+    """
+    x = np.asarray(x, dtype=F64)
+    return x.sum(axis=1) / x.shape[1]
+
+
+def pivotal_scores(x: np.ndarray) -> np.ndarray:
+    """Eq. 5 in the squared form of Alg. 1: s[b,n] = sum_c (x[b,n,c]-mean[b,c])^2.
+
+    Returns fp64 scores [B, N].
+    """
+    x = np.asarray(x, dtype=F64)
+    hf = x - dc_component(x)[:, None, :]          # high-frequency part
+    return (hf * hf).sum(axis=-1)
+
+
+def topk_indices(score32: np.ndarray, k: int) -> np.ndarray:
+    """Indices of the k largest scores per sample, ties to the lowest index.
+
+    score32 [B, N] fp32 -> int32 [B, k], each row ascending.
+    A stable descending sort keeps equal scores in ascending index order, so
+    its first k entries are exactly the lowest-index winners.
+    """
+    s = np.asarray(score32, dtype=np.float32)
+    B, N = s.shape
+    if not 0 <= k <= N:
+        raise ValueError("k out of range")
+    out = np.empty((B, k), dtype=np.int32)
+    for b in range(B):
+        order = np.argsort(-s[b].astype(F64), kind="stable")
+        out[b] = np.sort(order[:k])
+    return out
+
+
+def select_pivotal(x: np.ndarray, k: int) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """PTS: (idx [B,k] ascending int32, rank [B,N] int32, score [B,N] fp32).
+
+    rank[b,n] is the position of token n inside idx[b], or -1 if pruned.
+    """
+    s32 = pivotal_scores(x).astype(np.float32)
+    idx = topk_indices(s32, k)
+    B, N = s32.shape
+    rank = np.full((B, N), -1, dtype=np.int32)
+    for b in range(B):
+        rank[b, idx[b]] = np.arange(k, dtype=np.int32)
+    return idx, rank, s32
+
+
+def gather_tokens(x: np.ndarray, idx: np.ndarray) -> np.ndarray:
+    """x [B,N,D], idx [B,k] -> x_kept [B,k,D] (Alg. 1 gather)."""
+    x = np.asarray(x)
+    return np.stack([x[b, idx[b]] for b in range(x.shape[0])], axis=0)
+
+
+# ---------------------------------------------------------------------------
+# Transformer block on the kept tokens
+# ---------------------------------------------------------------------------
+
+def layer_norm(a: np.ndarray, gamma: np.ndarray, beta: np.ndarray, eps: float) -> np.ndarray:
+    """LayerNorm over the last axis, biased variance."""
+    a = np.asarray(a, dtype=F64)
+    m = a.mean(axis=-1, keepdims=True)
+    v = ((a - m) ** 2).mean(axis=-1, keepdims=True)
+    return (a - m) / np.sqrt(v + eps) * np.asarray(gamma, F64) + np.asarray(beta, F64)
+
+
+def gelu(a: np.ndarray) -> np.ndarray:
+    """Exact GELU: a * Phi(a) with the Gaussian CDF through erf."""
+    a = np.asarray(a, dtype=F64)
+    return 0.5 * a * (1.0 + _erf(a / math.sqrt(2.0)))
+
+
+def linear(a: np.ndarray, w: np.ndarray, b: Optional[np.ndarray]) -> np.ndarray:
+    """a [..., in] times w [out, in] transposed, plus bias."""
+    y = np.asarray(a, F64) @ np.asarray(w, F64).T
+    if b is not None:
+        y = y + np.asarray(b, F64)
+    return y
+
+
+def attention(q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: float) -> np.ndarray:
+    """Materialised softmax attention, no mask.
+
+    q [M, H, dh], K/V [L, H, dh] -> [M, H, dh].
+    """
+    M, H, dh = q.shape
+    out = np.empty((M, H, dh), dtype=F64)
+    for h in range(H):
+        s = (q[:, h, :] @ K[:, h, :].T) * scale          # [M, L]
+        s = s - s.max(axis=-1, keepdims=True)
+        p = np.exp(s)
+        p = p / p.sum(axis=-1, keepdims=True)
+        out[:, h, :] = p @ V[:, h, :]
+    return out
+
+
+def block_forward_pruned(xk: np.ndarray, W: Dict[str, np.ndarray], H: int,
+                         k_cache: np.ndarray, v_cache: np.ndarray,
+                         eps: float = 1e-6, scale: Optional[float] = None,
+                         return_parts: bool = False):
+    """One pre-LN block on kept tokens xk [B,k,D].
+
+    k_cache / v_cache [B, L0, H, dh] hold the keys/values of all earlier
+    scales.  Keys seen by the kept queries are the cached ones followed by the
+    kept tokens' own; only the kept tokens' K/V are appended (Sec. 3.3).
+
+    Returns (yk [B,k,D], k_new [B,k,H,dh], v_new [B,k,H,dh]); with
+    return_parts also the dict of intermediates (a1, q, o, h1, a2, u).
+    """
+    xk = np.asarray(xk, F64)
+    B, k, D = xk.shape
+    dh = D // H
+    if scale is None:
+        scale = 1.0 / math.sqrt(dh)
+    a1 = layer_norm(xk, W["ln1_g"], W["ln1_b"], eps)
+    qkv = linear(a1, W["w_qkv"], W.get("b_qkv"))
+    q = qkv[..., 0 * D:1 * D].reshape(B, k, H, dh)
+    kn = qkv[..., 1 * D:2 * D].reshape(B, k, H, dh)
+    vn = qkv[..., 2 * D:3 * D].reshape(B, k, H, dh)
+    o = np.empty((B, k, D), dtype=F64)
+    for b in range(B):
+        Kall = np.concatenate([np.asarray(k_cache[b], F64), kn[b]], axis=0)
+        Vall = np.concatenate([np.asarray(v_cache[b], F64), vn[b]], axis=0)
+        o[b] = attention(q[b], Kall, Vall, scale).reshape(k, D)
+    h1 = xk + linear(o, W["w_proj"], W.get("b_proj"))
+    a2 = layer_norm(h1, W["ln2_g"], W["ln2_b"], eps)
+    u = gelu(linear(a2, W["w_fc1"], W.get("b_fc1")))
+    yk = h1 + linear(u, W["w_fc2"], W.get("b_fc2"))
+    if return_parts:
+        return yk, kn, vn, dict(a1=a1, q=q, o=o, h1=h1, a2=a2, u=u)
+    return yk, kn, vn
+
+
+# ---------------------------------------------------------------------------
+# Cached Token Restoration  (Sec. 3.3, Eq. 6)
+# ---------------------------------------------------------------------------
+
+def _taps(n_in: int, n_out: int):
+    """Half-pixel-centre linear resampling taps along one axis.
+
+    For output position d the source coordinate is (d+0.5)*n_in/n_out-0.5,
+    clamped into [0, n_in-1]; returns (i0, i1, lam) with value
+    (1-lam)*src[i0] + lam*src[i1].
+    """
+    d = np.arange(n_out, dtype=F64)
+    src = (d + 0.5) * (float(n_in) / float(n_out)) - 0.5
+    src = np.clip(src, 0.0, float(n_in - 1))
+    i0 = np.floor(src).astype(np.int64)
+    i1 = np.minimum(i0 + 1, n_in - 1)
+    return i0, i1, src - i0
+
+
+def upsample_bilinear(cache_map: np.ndarray, hc: int, wc: int, h: int, w: int) -> np.ndarray:
+    """Eq. 6: cache_map [B, hc*wc, D] -> [B, h*w, D], bilinear, fp64."""
+    c = np.asarray(cache_map, F64)
+    B, Nc, D = c.shape
+    assert Nc == hc * wc
+    c = c.reshape(B, hc, wc, D)
+    r0, r1, lr = _taps(hc, h)
+    c0, c1, lc = _taps(wc, w)
+    rows = c[:, r0] * (1.0 - lr)[None, :, None, None] + c[:, r1] * lr[None, :, None, None]
+    out = rows[:, :, c0] * (1.0 - lc)[None, None, :, None] + rows[:, :, c1] * lc[None, None, :, None]
+    return out.reshape(B, h * w, D)
+
+
+def restore(yk: np.ndarray, idx: np.ndarray, cache_map: np.ndarray,
+            hc: int, wc: int, h: int, w: int) -> np.ndarray:
+    """CTR: the upsampled cache with the kept outputs scattered in at idx."""
+    y = upsample_bilinear(cache_map, hc, wc, h, w)
+    yk = np.asarray(yk, F64)
+    for b in range(y.shape[0]):
+        y[b, idx[b]] = yk[b]
+    return y
+
+
+# ---------------------------------------------------------------------------
+# Whole step
+# ---------------------------------------------------------------------------
+
+def step(x, h, w, k, W, H, k_cache, v_cache, cache_map, hc, wc,
+         eps: float = 1e-6, scale: Optional[float] = None):
+    """select -> block on kept tokens -> restore, block granularity.
+
+    Returns dict(idx, rank, score, yk, k_new, v_new, y).
+    """
+    idx, rank, s32 = select_pivotal(x, k)
+    xk = gather_tokens(np.asarray(x, F64), idx)
+    yk, kn, vn = block_forward_pruned(xk, W, H, k_cache, v_cache, eps, scale)
+    y = restore(yk, idx, cache_map, hc, wc, h, w)
+    return dict(idx=idx, rank=rank, score=s32, yk=yk, k_new=kn, v_new=vn, y=y)

@@ -1,0 +1,284 @@
+"""Pins for the oracle's block forward and cached token restoration.
+
+Block internals are textbook routines (LayerNorm, softmax attention, erf-GELU,
+linear layers); they are pinned against torch-CPU library routines in fp64 and
+against special cases with known answers.  Restoration (Sec. 3.3, Eq. 6) is
+pinned by closed forms, a hand-worked fixture and torch's bilinear resampler.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as TF
+
+from oracle import fastvar_oracle as O
+from paper_2503_23367_amd import synth
+from test_oracle_select import _read_golden
+
+DIMS = synth.BlockDims(D=32, H=4, dh=8, F=64)
+
+
+def _rand_weights(seed, dims=DIMS, scale=0.2):
+    rng = np.random.default_rng(seed)
+    D, F = dims.D, dims.F
+    g = lambda *s: rng.standard_normal(s) * scale
+    return dict(ln1_g=1 + g(D), ln1_b=g(D), w_qkv=g(3 * D, D), b_qkv=g(3 * D),
+                w_proj=g(D, D), b_proj=g(D), ln2_g=1 + g(D), ln2_b=g(D),
+                w_fc1=g(F, D), b_fc1=g(F), w_fc2=g(D, F), b_fc2=g(D))
+
+
+def _torch_block(xk, W, H, kc, vc, eps):
+    """The same block through torch-CPU library routines, fp64."""
+    t = lambda a: torch.from_numpy(np.asarray(a, np.float64))
+    x = t(xk)
+    B, k, D = x.shape
+    dh = D // H
+    a1 = TF.layer_norm(x, (D,), t(W["ln1_g"]), t(W["ln1_b"]), eps)
+    qkv = TF.linear(a1, t(W["w_qkv"]), t(W["b_qkv"]))
+    q, kn, vn = qkv.split(D, dim=-1)
+    q = q.reshape(B, k, H, dh)
+    kn = kn.reshape(B, k, H, dh)
+    vn = vn.reshape(B, k, H, dh)
+    K = torch.cat([t(kc), kn], dim=1)
+    V = torch.cat([t(vc), vn], dim=1)
+    o = TF.scaled_dot_product_attention(q.transpose(1, 2), K.transpose(1, 2), V.transpose(1, 2))
+    o = o.transpose(1, 2).reshape(B, k, D)
+    h1 = x + TF.linear(o, t(W["w_proj"]), t(W["b_proj"]))
+    a2 = TF.layer_norm(h1, (D,), t(W["ln2_g"]), t(W["ln2_b"]), eps)
+    u = TF.gelu(TF.linear(a2, t(W["w_fc1"]), t(W["b_fc1"])))
+    y = h1 + TF.linear(u, t(W["w_fc2"]), t(W["b_fc2"]))
+    return y.numpy(), kn.numpy(), vn.numpy()
+
+
+def test_block_matches_torch_library_routines():
+    rng = np.random.default_rng(1)
+    W = _rand_weights(2)
+    B, k, L0 = 2, 11, 7
+    xk = rng.standard_normal((B, k, DIMS.D))
+    kc = rng.standard_normal((B, L0, DIMS.H, DIMS.dh))
+    vc = rng.standard_normal((B, L0, DIMS.H, DIMS.dh))
+    y, kn, vn = O.block_forward_pruned(xk, W, DIMS.H, kc, vc, eps=1e-6)
+    yt, knt, vnt = _torch_block(xk, W, DIMS.H, kc, vc, 1e-6)
+    np.testing.assert_allclose(y, yt, rtol=1e-10, atol=1e-10)
+    np.testing.assert_allclose(kn, knt, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(vn, vnt, rtol=1e-12, atol=1e-12)
+
+
+def test_layer_norm_special_cases():
+    g = np.array([2.0, 3.0, 4.0, 5.0])
+    b = np.array([0.1, 0.2, 0.3, 0.4])
+    # constant row -> exactly beta
+    np.testing.assert_allclose(O.layer_norm(np.full((1, 4), 7.0), g, b, 1e-6), b[None], atol=1e-12)
+    # row (-1, 1, -1, 1): mean 0, biased var 1
+    out = O.layer_norm(np.array([[-1.0, 1.0, -1.0, 1.0]]), g, b, 0.0)
+    np.testing.assert_allclose(out, [[-2 + .1, 3 + .2, -4 + .3, 5 + .4]], atol=1e-12)
+    # biased (divide by D) variance: row (0, 2): var = 1, not 2
+    out = O.layer_norm(np.array([[0.0, 2.0]]), np.ones(2), np.zeros(2), 0.0)
+    np.testing.assert_allclose(out, [[-1.0, 1.0]], atol=1e-12)
+
+
+def test_gelu_known_values():
+    np.testing.assert_allclose(O.gelu(np.array([0.0])), [0.0])
+    # GELU(x) - GELU(-x) = x ; GELU(1) = Phi(1) = 0.841344746...
+    x = np.linspace(-4, 4, 33)
+    np.testing.assert_allclose(O.gelu(x) - O.gelu(-x), x, atol=1e-12)
+    assert O.gelu(np.array([1.0]))[0] == pytest.approx(0.8413447460685429, abs=1e-12)
+    assert O.gelu(np.array([-10.0]))[0] == pytest.approx(0.0, abs=1e-12)
+
+
+def test_attention_equal_keys_gives_mean_of_values():
+    rng = np.random.default_rng(4)
+    q = rng.standard_normal((5, 2, 4))
+    K = np.tile(rng.standard_normal((1, 2, 4)), (9, 1, 1))
+    V = rng.standard_normal((9, 2, 4))
+    out = O.attention(q, K, V, 0.5)
+    np.testing.assert_allclose(out, np.tile(V.mean(axis=0)[None], (5, 1, 1)), atol=1e-12)
+
+
+def test_attention_one_hot_key_selects_its_value_and_heads_do_not_mix():
+    # query aligned with key j at huge scale -> output is V[j]; per head.
+    H, dh, L = 2, 4, 6
+    K = np.zeros((L, H, dh))
+    for j in range(L):
+        K[j, 0, j % dh] = 1.0 + j          # head 0: distinct lengths
+        K[j, 1, (j + 1) % dh] = 1.0 + j
+    V = np.random.default_rng(5).standard_normal((L, H, dh))
+    q = np.zeros((1, H, dh))
+    q[0, 0, 5 % dh] = 1.0      # head 0 best match: largest j with j%dh==1 -> j=5
+    q[0, 1, (3 + 1) % dh] = 1.0  # head 1: keys with (j+1)%dh==0 -> j=3 only
+    out = O.attention(q, K, V, 1e3)
+    np.testing.assert_allclose(out[0, 0], V[5, 0], atol=1e-9)
+    np.testing.assert_allclose(out[0, 1], V[3, 1], atol=1e-9)
+
+
+def test_zero_weights_block_is_identity_on_kept_tokens():
+    W = {k: np.zeros_like(v) for k, v in _rand_weights(0).items()}
+    xk = np.random.default_rng(6).standard_normal((1, 5, DIMS.D))
+    kc = np.zeros((1, 3, DIMS.H, DIMS.dh))
+    y, kn, vn = O.block_forward_pruned(xk, W, DIMS.H, kc, kc)
+    np.testing.assert_array_equal(y, xk)
+    assert not kn.any() and not vn.any()
+
+
+def _dense_block_all_tokens(x, W, H, kc, vc, eps):
+    """Unpruned block written separately: per token, per head, explicit softmax."""
+    B, N, D = x.shape
+    dh = D // H
+    y = np.zeros_like(x)
+    for b in range(B):
+        a1 = np.stack([O.layer_norm(x[b, n], W["ln1_g"], W["ln1_b"], eps) for n in range(N)])
+        qkv = a1 @ W["w_qkv"].T + W["b_qkv"]
+        q, kn, vn = qkv[:, :D], qkv[:, D:2 * D], qkv[:, 2 * D:]
+        o = np.zeros((N, D))
+        for n in range(N):
+            for hh in range(H):
+                sl = slice(hh * dh, (hh + 1) * dh)
+                keys = np.concatenate([kc[b][:, hh, :], kn[:, sl]])
+                vals = np.concatenate([vc[b][:, hh, :], vn[:, sl]])
+                logits = keys @ q[n, sl] / math.sqrt(dh)
+                wgt = np.exp(logits - logits.max())
+                wgt /= wgt.sum()
+                o[n, sl] = wgt @ vals
+        h1 = x[b] + o @ W["w_proj"].T + W["b_proj"]
+        a2 = np.stack([O.layer_norm(h1[n], W["ln2_g"], W["ln2_b"], eps) for n in range(N)])
+        u = O.gelu(a2 @ W["w_fc1"].T + W["b_fc1"])
+        y[b] = h1 + u @ W["w_fc2"].T + W["b_fc2"]
+    return y
+
+
+def test_keep_ratio_one_equals_dense_unpruned_block():
+    rng = np.random.default_rng(8)
+    W = _rand_weights(9)
+    B, h, w, L0 = 2, 3, 4, 5
+    N = h * w
+    x = rng.standard_normal((B, N, DIMS.D))
+    kc = rng.standard_normal((B, L0, DIMS.H, DIMS.dh))
+    vc = rng.standard_normal((B, L0, DIMS.H, DIMS.dh))
+    cache = rng.standard_normal((B, 4, DIMS.D))
+    r = O.step(x, h, w, N, W, DIMS.H, kc, vc, cache, 2, 2)
+    dense = _dense_block_all_tokens(x, W, DIMS.H, kc, vc, 1e-6)
+    np.testing.assert_allclose(r["y"], dense, rtol=1e-10, atol=1e-10)
+    np.testing.assert_array_equal(r["idx"], np.tile(np.arange(N, dtype=np.int32), (B, 1)))
+
+
+def test_kept_order_does_not_change_restored_map():
+    """Shuffling the kept set (and scattering back by the same order) is a no-op."""
+    rng = np.random.default_rng(10)
+    W = _rand_weights(11)
+    x = rng.standard_normal((1, 12, DIMS.D))
+    kc = rng.standard_normal((1, 4, DIMS.H, DIMS.dh))
+    vc = rng.standard_normal((1, 4, DIMS.H, DIMS.dh))
+    cache = rng.standard_normal((1, 4, DIMS.D))
+    idx, _, _ = O.select_pivotal(x, 6)
+    perm = rng.permutation(6)
+    y1, _, _ = O.block_forward_pruned(O.gather_tokens(x, idx), W, DIMS.H, kc, vc)
+    idx2 = idx[:, perm]
+    y2, _, _ = O.block_forward_pruned(O.gather_tokens(x, idx2), W, DIMS.H, kc, vc)
+    np.testing.assert_allclose(y2, y1[:, perm], rtol=1e-10, atol=1e-12)
+    r1 = O.restore(y1, idx, cache, 2, 2, 3, 4)
+    r2 = O.restore(y2, idx2, cache, 2, 2, 3, 4)
+    np.testing.assert_allclose(r1, r2, rtol=1e-10, atol=1e-12)
+
+
+def test_cache_grows_by_kept_tokens_only():
+    rng = np.random.default_rng(12)
+    W = _rand_weights(13)
+    x = rng.standard_normal((1, 16, DIMS.D))
+    kc = rng.standard_normal((1, 9, DIMS.H, DIMS.dh))
+    r = O.step(x, 4, 4, 5, W, DIMS.H, kc, kc, rng.standard_normal((1, 4, DIMS.D)), 2, 2)
+    assert r["k_new"].shape == (1, 5, DIMS.H, DIMS.dh)
+    assert r["v_new"].shape == (1, 5, DIMS.H, DIMS.dh)
+    assert r["y"].shape == x.shape          # token-number invariance of PTS+CTR
+
+
+# ------------------------------ restoration ---------------------------------
+
+def test_upsample_matches_torch_bilinear_half_pixel():
+    rng = np.random.default_rng(14)
+    for (hc, wc, h, w) in [(2, 2, 4, 4), (13, 13, 16, 16), (3, 5, 7, 6), (32, 32, 64, 64),
+                           (1, 1, 5, 3), (4, 4, 4, 4), (18, 18, 24, 24)]:
+        c = rng.standard_normal((2, hc * wc, 3))
+        got = O.upsample_bilinear(c, hc, wc, h, w)
+        t = torch.from_numpy(c).reshape(2, hc, wc, 3).permute(0, 3, 1, 2)
+        want = TF.interpolate(t, size=(h, w), mode="bilinear", align_corners=False)
+        want = want.permute(0, 2, 3, 1).reshape(2, h * w, 3).numpy()
+        np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+
+
+def test_upsample_closed_forms():
+    rng = np.random.default_rng(15)
+    # constant map stays constant
+    c = np.full((1, 9, 2), 3.25)
+    np.testing.assert_allclose(O.upsample_bilinear(c, 3, 3, 8, 8), np.full((1, 64, 2), 3.25))
+    # same size is the identity
+    c = rng.standard_normal((1, 20, 3))
+    np.testing.assert_allclose(O.upsample_bilinear(c, 4, 5, 4, 5), c, atol=1e-15)
+    # 1x1 broadcasts
+    c = rng.standard_normal((2, 1, 3))
+    np.testing.assert_array_equal(O.upsample_bilinear(c, 1, 1, 3, 2), np.tile(c, (1, 6, 1)))
+    # a linear ramp stays linear away from the clamped border (rows and cols distinct)
+    hc, wc, h, w = 6, 5, 12, 10
+    ii, jj = np.meshgrid(np.arange(hc), np.arange(wc), indexing="ij")
+    c = (2.0 * ii + 7.0 * jj).reshape(1, hc * wc, 1).astype(float)
+    up = O.upsample_bilinear(c, hc, wc, h, w).reshape(h, w)
+    for i in range(1, h - 1):
+        for j in range(1, w - 1):
+            si = (i + 0.5) * hc / h - 0.5
+            sj = (j + 0.5) * wc / w - 0.5
+            assert up[i, j] == pytest.approx(2.0 * si + 7.0 * sj, abs=1e-12)
+
+
+def test_golden_bilinear_2x2_to_4x4():
+    g = _read_golden("bilinear_2x2_to_4x4.txt")
+    c = np.array(g["cache_2x2"]).reshape(1, 4, 1)
+    up = O.upsample_bilinear(c, 2, 2, 4, 4).reshape(-1)
+    np.testing.assert_allclose(up, g["up_4x4"], atol=1e-14)
+
+
+def test_golden_restore_2x2():
+    g = _read_golden("pts_ctr_2x2.txt")
+    yk = np.array(g["yk"]).reshape(1, 2, 2)
+    idx = np.array([g["idx_k2"]], dtype=np.int32)
+    cache = np.array(g["cache_1x1"]).reshape(1, 1, 2)
+    y = O.restore(yk, idx, cache, 1, 1, 2, 2)
+    np.testing.assert_array_equal(y.reshape(-1), g["y_restored"])
+
+
+def test_restore_kept_slots_and_pruned_slots():
+    rng = np.random.default_rng(16)
+    B, hc, wc, h, w, D, k = 2, 3, 3, 5, 5, 4, 7
+    cache = rng.standard_normal((B, hc * wc, D))
+    yk = rng.standard_normal((B, k, D))
+    idx = np.stack([np.sort(rng.permutation(h * w)[:k]) for _ in range(B)]).astype(np.int32)
+    y = O.restore(yk, idx, cache, hc, wc, h, w)
+    up = O.upsample_bilinear(cache, hc, wc, h, w)
+    for b in range(B):
+        kept = np.zeros(h * w, bool)
+        kept[idx[b]] = True
+        np.testing.assert_array_equal(y[b, idx[b]], yk[b])
+        np.testing.assert_array_equal(y[b, ~kept], up[b, ~kept])
+    # k = 0: pure upsample ; k = N: pure permutation back
+    y0 = O.restore(np.zeros((B, 0, D)), np.zeros((B, 0), np.int32), cache, hc, wc, h, w)
+    np.testing.assert_array_equal(y0, up)
+    full = np.tile(np.arange(h * w, dtype=np.int32), (B, 1))
+    ykf = rng.standard_normal((B, h * w, D))
+    np.testing.assert_array_equal(O.restore(ykf, full, cache, hc, wc, h, w), ykf)
+
+
+def test_planted_mistakes_are_caught(monkeypatch):
+    """Each plausible slip in the oracle must trip at least one pin above."""
+    rng = np.random.default_rng(17)
+    c = rng.standard_normal((1, 6, 2))
+    ref = O.upsample_bilinear(c, 2, 3, 4, 6)
+    # transposed grid (h,w swapped) must differ
+    assert not np.allclose(O.upsample_bilinear(c, 3, 2, 4, 6), ref)
+    # corner-aligned taps instead of half-pixel must differ from torch's half-pixel result
+    t = torch.from_numpy(c).reshape(1, 2, 3, 2).permute(0, 3, 1, 2)
+    ac = TF.interpolate(t, size=(4, 6), mode="bilinear", align_corners=True)
+    assert not np.allclose(ac.permute(0, 2, 3, 1).reshape(1, 24, 2).numpy(), ref)
+    # mean over channels instead of positions would break the shift-invariance pin
+    x = rng.standard_normal((1, 8, 4))
+    wrong = ((x - x.mean(axis=2, keepdims=True)) ** 2).sum(-1)
+    assert not np.allclose(wrong, O.pivotal_scores(x))

@@ -1,0 +1,289 @@
+#!/usr/bin/env python3
+"""Benchmark of the pruned VAR decoding step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A step is one pass of the whole hot path -- pivotal token selection, the
+transformer block on the kept tokens, cached token restoration -- through every
+block of the stack at the last scale of the 1024 px Infinity-2B-style schedule
+with keep ratio 0.5 (64x64 map, 2048 kept tokens, 6425 prior cache tokens,
+32 blocks with distinct weights, caches and cached maps).  Inputs are seeded
+and synthetic and are resident in HBM before the timed region.
+
+Prints ONE JSON line: effective tokens/s (B*N restored tokens per step time),
+ms per step, per-kernel timings, the roofline record of the dominant kernel
+and the CPU oracle baseline (one block, timed on the host cores).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from paper_2503_23367_amd import synth  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_state(wl, n_blocks, seed=0):
+    """All device buffers of the workload.  Block 0 comes from the shared
+    seeded numpy generators (so the CPU oracle can be fed the same values);
+    the remaining blocks are drawn on the GPU with the same distributions."""
+    import torch
+    from paper_2503_23367_amd import binding as fb
+    dev = "cuda:0"
+    dims = wl.dims
+    B, N, k, L0 = wl.B, wl.N, wl.k, wl.L0_full
+    L_cap = (L0 + k + 7) // 8 * 8
+
+    def up(a):
+        bits = synth.to_bf16_bits(a).astype(np.int16)
+        return torch.from_numpy(bits).to(dev).view(torch.bfloat16).reshape(a.shape)
+
+    host = dict(
+        x=synth.token_map(seed, B, wl.h, wl.h, dims.D),
+        W=synth.block_weights(seed, dims),
+        cache=synth.cached_map(seed, B, wl.hc, wl.hc, dims.D),
+    )
+    host["kp"], host["vp"] = synth.kv_prior(seed, B, L0, dims.H, dims.dh)
+
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed + 12345)
+
+    def randn(shape, std=1.0, mean=0.0):
+        return (torch.randn(shape, generator=gen, device=dev, dtype=torch.float32) * std + mean).to(torch.bfloat16)
+
+    blocks = []
+    for blk in range(n_blocks):
+        if blk == 0:
+            wt = {n: up(a) for n, a in host["W"].items()}
+            kc = torch.zeros((B, dims.H, L_cap, dims.dh), dtype=torch.bfloat16, device=dev)
+            vc = torch.zeros((B, dims.H, dims.dh, L_cap), dtype=torch.bfloat16, device=dev)
+            kc[:, :, :L0] = up(host["kp"]).permute(0, 2, 1, 3)
+            vc[:, :, :, :L0] = up(host["vp"]).permute(0, 2, 3, 1)
+            cache = up(host["cache"])
+        else:
+            D, F = dims.D, dims.F
+            wt = dict(ln1_g=randn((D,), 0.02, 1.0), ln1_b=randn((D,), 0.02),
+                      w_qkv=randn((3 * D, D), 0.02), b_qkv=randn((3 * D,), 0.02),
+                      w_proj=randn((D, D), 0.02), b_proj=randn((D,), 0.02),
+                      ln2_g=randn((D,), 0.02, 1.0), ln2_b=randn((D,), 0.02),
+                      w_fc1=randn((F, D), 0.02), b_fc1=randn((F,), 0.02),
+                      w_fc2=randn((D, F), 0.02), b_fc2=randn((D,), 0.02))
+            kc = torch.zeros((B, dims.H, L_cap, dims.dh), dtype=torch.bfloat16, device=dev)
+            vc = torch.zeros((B, dims.H, dims.dh, L_cap), dtype=torch.bfloat16, device=dev)
+            kc[:, :, :L0] = randn((B, dims.H, L0, dims.dh))
+            vc[:, :, :, :L0] = randn((B, dims.H, dims.dh, L0))
+            cache = randn((B, wl.hc * wl.hc, dims.D))
+        blocks.append(dict(wt=wt, w=fb.make_weights(wt), kc=kc, vc=vc, cache=cache))
+
+    d = fb.make_dims(dims.D, dims.H, dims.dh, dims.F)
+    ws = torch.empty(fb.fastvar_step_workspace_bytes(d, B, N, k), dtype=torch.uint8, device=dev)
+    xa = up(host["x"])
+    xb = torch.empty_like(xa)
+    idx = torch.empty((B, max(k, 1)), dtype=torch.int32, device=dev)
+    return dict(host=host, blocks=blocks, d=d, ws=ws, x_in=xa.clone(), xa=xa, xb=xb, idx=idx, L_cap=L_cap)
+
+
+def run_step(wl, st):
+    """One pass of the stack at this scale: the output map of a block is the next block's input."""
+    from paper_2503_23367_amd import binding as fb
+    st["xa"].copy_(st["x_in"])          # same starting map every step (outside the kernels' work)
+    src, dst = st["xa"], st["xb"]
+    sides = list(wl.sides)
+    for blk in st["blocks"]:
+        fb.fastvar_step(src, sides, sides, wl.step, wl.cache_step, wl.B, wl.k, st["d"], blk["w"],
+                        blk["kc"], blk["vc"], wl.L0_full, st["L_cap"], blk["cache"], dst, st["idx"], st["ws"])
+        src, dst = dst, src
+    return src
+
+
+def time_kernel(fn, iters):
+    """Average duration (ms) of `fn` launched back to back, from HIP events on
+    the stream the kernels are enqueued on (torch's current stream)."""
+    import torch
+    fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def kernel_table(wl, st, iters):
+    """Each kernel of the step alone, same shapes and launch configuration as inside the step."""
+    import torch
+    from paper_2503_23367_amd import binding as fb
+    dims = wl.dims
+    B, N, k, D, F, H, dh = wl.B, wl.N, wl.k, dims.D, dims.F, dims.H, dims.dh
+    M, L0, L = B * k, wl.L0_full, wl.L0_full + wl.k
+    L_cap = st["L_cap"]
+    blk, d = st["blocks"][0], st["d"]
+    wt = blk["wt"]
+    dev = "cuda:0"
+    bf = torch.bfloat16
+    x = st["x_in"]
+    idx = st["idx"]
+    rank = torch.empty((B, N), dtype=torch.int32, device=dev)
+    sel_ws = torch.empty(fb.fastvar_select_workspace_bytes(B, N, D), dtype=torch.uint8, device=dev)
+    fb.fastvar_select_pivotal(x, B, wl.h, wl.h, D, k, idx, rank, None, sel_ws)
+    a = torch.empty((M, D), dtype=bf, device=dev)
+    q = torch.empty((M, D), dtype=bf, device=dev)
+    o = torch.empty((M, D), dtype=bf, device=dev)
+    h1 = torch.empty((M, D), dtype=bf, device=dev)
+    u = torch.empty((M, F), dtype=bf, device=dev)
+    yk = torch.empty((M, D), dtype=bf, device=dev)
+    y = torch.empty((B, N, D), dtype=bf, device=dev)
+    fb.fastvar_layernorm(x, idx, B, N, k, D, wt["ln1_g"], wt["ln1_b"], 1e-6, a)
+    b2 = 2  # bytes per bf16
+    rows = [
+        ("select (colsum+score+topk)", "hbm", B * N * D * b2,
+         lambda: fb.fastvar_select_pivotal(x, B, wl.h, wl.h, D, k, idx, rank, None, sel_ws)),
+        ("gather+layernorm", "hbm", 2 * M * D * b2,
+         lambda: fb.fastvar_layernorm(x, idx, B, N, k, D, wt["ln1_g"], wt["ln1_b"], 1e-6, a)),
+        ("qkv gemm", "mfma", 2.0 * M * D * 3 * D,
+         lambda: fb.fastvar_qkv_gemm(a, wt["w_qkv"], wt["b_qkv"], B, k, d, q, blk["kc"], blk["vc"], L0, L_cap)),
+        ("attention", "mfma", 4.0 * B * k * L * D,
+         lambda: fb.fastvar_attention(q, blk["kc"], blk["vc"], B, k, d, L, L_cap, o)),
+        ("proj gemm", "mfma", 2.0 * M * D * D,
+         lambda: fb.fastvar_gemm_bf16(o, wt["w_proj"], wt["b_proj"], a, M, D, D, fb.EPI_BIAS_RES, h1)),
+        ("layernorm 2", "hbm", 2 * M * D * b2,
+         lambda: fb.fastvar_layernorm(h1, None, 1, 0, M, D, wt["ln2_g"], wt["ln2_b"], 1e-6, q)),
+        ("fc1 gemm", "mfma", 2.0 * M * D * F,
+         lambda: fb.fastvar_gemm_bf16(q, wt["w_fc1"], wt["b_fc1"], None, M, F, D, fb.EPI_BIAS_GELU, u)),
+        ("fc2 gemm", "mfma", 2.0 * M * D * F,
+         lambda: fb.fastvar_gemm_bf16(u, wt["w_fc2"], wt["b_fc2"], h1, M, D, F, fb.EPI_BIAS_RES, yk)),
+        ("restore", "hbm", (B * N * D + M * D + B * wl.hc * wl.hc * D) * b2,
+         lambda: fb.fastvar_restore(yk, idx, rank, B, k, blk["cache"], wl.hc, wl.hc, wl.h, wl.h, D, y)),
+    ]
+    out = []
+    for name, bound, work, fn in rows:
+        ms = time_kernel(fn, iters)
+        if bound == "mfma":
+            ach, peak, unit = work / (ms * 1e-3) / 1e12, PEAK_BF16_TFLOPS, "TFLOP/s"
+        else:
+            ach, peak, unit = work / (ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
+        out.append(dict(kernel=name, bound=bound, ms=round(ms, 5), work=work, achieved=round(ach, 2),
+                        peak=peak, unit=unit, frac=round(ach / peak, 4)))
+        log(f"  {name:28s} {ms*1e3:9.1f} us  {ach:9.1f} {unit:8s} {100*ach/peak:5.1f}% of peak")
+    return out
+
+
+def cpu_baseline(wl, st, n_blocks):
+    """The oracle as it stands, one block of the same workload, on the host cores."""
+    from oracle import fastvar_oracle as O
+    h = st["host"]
+    t0 = time.perf_counter()
+    O.step(h["x"], wl.h, wl.h, wl.k, h["W"], wl.dims.H, h["kp"], h["vp"], h["cache"], wl.hc, wl.hc)
+    dt = time.perf_counter() - t0
+    cores = len(os.sched_getaffinity(0))
+    try:
+        from threadpoolctl import threadpool_info
+        blas = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        blas = cores
+    est_step = dt * n_blocks
+    return dict(value=round(wl.B * wl.N / est_step, 3), unit="tokens/s", cores=min(cores, blas), kind="oracle",
+                sample=f"one block of {n_blocks} (select+block+restore, fp64 NumPy) timed at {dt:.2f} s; "
+                       f"stack time estimated as block time x {n_blocks}",
+                block_seconds=round(dt, 3), affinity_cores=cores, blas_threads=blas)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default=synth.HEADLINE, choices=sorted(synth.WORKLOADS))
+    ap.add_argument("--blocks", type=int, default=0, help="blocks in the stack (default: the workload's)")
+    ap.add_argument("--kernel-iters", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-table", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+    from paper_2503_23367_amd import binding as fb
+    fb.lib()
+    torch.cuda.set_device(0)
+
+    wl = synth.WORKLOADS[args.workload]
+    n_blocks = args.blocks or wl.n_blocks
+    log(f"workload {wl.name}: B={wl.B} N={wl.N} k={wl.k} L0={wl.L0_full} D={wl.dims.D} blocks={n_blocks}")
+    t0 = time.perf_counter()
+    st = build_state(wl, n_blocks)
+    torch.cuda.synchronize()
+    log(f"inputs resident after {time.perf_counter()-t0:.1f} s; "
+        f"HBM in use {torch.cuda.memory_allocated()/2**30:.2f} GiB")
+
+    for _ in range(args.warmup):
+        run_step(wl, st)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        run_step(wl, st)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ev_ms = e0.elapsed_time(e1) / args.steps
+    ms = max(wall_ms, ev_ms)
+    log(f"step: {ms:.3f} ms wall ({ev_ms:.3f} ms by events), {ms/n_blocks*1e3:.1f} us per block")
+
+    kernels = [] if args.no_kernel_table else kernel_table(wl, st, args.kernel_iters)
+    roofline = None
+    if kernels:
+        dom = max(kernels, key=lambda r: r["ms"])
+        roofline = dict(kernel=dom["kernel"], bound=dom["bound"], achieved=dom["achieved"], peak=dom["peak"],
+                        unit=dom["unit"], frac=dom["frac"], traffic=None, launch_ms=dom["ms"])
+    cpu = None if args.no_cpu_baseline else cpu_baseline(wl, st, n_blocks)
+
+    dims = wl.dims
+    M = wl.B * wl.k
+    flops_block = 2.0 * M * (4 * dims.D * dims.D + 2 * dims.D * dims.F) + 4.0 * wl.B * wl.k * (wl.L0_full + wl.k) * dims.D
+    rec = {
+        "metric": "effective tokens/s of the last-scale pruned step (1024px, keep 0.5)",
+        "value": round(wl.B * wl.N / (ms * 1e-3), 1),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "B": wl.B, "tokens": wl.N, "kept": wl.k, "prior_cache_tokens": wl.L0_full,
+                   "D": dims.D, "heads": dims.H, "head_dim": dims.dh, "mlp": dims.F, "blocks": n_blocks,
+                   "step": "select -> block on kept tokens -> restore, every block of the stack"},
+        "processed_tokens_per_s": round(wl.B * wl.k / (ms * 1e-3), 1),
+        "us_per_block": round(ms / n_blocks * 1e3, 2),
+        "mfma_frac_whole_block": round(flops_block * n_blocks / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "kernels": kernels,
+    }
+    print(json.dumps(rec), flush=True)
+
+
+if __name__ == "__main__":
+    main()

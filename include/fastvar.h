@@ -1,0 +1,234 @@
+/*
+ * fastvar.h -- C ABI of the MI355X (gfx950) pruned VAR decoding step.
+ *
+ * One large-scale decoding step of a next-scale-prediction VAR transformer
+ * with FastVAR's cached token pruning (arXiv 2503.23367, Sec. 3.3, Fig. 2,
+ * appendix algorithm):
+ *   1. Pivotal Token Selection (PTS): score every token of the current token
+ *      map by its squared distance from the map mean (Eq. 4, Eq. 5) and keep
+ *      the k highest-scoring tokens.
+ *   2. One pre-LayerNorm transformer block on the kept tokens only; their
+ *      queries attend to the keys/values of all earlier scales held in the
+ *      KV cache plus the kept tokens' own, and only the kept tokens' K/V are
+ *      appended to the cache (Sec. 3.1, Sec. 3.3).
+ *   3. Cached Token Restoration (CTR): the cached output of the last unpruned
+ *      scale is bilinearly upsampled to the current grid (Eq. 6) and the kept
+ *      tokens' outputs are scattered into it at the kept positions.
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless its comment says "host".
+ *   - All activations, weights and caches are bf16 (16-bit patterns); index
+ *     arrays are int32; scores are fp32.
+ *   - Row-major everywhere.  A token map is [B, h*w, D] with token index
+ *     n = i*w + j (row i, column j of the h x w grid).
+ *   - The caller owns every buffer.  The library allocates nothing, keeps no
+ *     state between calls and never synchronises: each call validates its
+ *     arguments on the host, enqueues its kernels on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream) and returns.
+ *   - Return value: FASTVAR_OK (0) or a negative FASTVAR_E* code.  Arguments
+ *     are checked before anything is launched; on an argument error no output
+ *     buffer is touched.
+ *   - Pointers must be 16-byte aligned; D must be a multiple of 8.  The block
+ *     entry points additionally need D, F multiples of 64, dh in {64, 128}
+ *     and L_cap a multiple of 8.
+ *
+ * KV-cache layout (chosen for the attention kernel's 16-byte LDS reads):
+ *   k_cache [B, H, L_cap, dh]   key rows, dh contiguous
+ *   v_cache [B, H, dh, L_cap]   value columns, cache position contiguous
+ * Rows / columns [0, L0) hold the earlier scales; a block call writes
+ * positions [L0, L0+k) and the caller then treats the length as L0+k.
+ */
+#ifndef FASTVAR_H
+#define FASTVAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FASTVAR_VERSION 100 /* major*10000 + minor*100 + patch */
+
+enum {
+    FASTVAR_OK = 0,
+    FASTVAR_EINVAL = -1,     /* null pointer, non-positive size, k outside [0,N], D != H*dh, bad step */
+    FASTVAR_ECAPACITY = -2,  /* L0 + k > L_cap, or a size beyond a documented maximum */
+    FASTVAR_EWORKSPACE = -3, /* ws_bytes smaller than the matching *_workspace_bytes() */
+    FASTVAR_EALIGN = -4,     /* pointer not 16-byte aligned, or a width not a required multiple */
+    FASTVAR_EHIP = -5        /* a kernel launch reported an error */
+};
+
+/* Largest token map the selection kernel accepts (tokens per sample). */
+#define FASTVAR_MAX_TOKENS 32768
+
+/* Block geometry and scalars.  D == H*dh.  ln_eps is LayerNorm's epsilon
+ * (biased variance); softmax_scale multiplies q.k (use 1/sqrt(dh)). */
+typedef struct fastvar_dims {
+    int32_t D;
+    int32_t H;
+    int32_t dh;
+    int32_t F;
+    float ln_eps;
+    float softmax_scale;
+} fastvar_dims;
+
+/* Device pointers to one block's bf16 parameters.  Linear weights are
+ * [out_features, in_features] row-major.  w_qkv is [3D, D] with output rows
+ * ordered q (D rows, feature = head*dh + d), then k, then v.  Biases may be
+ * NULL (treated as zero); everything else must be non-NULL. */
+typedef struct fastvar_block_weights {
+    const void* ln1_g;  /* [D] */
+    const void* ln1_b;  /* [D] */
+    const void* w_qkv;  /* [3D, D] */
+    const void* b_qkv;  /* [3D] or NULL */
+    const void* w_proj; /* [D, D] */
+    const void* b_proj; /* [D] or NULL */
+    const void* ln2_g;  /* [D] */
+    const void* ln2_b;  /* [D] */
+    const void* w_fc1;  /* [F, D] */
+    const void* b_fc1;  /* [F] or NULL */
+    const void* w_fc2;  /* [D, F] */
+    const void* b_fc2;  /* [D] or NULL */
+} fastvar_block_weights;
+
+/* ---- host-only helpers -------------------------------------------------- */
+
+int fastvar_version(void);
+
+/* Static string for an error code. */
+const char* fastvar_strerror(int code);
+
+/* Kept-token count for a keep ratio (keep = 1 - pruning ratio, Sec. 4.1):
+ * floor(keep_ratio*N + 0.5) evaluated in double, clamped to [0, N].
+ * Returns FASTVAR_EINVAL if N < 0. */
+int fastvar_keep_count(int N, double keep_ratio);
+
+/* Scratch bytes needed by fastvar_select_pivotal for a [B, N, D] map. */
+size_t fastvar_select_workspace_bytes(int B, int N, int D);
+
+/* Scratch bytes needed by fastvar_block_forward_pruned for B*k kept tokens. */
+size_t fastvar_block_workspace_bytes(const fastvar_dims* dims, int B, int k);
+
+/* Scratch bytes needed by fastvar_restore when `rank` is NULL (else 0). */
+size_t fastvar_restore_workspace_bytes(int B, int N);
+
+/* Scratch bytes needed by fastvar_step (covers all three stages). */
+size_t fastvar_step_workspace_bytes(const fastvar_dims* dims, int B, int N, int k);
+
+/* ---- device entry points ------------------------------------------------ */
+
+/*
+ * Pivotal Token Selection (Sec. 3.3, Eq. 4-5; appendix algorithm, first
+ * function).
+ *   x          [B, h*w, D] bf16   current token map (layer input)
+ *   k          tokens to keep per sample, 0 <= k <= h*w <= FASTVAR_MAX_TOKENS
+ *   idx_out    [B, k] int32       kept token indices, ascending per sample
+ *   rank_out   [B, h*w] int32     position of token n inside idx_out, -1 if
+ *                                 pruned; may be NULL
+ *   score_out  [B, h*w] fp32      pivotal score; may be NULL
+ *   ws         scratch of fastvar_select_workspace_bytes(B, h*w, D) bytes
+ * The score is sum_c (x[n,c] - mean[c])^2 with the mean over the h*w
+ * positions of the sample, accumulated in fp64 and rounded once to fp32; the
+ * top-k decision is taken on that fp32 value, ties going to the lowest token
+ * index.  Results are bit-reproducible run to run.
+ */
+int fastvar_select_pivotal(const void* x, int B, int h, int w, int D, int k,
+                           int32_t* idx_out, int32_t* rank_out, float* score_out,
+                           void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * One transformer block on the kept tokens (Sec. 3.3, implementation paragraph:
+ * the layer itself is unchanged, it just sees fewer tokens; Sec. 3.1 KV cache).
+ *   x          [B, N, D] bf16     current token map
+ *   idx        [B, k] int32       kept token indices (from selection)
+ *   k_cache    [B, H, L_cap, dh]  bf16, positions [0, L0) valid on entry
+ *   v_cache    [B, H, dh, L_cap]  bf16, positions [0, L0) valid on entry
+ *   y_kept_out [B, k, D] bf16     block output for the kept tokens
+ *   ws         scratch of fastvar_block_workspace_bytes(dims, B, k) bytes
+ * Computes xk = x[idx]; h1 = xk + proj(attn(LN1(xk))); y = h1 + fc2(gelu(
+ * fc1(LN2(h1)))) with exact (erf) GELU; attention is unmasked softmax over
+ * cache positions [0, L0+k), the last k of which this call writes.  k == 0
+ * is a no-op that returns FASTVAR_OK.
+ */
+int fastvar_block_forward_pruned(const void* x, int N, const int32_t* idx, int B, int k,
+                                 const fastvar_dims* dims /* host */,
+                                 const fastvar_block_weights* weights /* host struct of device ptrs */,
+                                 void* k_cache, void* v_cache, int L0, int L_cap,
+                                 void* y_kept_out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Cached Token Restoration (Sec. 3.3, Eq. 6; appendix algorithm, second
+ * function).
+ *   y_kept     [B, k, D] bf16     block output of the kept tokens (NULL ok if k == 0)
+ *   idx        [B, k] int32       kept indices, ascending, unique (NULL ok if k == 0)
+ *   rank       [B, h*w] int32     inverse map from selection, or NULL to have
+ *                                 it rebuilt from idx in `ws`
+ *   cache_map  [B, hc*wc, D] bf16 cached output of the last unpruned scale
+ *   y_out      [B, h*w, D] bf16   restored map; must not alias any input
+ * Kept slots receive the kept outputs bit for bit; every other slot receives
+ * the cached map bilinearly resampled at half-pixel centres
+ * (src = (dst+0.5)*in/out-0.5 clamped to [0,in-1]), computed in fp32 and
+ * rounded once to bf16.  k == 0 gives the pure upsample (a skipped step),
+ * k == h*w the pure scatter.
+ */
+int fastvar_restore(const void* y_kept, const int32_t* idx, const int32_t* rank, int B, int k,
+                    const void* cache_map, int hc, int wc, int h, int w, int D,
+                    void* y_out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * One whole step for one block: selection, block on kept tokens, restoration
+ * (Fig. 2(b) at block granularity).
+ *   sched_h, sched_w  host int arrays of length K: the scale schedule
+ *   step              index of the scale being decoded; (h,w) = sched[step]
+ *   cache_step        index of the scale whose output cache_map holds
+ *                     (the last unpruned one, K-N in the paper); < step
+ *   kv_len            host in/out: cache length before / after the call
+ *   idx_out           [B, k] int32, kept indices (also an output)
+ * Other arguments as in the three calls above.
+ */
+int fastvar_step(const void* x, const int32_t* sched_h /* host */, const int32_t* sched_w /* host */,
+                 int K, int step, int cache_step, int B, int k,
+                 const fastvar_dims* dims /* host */, const fastvar_block_weights* weights /* host */,
+                 void* k_cache, void* v_cache, int32_t* kv_len /* host in/out */, int L_cap,
+                 const void* cache_map, void* y_out, int32_t* idx_out,
+                 void* ws, size_t ws_bytes, void* stream);
+
+/* ---- component entry points ----------------------------------------------
+ * The kernels of the block one at a time, with the same launch configuration
+ * fastvar_block_forward_pruned uses for the same shapes.  They exist so that
+ * each kernel can be checked against the oracle and timed on its own; the
+ * block (Sec. 3.3, implementation paragraph: an unchanged transformer layer on
+ * fewer tokens; Sec. 3.1 for the KV cache) is their composition.  Same
+ * conventions as above; no workspace is needed.
+ */
+
+/* out[m,:] = LayerNorm(in[row(m),:]) * gamma + beta for M = B*k rows, biased
+ * variance, fp32 statistics.  With idx != NULL row(m) = (m / k) * N + idx[m]
+ * (the gather of the kept tokens, appendix algorithm); else row(m) = m. */
+int fastvar_layernorm(const void* in, const int32_t* idx, int B, int N, int k, int D,
+                      const void* gamma, const void* beta, float eps, void* out, void* stream);
+
+/* out[M,N] = epilogue(A[M,K] * W[N,K]^T + bias); bf16 MFMA, fp32 accumulate.
+ * epilogue 1: + residual[M,N];  epilogue 2: exact-form GELU.  bias may be NULL;
+ * residual must be non-NULL for epilogue 1.  K % 64 == 0. */
+int fastvar_gemm_bf16(const void* A, const void* W, const void* bias, const void* residual,
+                      int M, int N, int K, int epilogue, void* out, void* stream);
+
+/* [q | k | v] = a[B*k, D] * w_qkv[3D, D]^T + b_qkv; q -> q_out [B*k, D]; k and
+ * v are appended to the caches at positions [L0, L0+k) (Sec. 3.3: only kept
+ * tokens enter the cache). */
+int fastvar_qkv_gemm(const void* a, const void* w_qkv, const void* b_qkv, int B, int k,
+                     const fastvar_dims* dims /* host */, void* q_out, void* k_cache, void* v_cache,
+                     int L0, int L_cap, void* stream);
+
+/* o[B*k, D] = softmax(q K^T * softmax_scale) V per head over cache positions
+ * [0, L), no mask (Sec. 3.1: queries of the current scale see the cached keys
+ * of every earlier scale and the current scale's own). */
+int fastvar_attention(const void* q, const void* k_cache, const void* v_cache, int B, int k,
+                      const fastvar_dims* dims /* host */, int L, int L_cap, void* o, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASTVAR_H */

@@ -160,7 +160,7 @@ def attention(q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: float) -> np.n
 def block_forward_pruned(xk: np.ndarray, W: Dict[str, np.ndarray], H: int,
                          k_cache: np.ndarray, v_cache: np.ndarray,
                          eps: float = 1e-6, scale: Optional[float] = None,
-                         return_parts: bool = False):
+                         return_parts: bool = False, rows: Optional[np.ndarray] = None):
     """One pre-LN block on kept tokens xk [B,k,D].
 
     k_cache / v_cache [B, L0, H, dh] hold the keys/values of all earlier
@@ -169,6 +169,11 @@ def block_forward_pruned(xk: np.ndarray, W: Dict[str, np.ndarray], H: int,
 
     Returns (yk [B,k,D], k_new [B,k,H,dh], v_new [B,k,H,dh]); with
     return_parts also the dict of intermediates (a1, q, o, h1, a2, u).
+
+    `rows` (positions inside the kept set, the same for every sample) limits
+    the outputs to those kept tokens: every kept token still contributes its
+    key and value, but queries, attention and the MLP are evaluated only for
+    the chosen rows, so single outputs of a large step can be checked.
     """
     xk = np.asarray(xk, F64)
     B, k, D = xk.shape
@@ -180,11 +185,16 @@ def block_forward_pruned(xk: np.ndarray, W: Dict[str, np.ndarray], H: int,
     q = qkv[..., 0 * D:1 * D].reshape(B, k, H, dh)
     kn = qkv[..., 1 * D:2 * D].reshape(B, k, H, dh)
     vn = qkv[..., 2 * D:3 * D].reshape(B, k, H, dh)
-    o = np.empty((B, k, D), dtype=F64)
+    if rows is not None:
+        rows = np.asarray(rows, dtype=np.int64)
+        q = q[:, rows]
+        xk = xk[:, rows]
+    kq = q.shape[1]
+    o = np.empty((B, kq, D), dtype=F64)
     for b in range(B):
         Kall = np.concatenate([np.asarray(k_cache[b], F64), kn[b]], axis=0)
         Vall = np.concatenate([np.asarray(v_cache[b], F64), vn[b]], axis=0)
-        o[b] = attention(q[b], Kall, Vall, scale).reshape(k, D)
+        o[b] = attention(q[b], Kall, Vall, scale).reshape(kq, D)
     h1 = xk + linear(o, W["w_proj"], W.get("b_proj"))
     a2 = layer_norm(h1, W["ln2_g"], W["ln2_b"], eps)
     u = gelu(linear(a2, W["w_fc1"], W.get("b_fc1")))

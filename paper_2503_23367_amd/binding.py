@@ -1,0 +1,229 @@
+"""ctypes binding of libfastvar.so: same names as the C ABI, argument
+marshalling only.  Tensors are torch CUDA tensors used purely as device
+buffers; kernels are enqueued on torch's current stream.
+
+There is no fallback: if the shared library is missing `lib()` raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libfastvar.so")
+
+FASTVAR_OK = 0
+FASTVAR_EINVAL = -1
+FASTVAR_ECAPACITY = -2
+FASTVAR_EWORKSPACE = -3
+FASTVAR_EALIGN = -4
+FASTVAR_EHIP = -5
+FASTVAR_MAX_TOKENS = 32768
+
+
+class FastvarError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+class Dims(C.Structure):
+    _fields_ = [("D", C.c_int32), ("H", C.c_int32), ("dh", C.c_int32), ("F", C.c_int32),
+                ("ln_eps", C.c_float), ("softmax_scale", C.c_float)]
+
+
+WEIGHT_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj",
+                 "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
+
+
+class BlockWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in WEIGHT_FIELDS]
+
+
+_lib = None
+
+EXPORTS = ("fastvar_version", "fastvar_strerror", "fastvar_keep_count",
+           "fastvar_select_workspace_bytes", "fastvar_block_workspace_bytes",
+           "fastvar_restore_workspace_bytes", "fastvar_step_workspace_bytes",
+           "fastvar_select_pivotal", "fastvar_block_forward_pruned", "fastvar_restore",
+           "fastvar_step", "fastvar_layernorm", "fastvar_gemm_bf16", "fastvar_qkv_gemm",
+           "fastvar_attention")
+
+
+def lib() -> C.CDLL:
+    """Load libfastvar.so (once) and declare the prototypes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} not found: build it with `python -m paper_2503_23367_amd.build` "
+            "(there is no CPU or PyTorch fallback)")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, sz = C.c_void_p, C.c_int, C.c_size_t
+    L.fastvar_version.restype = i32
+    L.fastvar_strerror.restype = C.c_char_p
+    L.fastvar_strerror.argtypes = [i32]
+    L.fastvar_keep_count.restype = i32
+    L.fastvar_keep_count.argtypes = [i32, C.c_double]
+    L.fastvar_select_workspace_bytes.restype = sz
+    L.fastvar_select_workspace_bytes.argtypes = [i32, i32, i32]
+    L.fastvar_block_workspace_bytes.restype = sz
+    L.fastvar_block_workspace_bytes.argtypes = [C.POINTER(Dims), i32, i32]
+    L.fastvar_restore_workspace_bytes.restype = sz
+    L.fastvar_restore_workspace_bytes.argtypes = [i32, i32]
+    L.fastvar_step_workspace_bytes.restype = sz
+    L.fastvar_step_workspace_bytes.argtypes = [C.POINTER(Dims), i32, i32, i32]
+    L.fastvar_select_pivotal.restype = i32
+    L.fastvar_select_pivotal.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp]
+    L.fastvar_block_forward_pruned.restype = i32
+    L.fastvar_block_forward_pruned.argtypes = [vp, i32, vp, i32, i32, C.POINTER(Dims),
+                                               C.POINTER(BlockWeights), vp, vp, i32, i32, vp, vp, sz, vp]
+    L.fastvar_restore.restype = i32
+    L.fastvar_restore.argtypes = [vp, vp, vp, i32, i32, vp, i32, i32, i32, i32, i32, vp, vp, sz, vp]
+    L.fastvar_step.restype = i32
+    L.fastvar_step.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), i32, i32, i32, i32, i32,
+                               C.POINTER(Dims), C.POINTER(BlockWeights), vp, vp, C.POINTER(C.c_int32), i32,
+                               vp, vp, vp, vp, sz, vp]
+    L.fastvar_layernorm.restype = i32
+    L.fastvar_layernorm.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, C.c_float, vp, vp]
+    L.fastvar_gemm_bf16.restype = i32
+    L.fastvar_gemm_bf16.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp, vp]
+    L.fastvar_qkv_gemm.restype = i32
+    L.fastvar_qkv_gemm.argtypes = [vp, vp, vp, i32, i32, C.POINTER(Dims), vp, vp, vp, i32, i32, vp]
+    L.fastvar_attention.restype = i32
+    L.fastvar_attention.argtypes = [vp, vp, vp, i32, i32, C.POINTER(Dims), i32, i32, vp, vp]
+    _lib = L
+    return L
+
+
+# ---------------------------------------------------------------------------
+# helpers
+# ---------------------------------------------------------------------------
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != FASTVAR_OK:
+        raise FastvarError(rc, where)
+
+
+def strerror(code: int) -> str:
+    return lib().fastvar_strerror(code).decode()
+
+
+def make_dims(D: int, H: int, dh: int, F: int, ln_eps: float = 1e-6,
+              softmax_scale: Optional[float] = None) -> Dims:
+    if softmax_scale is None:
+        softmax_scale = dh ** -0.5
+    return Dims(D, H, dh, F, ln_eps, softmax_scale)
+
+
+def make_weights(tensors: Dict[str, "object"]) -> BlockWeights:
+    """Struct of device pointers; keeps no reference, the caller keeps the tensors alive."""
+    w = BlockWeights()
+    for n in WEIGHT_FIELDS:
+        setattr(w, n, _ptr(tensors.get(n)))
+    return w
+
+
+# ---------------------------------------------------------------------------
+# the C ABI, name for name
+# ---------------------------------------------------------------------------
+
+def fastvar_version() -> int:
+    return lib().fastvar_version()
+
+
+def fastvar_keep_count(N: int, keep_ratio: float) -> int:
+    return lib().fastvar_keep_count(N, keep_ratio)
+
+
+def fastvar_select_workspace_bytes(B: int, N: int, D: int) -> int:
+    return lib().fastvar_select_workspace_bytes(B, N, D)
+
+
+def fastvar_block_workspace_bytes(dims: Dims, B: int, k: int) -> int:
+    return lib().fastvar_block_workspace_bytes(C.byref(dims), B, k)
+
+
+def fastvar_restore_workspace_bytes(B: int, N: int) -> int:
+    return lib().fastvar_restore_workspace_bytes(B, N)
+
+
+def fastvar_step_workspace_bytes(dims: Dims, B: int, N: int, k: int) -> int:
+    return lib().fastvar_step_workspace_bytes(C.byref(dims), B, N, k)
+
+
+def fastvar_select_pivotal(x, B, h, w, D, k, idx_out, rank_out, score_out, ws) -> None:
+    rc = lib().fastvar_select_pivotal(_ptr(x), B, h, w, D, k, _ptr(idx_out), _ptr(rank_out),
+                                      _ptr(score_out), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+                                      _stream())
+    _check(rc, "fastvar_select_pivotal")
+
+
+def fastvar_block_forward_pruned(x, N, idx, B, k, dims: Dims, weights: BlockWeights, k_cache, v_cache,
+                                 L0, L_cap, y_kept_out, ws) -> None:
+    rc = lib().fastvar_block_forward_pruned(_ptr(x), N, _ptr(idx), B, k, C.byref(dims), C.byref(weights),
+                                            _ptr(k_cache), _ptr(v_cache), L0, L_cap, _ptr(y_kept_out),
+                                            _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+                                            _stream())
+    _check(rc, "fastvar_block_forward_pruned")
+
+
+def fastvar_restore(y_kept, idx, rank, B, k, cache_map, hc, wc, h, w, D, y_out, ws=None) -> None:
+    rc = lib().fastvar_restore(_ptr(y_kept), _ptr(idx), _ptr(rank), B, k, _ptr(cache_map), hc, wc, h, w, D,
+                               _ptr(y_out), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+                               _stream())
+    _check(rc, "fastvar_restore")
+
+
+def fastvar_step(x, sched_h, sched_w, step, cache_step, B, k, dims: Dims, weights: BlockWeights,
+                 k_cache, v_cache, kv_len: int, L_cap, cache_map, y_out, idx_out, ws) -> int:
+    """Returns the new cache length."""
+    K = len(sched_h)
+    sh = (C.c_int32 * K)(*sched_h)
+    sw = (C.c_int32 * K)(*sched_w)
+    kv = C.c_int32(kv_len)
+    rc = lib().fastvar_step(_ptr(x), sh, sw, K, step, cache_step, B, k, C.byref(dims), C.byref(weights),
+                            _ptr(k_cache), _ptr(v_cache), C.byref(kv), L_cap, _ptr(cache_map), _ptr(y_out),
+                            _ptr(idx_out), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+                            _stream())
+    _check(rc, "fastvar_step")
+    return kv.value
+
+
+EPI_BIAS_RES = 1
+EPI_BIAS_GELU = 2
+
+
+def fastvar_layernorm(inp, idx, B, N, k, D, gamma, beta, eps, out) -> None:
+    rc = lib().fastvar_layernorm(_ptr(inp), _ptr(idx), B, N, k, D, _ptr(gamma), _ptr(beta), eps, _ptr(out),
+                                 _stream())
+    _check(rc, "fastvar_layernorm")
+
+
+def fastvar_gemm_bf16(A, W, bias, residual, M, N, K, epilogue, out) -> None:
+    rc = lib().fastvar_gemm_bf16(_ptr(A), _ptr(W), _ptr(bias), _ptr(residual), M, N, K, epilogue, _ptr(out),
+                                 _stream())
+    _check(rc, "fastvar_gemm_bf16")
+
+
+def fastvar_qkv_gemm(a, w_qkv, b_qkv, B, k, dims: Dims, q_out, k_cache, v_cache, L0, L_cap) -> None:
+    rc = lib().fastvar_qkv_gemm(_ptr(a), _ptr(w_qkv), _ptr(b_qkv), B, k, C.byref(dims), _ptr(q_out),
+                                _ptr(k_cache), _ptr(v_cache), L0, L_cap, _stream())
+    _check(rc, "fastvar_qkv_gemm")
+
+
+def fastvar_attention(q, k_cache, v_cache, B, k, dims: Dims, L, L_cap, o) -> None:
+    rc = lib().fastvar_attention(_ptr(q), _ptr(k_cache), _ptr(v_cache), B, k, C.byref(dims), L, L_cap,
+                                 _ptr(o), _stream())
+    _check(rc, "fastvar_attention")

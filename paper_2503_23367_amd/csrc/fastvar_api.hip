@@ -1,0 +1,356 @@
+// C-ABI layer: argument validation, workspace carving and launch order.
+// Everything that computes runs in the kernels; this file only checks,
+// slices the caller's scratch buffer and enqueues.
+#include "../../include/fastvar.h"
+
+#include <hip/hip_runtime.h>
+#include <math.h>
+
+#include "kernels.h"
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+constexpr int kMaxWidth = 8192;  // LayerNorm keeps a row in registers; score keeps the mean in 64 KB of LDS
+
+struct BlockPlan {
+    size_t off_a, off_q, off_h1, off_u, bytes;
+};
+
+BlockPlan block_plan(const fastvar_dims* d, int B, int k) {
+    const size_t M = (size_t)B * (size_t)k;
+    BlockPlan p;
+    size_t off = 0;
+    p.off_a = off;   off += round256(M * d->D * 2);  // LN1 output, later the attention output
+    p.off_q = off;   off += round256(M * d->D * 2);  // queries, later the LN2 output
+    p.off_h1 = off;  off += round256(M * d->D * 2);  // residual stream after attention
+    p.off_u = off;   off += round256(M * d->F * 2);  // MLP hidden
+    p.bytes = off;
+    return p;
+}
+
+int check_dims(const fastvar_dims* d) {
+    if (!d) return FASTVAR_EINVAL;
+    if (d->D <= 0 || d->H <= 0 || d->dh <= 0 || d->F <= 0) return FASTVAR_EINVAL;
+    if ((long)d->H * d->dh != d->D) return FASTVAR_EINVAL;
+    if (!(d->ln_eps >= 0.f) || !(d->softmax_scale > 0.f) || !isfinite(d->softmax_scale)) return FASTVAR_EINVAL;
+    if (d->D % 64 != 0 || d->F % 64 != 0) return FASTVAR_EALIGN;
+    if (d->dh != 64 && d->dh != 128) return FASTVAR_EALIGN;
+    if (d->D > kMaxWidth) return FASTVAR_ECAPACITY;
+    return FASTVAR_OK;
+}
+
+int check_weights(const fastvar_block_weights* w) {
+    if (!w) return FASTVAR_EINVAL;
+    const void* need[] = {w->ln1_g, w->ln1_b, w->w_qkv, w->w_proj, w->ln2_g, w->ln2_b, w->w_fc1, w->w_fc2};
+    for (const void* p : need) {
+        if (!p) return FASTVAR_EINVAL;
+        if (!aligned16(p)) return FASTVAR_EALIGN;
+    }
+    const void* opt[] = {w->b_qkv, w->b_proj, w->b_fc1, w->b_fc2};
+    for (const void* p : opt)
+        if (p && !aligned16(p)) return FASTVAR_EALIGN;
+    return FASTVAR_OK;
+}
+
+int check_select(const void* x, int B, int h, int w, int D, int k, const int32_t* idx, const void* ws,
+                 size_t ws_bytes) {
+    if (!x || B <= 0 || h <= 0 || w <= 0 || D <= 0) return FASTVAR_EINVAL;
+    const long N = (long)h * w;
+    if (k < 0 || k > N) return FASTVAR_EINVAL;
+    if (k > 0 && !idx) return FASTVAR_EINVAL;
+    if (N > FASTVAR_MAX_TOKENS || D > kMaxWidth) return FASTVAR_ECAPACITY;
+    if ((double)B * (double)N * (double)D >= 2147483648.0 * 4.0) return FASTVAR_ECAPACITY;
+    if (D % 8 != 0 || !aligned16(x) || (ws && !aligned16(ws))) return FASTVAR_EALIGN;
+    if (!ws || ws_bytes < fastvar_select_workspace_bytes(B, (int)N, D)) return FASTVAR_EWORKSPACE;
+    return FASTVAR_OK;
+}
+
+int check_block(const void* x, int N, const int32_t* idx, int B, int k, const fastvar_dims* dims,
+                const fastvar_block_weights* wts, const void* kc, const void* vc, int L0, int L_cap,
+                const void* y, const void* ws, size_t ws_bytes) {
+    int rc = check_dims(dims);
+    if (rc) return rc;
+    rc = check_weights(wts);
+    if (rc) return rc;
+    if (!x || !kc || !vc || B <= 0 || N <= 0 || k < 0 || k > N || L0 < 0 || L_cap <= 0) return FASTVAR_EINVAL;
+    if (k > 0 && (!idx || !y)) return FASTVAR_EINVAL;
+    if ((long)L0 + k > L_cap) return FASTVAR_ECAPACITY;
+    if (L_cap % 8 != 0) return FASTVAR_EALIGN;
+    if (!aligned16(x) || !aligned16(kc) || !aligned16(vc) || (y && !aligned16(y)) || (ws && !aligned16(ws)))
+        return FASTVAR_EALIGN;
+    // 32-bit element offsets inside the GEMM operand loads
+    const double M = (double)B * k;
+    const double widest = dims->F > 3 * dims->D ? dims->F : 3 * dims->D;
+    if (M * widest >= 2147483648.0 || (double)widest * dims->F >= 2147483648.0) return FASTVAR_ECAPACITY;
+    if (k > 0 && (!ws || ws_bytes < fastvar_block_workspace_bytes(dims, B, k))) return FASTVAR_EWORKSPACE;
+    return FASTVAR_OK;
+}
+
+int check_restore(const void* y_kept, const int32_t* idx, const int32_t* rank, int B, int k, const void* cache,
+                  int hc, int wc, int h, int w, int D, const void* y_out, const void* ws, size_t ws_bytes) {
+    if (!cache || !y_out || B <= 0 || hc <= 0 || wc <= 0 || h <= 0 || w <= 0 || D <= 0) return FASTVAR_EINVAL;
+    const long N = (long)h * w;
+    if (k < 0 || k > N) return FASTVAR_EINVAL;
+    if (k > 0 && (!y_kept || (!rank && !idx))) return FASTVAR_EINVAL;
+    if (y_out == cache || (k > 0 && y_out == y_kept)) return FASTVAR_EINVAL;
+    if (N > FASTVAR_MAX_TOKENS) return FASTVAR_ECAPACITY;
+    if (D % 8 != 0 || !aligned16(cache) || !aligned16(y_out) || (y_kept && !aligned16(y_kept)))
+        return FASTVAR_EALIGN;
+    if (k > 0 && !rank) {
+        if (!ws || ws_bytes < fastvar_restore_workspace_bytes(B, (int)N)) return FASTVAR_EWORKSPACE;
+        if (!aligned16(ws)) return FASTVAR_EALIGN;
+    }
+    return FASTVAR_OK;
+}
+
+int launch_status() { return hipGetLastError() == hipSuccess ? FASTVAR_OK : FASTVAR_EHIP; }
+
+void enqueue_block(const void* x, int N, const int32_t* idx, int B, int k, const fastvar_dims* d,
+                   const fastvar_block_weights* w, void* kc, void* vc, int L0, int L_cap, void* y, void* ws,
+                   hipStream_t st) {
+    const BlockPlan bp = block_plan(d, B, k);
+    char* base = static_cast<char*>(ws);
+    void* buf_a = base + bp.off_a;
+    void* buf_q = base + bp.off_q;
+    void* buf_h1 = base + bp.off_h1;
+    void* buf_u = base + bp.off_u;
+    const int M = B * k;
+
+    // a1 = LN1(x[idx])
+    fv::launch_gather_layernorm(x, idx, B, N, k, d->D, w->ln1_g, w->ln1_b, d->ln_eps, nullptr, buf_a, st);
+    // q | k | v = a1 * Wqkv^T + b ; k, v appended to the caches at [L0, L0+k)
+    fv::GemmArgs g{};
+    g.A = buf_a; g.W = w->w_qkv; g.bias = w->b_qkv; g.M = M; g.N = 3 * d->D; g.K = d->D;
+    g.q_out = buf_q; g.k_cache = kc; g.v_cache = vc;
+    g.D = d->D; g.H = d->H; g.dh = d->dh; g.k_tokens = k; g.L0 = L0; g.L_cap = L_cap;
+    fv::launch_gemm(fv::EPI_QKV, g, st);
+    // o = softmax(q K^T * scale) V over cache positions [0, L0+k)
+    fv::AttnArgs at{};
+    at.q = buf_q; at.k_cache = kc; at.v_cache = vc; at.o = buf_a;
+    at.B = B; at.H = d->H; at.dh = d->dh; at.k_tokens = k; at.L = L0 + k; at.L_cap = L_cap;
+    at.scale = d->softmax_scale;
+    fv::launch_attention(at, st);
+    // h1 = x[idx] + o * Wp^T + bp
+    fv::GemmArgs pj{};
+    pj.A = buf_a; pj.W = w->w_proj; pj.bias = w->b_proj; pj.M = M; pj.N = d->D; pj.K = d->D;
+    pj.out = buf_h1; pj.residual = x; pj.res_idx = idx; pj.res_N = N; pj.k_tokens = k;
+    fv::launch_gemm(fv::EPI_BIAS_RES, pj, st);
+    // a2 = LN2(h1)
+    fv::launch_layernorm(buf_h1, M, d->D, w->ln2_g, w->ln2_b, d->ln_eps, buf_q, st);
+    // u = gelu(a2 * W1^T + b1)
+    fv::GemmArgs f1{};
+    f1.A = buf_q; f1.W = w->w_fc1; f1.bias = w->b_fc1; f1.M = M; f1.N = d->F; f1.K = d->D;
+    f1.out = buf_u; f1.k_tokens = k;
+    fv::launch_gemm(fv::EPI_BIAS_GELU, f1, st);
+    // y = h1 + u * W2^T + b2
+    fv::GemmArgs f2{};
+    f2.A = buf_u; f2.W = w->w_fc2; f2.bias = w->b_fc2; f2.M = M; f2.N = d->D; f2.K = d->F;
+    f2.out = y; f2.residual = buf_h1; f2.k_tokens = k;
+    fv::launch_gemm(fv::EPI_BIAS_RES, f2, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+int fastvar_version(void) { return FASTVAR_VERSION; }
+
+const char* fastvar_strerror(int code) {
+    switch (code) {
+        case FASTVAR_OK: return "ok";
+        case FASTVAR_EINVAL: return "invalid argument";
+        case FASTVAR_ECAPACITY: return "capacity exceeded";
+        case FASTVAR_EWORKSPACE: return "workspace too small";
+        case FASTVAR_EALIGN: return "misaligned pointer or unsupported width";
+        case FASTVAR_EHIP: return "HIP launch failed";
+        default: return "unknown error";
+    }
+}
+
+int fastvar_keep_count(int N, double keep_ratio) {
+    if (N < 0) return FASTVAR_EINVAL;
+    if (!(keep_ratio > 0.0)) return 0;
+    const double v = floor(keep_ratio * (double)N + 0.5);
+    if (v >= (double)N) return N;
+    return (int)v;
+}
+
+size_t fastvar_select_workspace_bytes(int B, int N, int D) {
+    if (B <= 0 || N <= 0 || D <= 0) return 0;
+    return fv::select_plan(B, N, D).bytes;
+}
+
+size_t fastvar_block_workspace_bytes(const fastvar_dims* dims, int B, int k) {
+    if (!dims || B <= 0 || k <= 0 || dims->D <= 0 || dims->F <= 0) return 0;
+    return block_plan(dims, B, k).bytes;
+}
+
+size_t fastvar_restore_workspace_bytes(int B, int N) {
+    if (B <= 0 || N <= 0) return 0;
+    return round256((size_t)B * N * sizeof(int32_t));
+}
+
+size_t fastvar_step_workspace_bytes(const fastvar_dims* dims, int B, int N, int k) {
+    if (!dims || B <= 0 || N <= 0) return 0;
+    return fastvar_select_workspace_bytes(B, N, dims->D) + fastvar_restore_workspace_bytes(B, N) +
+           fastvar_block_workspace_bytes(dims, B, k);
+}
+
+int fastvar_select_pivotal(const void* x, int B, int h, int w, int D, int k, int32_t* idx_out,
+                           int32_t* rank_out, float* score_out, void* ws, size_t ws_bytes, void* stream) {
+    const int rc = check_select(x, B, h, w, D, k, idx_out, ws, ws_bytes);
+    if (rc) return rc;
+    const int N = h * w;
+    const fv::SelectPlan plan = fv::select_plan(B, N, D);
+    fv::launch_select(x, B, N, D, k, idx_out, rank_out, score_out, ws, plan, static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+int fastvar_block_forward_pruned(const void* x, int N, const int32_t* idx, int B, int k,
+                                 const fastvar_dims* dims, const fastvar_block_weights* weights, void* k_cache,
+                                 void* v_cache, int L0, int L_cap, void* y_kept_out, void* ws, size_t ws_bytes,
+                                 void* stream) {
+    const int rc = check_block(x, N, idx, B, k, dims, weights, k_cache, v_cache, L0, L_cap, y_kept_out, ws,
+                               ws_bytes);
+    if (rc) return rc;
+    if (k == 0) return FASTVAR_OK;
+    enqueue_block(x, N, idx, B, k, dims, weights, k_cache, v_cache, L0, L_cap, y_kept_out, ws,
+                  static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+int fastvar_restore(const void* y_kept, const int32_t* idx, const int32_t* rank, int B, int k,
+                    const void* cache_map, int hc, int wc, int h, int w, int D, void* y_out, void* ws,
+                    size_t ws_bytes, void* stream) {
+    const int rc = check_restore(y_kept, idx, rank, B, k, cache_map, hc, wc, h, w, D, y_out, ws, ws_bytes);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int N = h * w;
+    if (k > 0 && !rank) {
+        int32_t* rebuilt = static_cast<int32_t*>(ws);
+        fv::launch_rank_from_idx(idx, rebuilt, B, N, k, st);
+        rank = rebuilt;
+    }
+    fv::launch_restore(y_kept, rank, B, k, cache_map, hc, wc, h, w, D, y_out, st);
+    return launch_status();
+}
+
+int fastvar_step(const void* x, const int32_t* sched_h, const int32_t* sched_w, int K, int step, int cache_step,
+                 int B, int k, const fastvar_dims* dims, const fastvar_block_weights* weights, void* k_cache,
+                 void* v_cache, int32_t* kv_len, int L_cap, const void* cache_map, void* y_out,
+                 int32_t* idx_out, void* ws, size_t ws_bytes, void* stream) {
+    if (!sched_h || !sched_w || !kv_len || K <= 0) return FASTVAR_EINVAL;
+    if (step < 0 || step >= K || cache_step < 0 || cache_step >= step) return FASTVAR_EINVAL;
+    const int h = sched_h[step], w = sched_w[step];
+    const int hc = sched_h[cache_step], wc = sched_w[cache_step];
+    if (h <= 0 || w <= 0 || hc <= 0 || wc <= 0 || (long)h * w > FASTVAR_MAX_TOKENS) return FASTVAR_EINVAL;
+    const int N = h * w;
+    const int L0 = *kv_len;
+    int rc = check_dims(dims);
+    if (rc) return rc;
+    const int D = dims->D;
+    if (B <= 0 || k < 0 || k > N || y_out == x) return FASTVAR_EINVAL;
+    if (!ws) return FASTVAR_EWORKSPACE;
+    if (!aligned16(ws)) return FASTVAR_EALIGN;
+    if (ws_bytes < fastvar_step_workspace_bytes(dims, B, N, k)) return FASTVAR_EWORKSPACE;
+
+    // scratch: [selection | rank [B,N] | block buffers]
+    const size_t sel_bytes = fastvar_select_workspace_bytes(B, N, D);
+    const size_t rank_bytes = fastvar_restore_workspace_bytes(B, N);
+    char* base = static_cast<char*>(ws);
+    void* ws_sel = base;
+    int32_t* rank = reinterpret_cast<int32_t*>(base + sel_bytes);
+    char* ws_blk = base + sel_bytes + rank_bytes;
+    const size_t blk_bytes = ws_bytes - sel_bytes - rank_bytes;
+    // The kept outputs go to the block's query buffer: it is last read by FC1
+    // (as the LN2 output), before FC2 writes the block output.
+    void* yk = k > 0 ? static_cast<void*>(ws_blk + block_plan(dims, B, k).off_q) : nullptr;
+
+    rc = check_select(x, B, h, w, D, k, idx_out, ws_sel, sel_bytes);
+    if (rc) return rc;
+    rc = check_block(x, N, idx_out, B, k, dims, weights, k_cache, v_cache, L0, L_cap, yk, ws_blk, blk_bytes);
+    if (rc) return rc;
+    rc = check_restore(yk, idx_out, rank, B, k, cache_map, hc, wc, h, w, D, y_out, nullptr, 0);
+    if (rc) return rc;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    fv::launch_select(x, B, N, D, k, idx_out, rank, nullptr, ws_sel, fv::select_plan(B, N, D), st);
+    if (k > 0)
+        enqueue_block(x, N, idx_out, B, k, dims, weights, k_cache, v_cache, L0, L_cap, yk, ws_blk, st);
+    fv::launch_restore(yk, rank, B, k, cache_map, hc, wc, h, w, D, y_out, st);
+    rc = launch_status();
+    if (rc == FASTVAR_OK) *kv_len = L0 + k;
+    return rc;
+}
+
+int fastvar_layernorm(const void* in, const int32_t* idx, int B, int N, int k, int D, const void* gamma,
+                      const void* beta, float eps, void* out, void* stream) {
+    if (!in || !gamma || !beta || !out || B <= 0 || k <= 0 || D <= 0 || !(eps >= 0.f)) return FASTVAR_EINVAL;
+    if (idx && N <= 0) return FASTVAR_EINVAL;
+    if (D > kMaxWidth) return FASTVAR_ECAPACITY;
+    if (D % 8 != 0 || !aligned16(in) || !aligned16(gamma) || !aligned16(beta) || !aligned16(out))
+        return FASTVAR_EALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (idx)
+        fv::launch_gather_layernorm(in, idx, B, N, k, D, gamma, beta, eps, nullptr, out, st);
+    else
+        fv::launch_layernorm(in, B * k, D, gamma, beta, eps, out, st);
+    return launch_status();
+}
+
+int fastvar_gemm_bf16(const void* A, const void* W, const void* bias, const void* residual, int M, int N, int K,
+                      int epilogue, void* out, void* stream) {
+    if (!A || !W || !out || M <= 0 || N <= 0 || K <= 0) return FASTVAR_EINVAL;
+    if (epilogue != fv::EPI_BIAS_RES && epilogue != fv::EPI_BIAS_GELU) return FASTVAR_EINVAL;
+    if (epilogue == fv::EPI_BIAS_RES && !residual) return FASTVAR_EINVAL;
+    if (K % 64 != 0 || N % 8 != 0 || !aligned16(A) || !aligned16(W) || !aligned16(out) ||
+        (bias && !aligned16(bias)) || (residual && !aligned16(residual)))
+        return FASTVAR_EALIGN;
+    if ((double)M * K >= 2147483648.0 || (double)N * K >= 2147483648.0 || (double)M * N >= 2147483648.0)
+        return FASTVAR_ECAPACITY;
+    fv::GemmArgs g{};
+    g.A = A; g.W = W; g.bias = bias; g.M = M; g.N = N; g.K = K;
+    g.out = out; g.residual = residual; g.k_tokens = M;
+    fv::launch_gemm(static_cast<fv::GemmEpilogue>(epilogue), g, static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+int fastvar_qkv_gemm(const void* a, const void* w_qkv, const void* b_qkv, int B, int k, const fastvar_dims* dims,
+                     void* q_out, void* k_cache, void* v_cache, int L0, int L_cap, void* stream) {
+    const int rc = check_dims(dims);
+    if (rc) return rc;
+    if (!a || !w_qkv || !q_out || !k_cache || !v_cache || B <= 0 || k <= 0 || L0 < 0 || L_cap <= 0)
+        return FASTVAR_EINVAL;
+    if ((long)L0 + k > L_cap) return FASTVAR_ECAPACITY;
+    if (L_cap % 8 != 0 || !aligned16(a) || !aligned16(w_qkv) || !aligned16(q_out) || !aligned16(k_cache) ||
+        !aligned16(v_cache) || (b_qkv && !aligned16(b_qkv)))
+        return FASTVAR_EALIGN;
+    if ((double)B * k * 3.0 * dims->D >= 2147483648.0) return FASTVAR_ECAPACITY;
+    fv::GemmArgs g{};
+    g.A = a; g.W = w_qkv; g.bias = b_qkv; g.M = B * k; g.N = 3 * dims->D; g.K = dims->D;
+    g.q_out = q_out; g.k_cache = k_cache; g.v_cache = v_cache;
+    g.D = dims->D; g.H = dims->H; g.dh = dims->dh; g.k_tokens = k; g.L0 = L0; g.L_cap = L_cap;
+    fv::launch_gemm(fv::EPI_QKV, g, static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+int fastvar_attention(const void* q, const void* k_cache, const void* v_cache, int B, int k,
+                      const fastvar_dims* dims, int L, int L_cap, void* o, void* stream) {
+    const int rc = check_dims(dims);
+    if (rc) return rc;
+    if (!q || !k_cache || !v_cache || !o || B <= 0 || k <= 0 || L <= 0 || L_cap <= 0) return FASTVAR_EINVAL;
+    if (L > L_cap) return FASTVAR_ECAPACITY;
+    if (L_cap % 8 != 0 || !aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(o))
+        return FASTVAR_EALIGN;
+    fv::AttnArgs at{};
+    at.q = q; at.k_cache = k_cache; at.v_cache = v_cache; at.o = o;
+    at.B = B; at.H = dims->H; at.dh = dims->dh; at.k_tokens = k; at.L = L; at.L_cap = L_cap;
+    at.scale = dims->softmax_scale;
+    fv::launch_attention(at, static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+}  // extern "C"

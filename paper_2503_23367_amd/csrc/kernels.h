@@ -1,0 +1,73 @@
+// Host-side launchers of the gfx950 kernels (internal to the library).
+// Every launcher enqueues on `stream` and returns; shapes are validated by the
+// C-ABI layer before any launcher is called.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace fv {
+
+// ---- selection (Sec. 3.3, Eq. 4-5) ----
+struct SelectPlan {
+    int col_tiles;     // column tiles of 512
+    int n_chunks;      // row chunks of the column-sum pass
+    int rows_per_chunk;
+    size_t off_partial;  // fp64 [B, n_chunks, D]
+    size_t off_mean;     // fp64 [B, D]
+    size_t off_score;    // fp32 [B, N]
+    size_t bytes;
+};
+SelectPlan select_plan(int B, int N, int D);
+void launch_select(const void* x, int B, int N, int D, int k, int32_t* idx, int32_t* rank,
+                   float* score_out, void* ws, const SelectPlan& plan, hipStream_t stream);
+
+// ---- restoration (Sec. 3.3, Eq. 6) ----
+void launch_rank_from_idx(const int32_t* idx, int32_t* rank, int B, int N, int k, hipStream_t stream);
+void launch_restore(const void* y_kept, const int32_t* rank, int B, int k, const void* cache_map,
+                    int hc, int wc, int h, int w, int D, void* y_out, hipStream_t stream);
+
+// ---- block pieces ----
+// xk = x[idx] (optional copy out) and a = LayerNorm(xk); one wave per row.
+void launch_gather_layernorm(const void* x, const int32_t* idx, int B, int N, int k, int D,
+                             const void* gamma, const void* beta, float eps, void* xk_out,
+                             void* a_out, hipStream_t stream);
+// a = LayerNorm(rows of `in`), M rows.
+void launch_layernorm(const void* in, int M, int D, const void* gamma, const void* beta, float eps,
+                      void* a_out, hipStream_t stream);
+
+enum GemmEpilogue {
+    EPI_QKV = 0,       // +bias; q -> q_out [M, D]; k, v -> caches at positions L0 + t
+    EPI_BIAS_RES = 1,  // out = acc + bias + residual
+    EPI_BIAS_GELU = 2  // out = gelu(acc + bias)
+};
+struct GemmArgs {
+    const void* A;     // [M, K] bf16
+    const void* W;     // [N, K] bf16
+    const void* bias;  // [N] bf16 or null
+    int M, N, K;
+    // EPI_BIAS_RES / EPI_BIAS_GELU
+    void* out;             // [M, N] bf16
+    const void* residual;  // [M, N] bf16 (EPI_BIAS_RES), or the gather source when res_idx is set
+    const int32_t* res_idx = nullptr;  // optional: residual row of m is (m / k_tokens) * res_N + res_idx[m]
+    int res_N = 0;
+    // EPI_QKV
+    void* q_out;    // [M, D]
+    void* k_cache;  // [B, H, L_cap, dh]
+    void* v_cache;  // [B, H, dh, L_cap]
+    int D, H, dh, k_tokens, L0, L_cap;
+};
+void launch_gemm(GemmEpilogue epi, const GemmArgs& a, hipStream_t stream);
+
+struct AttnArgs {
+    const void* q;        // [B*k, D] bf16 (feature = head*dh + d)
+    const void* k_cache;  // [B, H, L_cap, dh]
+    const void* v_cache;  // [B, H, dh, L_cap]
+    void* o;              // [B*k, D] bf16
+    int B, H, dh, k_tokens, L, L_cap;
+    float scale;
+};
+void launch_attention(const AttnArgs& a, hipStream_t stream);
+
+}  // namespace fv

@@ -1,0 +1,113 @@
+// Gather of the kept tokens fused with the block's first LayerNorm, and the
+// plain LayerNorm before the MLP.  One wave per token row; the row is held in
+// registers (two-pass mean / biased variance in fp32); 16-byte loads and stores.
+// HBM bound: reads k*D bf16, writes k*D bf16.
+#include "common.h"
+#include "kernels.h"
+
+namespace fv {
+
+namespace {
+
+__device__ __forceinline__ void unpack8(const uint4& v, float (&f)[8]) {
+    f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x);
+    f[2] = bf16_lo(v.y); f[3] = bf16_hi(v.y);
+    f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z);
+    f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
+}
+
+// CH = number of 512-column groups held in registers (D <= 512*CH).
+// Row m of the output reads input row (idx ? b*N + idx[m] : m), b = m / k.
+template <int CH>
+__global__ __launch_bounds__(256) void layernorm_rows_kernel(const bf16_t* __restrict__ in,
+                                                             const int32_t* __restrict__ idx, int N, int k,
+                                                             int M, int D, const bf16_t* __restrict__ gamma,
+                                                             const bf16_t* __restrict__ beta, float eps,
+                                                             bf16_t* __restrict__ copy_out,
+                                                             bf16_t* __restrict__ out) {
+    const int lane = threadIdx.x & 63;
+    const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (m >= M) return;
+    size_t src_row = (size_t)m;
+    if (idx) src_row = (size_t)(m / k) * N + idx[m];
+    const bf16_t* src = in + src_row * D;
+
+    float v[CH][8];
+    float sum = 0.f;
+#pragma unroll
+    for (int g = 0; g < CH; ++g) {
+        const int col = g * 512 + lane * 8;
+        if (col < D) {
+            const uint4 raw = *reinterpret_cast<const uint4*>(src + col);
+            if (copy_out) *reinterpret_cast<uint4*>(copy_out + (size_t)m * D + col) = raw;
+            unpack8(raw, v[g]);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) sum += v[g][j];
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[g][j] = 0.f;
+        }
+    }
+    const float mean = wave_sum(sum) / (float)D;
+    float sq = 0.f;
+#pragma unroll
+    for (int g = 0; g < CH; ++g) {
+        const int col = g * 512 + lane * 8;
+        if (col < D) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float d = v[g][j] - mean;
+                sq = fmaf(d, d, sq);
+            }
+        }
+    }
+    const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)D + eps);
+#pragma unroll
+    for (int g = 0; g < CH; ++g) {
+        const int col = g * 512 + lane * 8;
+        if (col < D) {
+            float gm[8], bt[8];
+            unpack8(*reinterpret_cast<const uint4*>(gamma + col), gm);
+            unpack8(*reinterpret_cast<const uint4*>(beta + col), bt);
+            float o[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) o[j] = (v[g][j] - mean) * rstd * gm[j] + bt[j];
+            uint4 pk;
+            pk.x = pack_bf16x2(o[0], o[1]);
+            pk.y = pack_bf16x2(o[2], o[3]);
+            pk.z = pack_bf16x2(o[4], o[5]);
+            pk.w = pack_bf16x2(o[6], o[7]);
+            *reinterpret_cast<uint4*>(out + (size_t)m * D + col) = pk;
+        }
+    }
+}
+
+void dispatch(const void* in, const int32_t* idx, int N, int k, int M, int D, const void* gamma,
+              const void* beta, float eps, void* copy_out, void* out, hipStream_t stream) {
+    const dim3 grid((M + 3) / 4), block(256);
+    const int ch = (D + 511) / 512;
+#define FV_LN_CASE(CHV)                                                                                  \
+    layernorm_rows_kernel<CHV><<<grid, block, 0, stream>>>(                                              \
+        static_cast<const bf16_t*>(in), idx, N, k, M, D, static_cast<const bf16_t*>(gamma),              \
+        static_cast<const bf16_t*>(beta), eps, static_cast<bf16_t*>(copy_out), static_cast<bf16_t*>(out))
+    if (ch <= 1) FV_LN_CASE(1);
+    else if (ch <= 2) FV_LN_CASE(2);
+    else if (ch <= 4) FV_LN_CASE(4);
+    else if (ch <= 8) FV_LN_CASE(8);
+    else FV_LN_CASE(16);  // D <= 8192, checked by the caller
+#undef FV_LN_CASE
+}
+
+}  // namespace
+
+void launch_gather_layernorm(const void* x, const int32_t* idx, int B, int N, int k, int D, const void* gamma,
+                             const void* beta, float eps, void* xk_out, void* a_out, hipStream_t stream) {
+    dispatch(x, idx, N, k, B * k, D, gamma, beta, eps, xk_out, a_out, stream);
+}
+
+void launch_layernorm(const void* in, int M, int D, const void* gamma, const void* beta, float eps, void* a_out,
+                      hipStream_t stream) {
+    dispatch(in, nullptr, 0, 1, M, D, gamma, beta, eps, nullptr, a_out, stream);
+}
+
+}  // namespace fv

@@ -1,0 +1,118 @@
+// Cached Token Restoration (FastVAR Sec. 3.3, Eq. 6 and the scatter that
+// follows it): every slot of the restored map is either the kept token's block
+// output (a row copy) or the cached previous-scale map resampled bilinearly at
+// half-pixel centres.  One pass over the output, one wave per token row,
+// 16-byte loads and stores; HBM bound (writes N*D bf16 once).
+#include "common.h"
+#include "kernels.h"
+
+namespace fv {
+
+namespace {
+
+// rank[b,n] = position of n in the ascending idx[b,:], or -1.  Binary search,
+// so no ordering between a fill and a scatter is needed.
+__global__ __launch_bounds__(256) void rank_from_idx_kernel(const int32_t* __restrict__ idx,
+                                                            int32_t* __restrict__ rank, int N, int k) {
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    const int b = blockIdx.y;
+    if (n >= N) return;
+    const int32_t* row = idx + (size_t)b * k;
+    int lo = 0, hi = k;  // first position with row[pos] >= n
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (row[mid] < n) lo = mid + 1; else hi = mid;
+    }
+    rank[(size_t)b * N + n] = (lo < k && row[lo] == n) ? lo : -1;
+}
+
+// Source taps of one axis for output position d (half-pixel centres, clamped).
+__device__ __forceinline__ void axis_taps(int d, int n_in, int n_out, int& i0, int& i1, float& lam) {
+    double src = ((double)d + 0.5) * ((double)n_in / (double)n_out) - 0.5;
+    src = fmin(fmax(src, 0.0), (double)(n_in - 1));
+    const double f = floor(src);
+    i0 = (int)f;
+    i1 = min(i0 + 1, n_in - 1);
+    lam = (float)(src - f);
+}
+
+__device__ __forceinline__ float lerp2(float c00, float c01, float c10, float c11, float lr, float lc) {
+    const float top = c00 + lc * (c01 - c00);
+    const float bot = c10 + lc * (c11 - c10);
+    return top + lr * (bot - top);
+}
+
+constexpr int kRowsPerWave = 2;
+
+// grid (ceil(N / (4*kRowsPerWave)), B), block 256.
+__global__ __launch_bounds__(256) void restore_kernel(const bf16_t* __restrict__ y_kept,
+                                                      const int32_t* __restrict__ rank, int k,
+                                                      const bf16_t* __restrict__ cache_map, int hc, int wc,
+                                                      int h, int w, int D, bf16_t* __restrict__ y_out) {
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int b = blockIdx.y;
+    const int N = h * w;
+    const int groups = (D + 511) >> 9;
+#pragma unroll
+    for (int rr = 0; rr < kRowsPerWave; ++rr) {
+        const int n = (blockIdx.x * 4 + wave) * kRowsPerWave + rr;
+        if (n >= N) break;
+        const int r = (k > 0) ? rank[(size_t)b * N + n] : -1;
+        bf16_t* dst = y_out + ((size_t)b * N + n) * D;
+        if (r >= 0) {
+            const bf16_t* src = y_kept + ((size_t)b * k + r) * D;
+            for (int g = 0; g < groups; ++g) {
+                const int col = g * 512 + lane * 8;
+                if (col < D)
+                    *reinterpret_cast<uint4*>(dst + col) = *reinterpret_cast<const uint4*>(src + col);
+            }
+        } else {
+            int i0, i1, j0, j1;
+            float lr, lc;
+            axis_taps(n / w, hc, h, i0, i1, lr);
+            axis_taps(n % w, wc, w, j0, j1, lc);
+            const bf16_t* cb = cache_map + (size_t)b * hc * wc * D;
+            const bf16_t* p00 = cb + ((size_t)i0 * wc + j0) * D;
+            const bf16_t* p01 = cb + ((size_t)i0 * wc + j1) * D;
+            const bf16_t* p10 = cb + ((size_t)i1 * wc + j0) * D;
+            const bf16_t* p11 = cb + ((size_t)i1 * wc + j1) * D;
+            for (int g = 0; g < groups; ++g) {
+                const int col = g * 512 + lane * 8;
+                if (col < D) {
+                    const uint4 a = *reinterpret_cast<const uint4*>(p00 + col);
+                    const uint4 bq = *reinterpret_cast<const uint4*>(p01 + col);
+                    const uint4 c = *reinterpret_cast<const uint4*>(p10 + col);
+                    const uint4 d = *reinterpret_cast<const uint4*>(p11 + col);
+                    uint4 o;
+                    o.x = pack_bf16x2(lerp2(bf16_lo(a.x), bf16_lo(bq.x), bf16_lo(c.x), bf16_lo(d.x), lr, lc),
+                                      lerp2(bf16_hi(a.x), bf16_hi(bq.x), bf16_hi(c.x), bf16_hi(d.x), lr, lc));
+                    o.y = pack_bf16x2(lerp2(bf16_lo(a.y), bf16_lo(bq.y), bf16_lo(c.y), bf16_lo(d.y), lr, lc),
+                                      lerp2(bf16_hi(a.y), bf16_hi(bq.y), bf16_hi(c.y), bf16_hi(d.y), lr, lc));
+                    o.z = pack_bf16x2(lerp2(bf16_lo(a.z), bf16_lo(bq.z), bf16_lo(c.z), bf16_lo(d.z), lr, lc),
+                                      lerp2(bf16_hi(a.z), bf16_hi(bq.z), bf16_hi(c.z), bf16_hi(d.z), lr, lc));
+                    o.w = pack_bf16x2(lerp2(bf16_lo(a.w), bf16_lo(bq.w), bf16_lo(c.w), bf16_lo(d.w), lr, lc),
+                                      lerp2(bf16_hi(a.w), bf16_hi(bq.w), bf16_hi(c.w), bf16_hi(d.w), lr, lc));
+                    *reinterpret_cast<uint4*>(dst + col) = o;
+                }
+            }
+        }
+    }
+}
+
+}  // namespace
+
+void launch_rank_from_idx(const int32_t* idx, int32_t* rank, int B, int N, int k, hipStream_t stream) {
+    rank_from_idx_kernel<<<dim3((N + 255) / 256, B), 256, 0, stream>>>(idx, rank, N, k);
+}
+
+void launch_restore(const void* y_kept, const int32_t* rank, int B, int k, const void* cache_map, int hc,
+                    int wc, int h, int w, int D, void* y_out, hipStream_t stream) {
+    const int N = h * w;
+    const int rows_per_block = 4 * kRowsPerWave;
+    restore_kernel<<<dim3((N + rows_per_block - 1) / rows_per_block, B), 256, 0, stream>>>(
+        static_cast<const bf16_t*>(y_kept), rank, k, static_cast<const bf16_t*>(cache_map), hc, wc, h, w, D,
+        static_cast<bf16_t*>(y_out));
+}
+
+}  // namespace fv

@@ -1,0 +1,232 @@
+"""GPU parity: fastvar_block_forward_pruned and fastvar_step vs the CPU oracle.
+
+Bar for floating-point outputs: max |gpu - oracle| / max |oracle| <= 2e-2 per
+tensor (bf16 kernels vs the fp64 oracle), also asserted on the two residual
+branches (h1 - xk is not observable from outside, so the branch check is on
+y - xk, whose magnitude is that of the branches, not of the O(1) residual).
+Appended K/V rows are compared the same way; cache rows outside [L0, L0+k)
+must be untouched bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fastvar_oracle as O
+from paper_2503_23367_amd import binding as fb
+from paper_2503_23367_amd import synth
+from gpu_util import (DEV, cache_rows, empty_ws, from_dev_bf16, make_caches, max_rel, to_dev_bf16,
+                      upload_weights)
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+def run_block(x_np, idx_np, dims, W, kp, vp, L_cap, eps=1e-6, scale=None):
+    B, N, D = x_np.shape
+    k = idx_np.shape[1]
+    L0 = kp.shape[1]
+    d = fb.make_dims(dims.D, dims.H, dims.dh, dims.F, eps, scale)
+    wt, ws_struct = upload_weights(W)
+    x = to_dev_bf16(x_np)
+    idx = torch.from_numpy(idx_np.astype(np.int32)).to(DEV)
+    kc, vc = make_caches(kp, vp, L_cap)
+    kc0, vc0 = kc.clone(), vc.clone()
+    y = torch.full((B, max(k, 1), D), float("nan"), dtype=torch.bfloat16, device=DEV)
+    ws = empty_ws(fb.fastvar_block_workspace_bytes(d, B, k))
+    ws.fill_(0xFF)   # NaN patterns: stale scratch must never leak into results
+    fb.fastvar_block_forward_pruned(x, N, idx, B, k, d, ws_struct, kc, vc, L0, L_cap, y, ws)
+    torch.cuda.synchronize()
+    return from_dev_bf16(y)[:, :k], kc, vc, kc0, vc0
+
+
+def check_block(name, dims, B, h, w, k, L0, L_cap, seed=0, rows=None, kind="smooth_spike"):
+    print(f"[block] {name} D={dims.D} H={dims.H} dh={dims.dh} F={dims.F} B={B} N={h*w} k={k} L0={L0} L_cap={L_cap}",
+          flush=True)
+    N = h * w
+    x = synth.token_map(seed, B, h, w, dims.D, kind=kind)
+    W = synth.block_weights(seed, dims)
+    kp, vp = synth.kv_prior(seed, B, L0, dims.H, dims.dh)
+    idx, _, _ = O.select_pivotal(x, k)
+    y, kc, vc, kc0, vc0 = run_block(x, idx, dims, W, kp, vp, L_cap)
+    xk = O.gather_tokens(x, idx)
+    yo, kn, vn = O.block_forward_pruned(xk, W, dims.H, kp, vp, rows=rows)
+    if rows is not None:
+        y = y[:, rows]
+        xk = xk[:, rows]
+    assert not np.isnan(y).any(), name
+    e_y = max_rel(y, yo)
+    e_br = max_rel(y.astype(np.float64) - xk, yo - xk)
+    kg, vg = cache_rows(kc, vc, L0, L0 + k)
+    e_k, e_v = max_rel(kg, kn), max_rel(vg, vn)
+    print(f"    max-rel: y {e_y:.2e}  branches {e_br:.2e}  k_new {e_k:.2e}  v_new {e_v:.2e}", flush=True)
+    assert e_y <= TOL and e_br <= TOL and e_k <= TOL and e_v <= TOL, name
+    # cache outside the appended window untouched (bitwise, NaN poison included)
+    kb, kb0 = kc.view(torch.int16), kc0.view(torch.int16)
+    vb, vb0 = vc.view(torch.int16), vc0.view(torch.int16)
+    assert torch.equal(kb[:, :, :L0], kb0[:, :, :L0]) and torch.equal(kb[:, :, L0 + k:], kb0[:, :, L0 + k:])
+    assert torch.equal(vb[:, :, :, :L0], vb0[:, :, :, :L0]) and torch.equal(vb[:, :, :, L0 + k:], vb0[:, :, :, L0 + k:])
+
+
+TINY128 = synth.BlockDims(D=256, H=2, dh=128, F=512)
+TINY64 = synth.BlockDims(D=192, H=3, dh=64, F=320)
+
+CASES = [
+    # name, dims, B, h, w, k, L0, L_cap
+    ("d16_256px_last", synth.D16, 1, 16, 16, 128, 424, 688),
+    ("tiny64_ragged", TINY64, 2, 7, 9, 37, 29, 104),
+    ("tiny128_ragged", TINY128, 3, 9, 11, 70, 45, 128),
+    ("tiny128_no_prior", TINY128, 1, 8, 8, 33, 0, 40),
+    ("tiny64_single_kept", TINY64, 2, 5, 5, 1, 63, 64),
+    ("tiny128_keep_all_tile_edges", TINY128, 1, 16, 16, 256, 128, 384),
+    ("d30_s24_b2", synth.D30, 2, 24, 24, 346, 640, 992),
+    ("inf2b_s40_keep0.6", synth.INF2B, 1, 40, 40, 960, 2521, 3488),
+]
+
+
+@pytest.mark.parametrize("name,dims,B,h,w,k,L0,L_cap", CASES, ids=[c[0] for c in CASES])
+def test_block_matches_oracle(name, dims, B, h, w, k, L0, L_cap):
+    check_block(name, dims, B, h, w, k, L0, L_cap, seed=7)
+
+
+def test_block_headline_full_size_sampled_rows():
+    """1024 px last scale, keep 0.5: every kept token's K/V checked, outputs on sampled rows."""
+    wl = synth.WORKLOADS[synth.HEADLINE]
+    rows = np.unique(np.concatenate([np.arange(0, 3), np.arange(1020, 1030), np.arange(2040, 2048),
+                                     np.random.default_rng(1).integers(0, 2048, 40)]))
+    check_block("headline_sampled", wl.dims, 1, wl.h, wl.h, wl.k, wl.L0_full, 8480, seed=5, rows=rows)
+
+
+def test_block_d30_batch8_sampled_rows():
+    wl = synth.WORKLOADS["d30_512px_s32_keep0.4"]
+    rows = np.unique(np.random.default_rng(2).integers(0, wl.k, 48))
+    check_block("d30_s32_b8_sampled", wl.dims, wl.B, wl.h, wl.h, wl.k, wl.L0_pruned, 1400, seed=6, rows=rows)
+
+
+def test_keep_all_equals_dense_block_on_gpu():
+    """Keep ratio 1.0: the pruned path is the unpruned block (any kept order)."""
+    print("[block] keep 1.0 == dense", flush=True)
+    dims, B, h, w, L0 = TINY128, 1, 6, 6, 20
+    N = h * w
+    x = synth.token_map(3, B, h, w, dims.D)
+    W = synth.block_weights(3, dims)
+    kp, vp = synth.kv_prior(3, B, L0, dims.H, dims.dh)
+    idx = np.tile(np.arange(N, dtype=np.int32), (B, 1))
+    y, *_ = run_block(x, idx, dims, W, kp, vp, 64)
+    yo, _, _ = O.block_forward_pruned(x, W, dims.H, kp, vp)
+    assert max_rel(y, yo) <= TOL
+    # a shuffled kept set gives the same rows, permuted
+    perm = np.random.default_rng(0).permutation(N).astype(np.int32)
+    y2, *_ = run_block(x, perm[None], dims, W, kp, vp, 64)
+    assert max_rel(y2, yo[:, perm]) <= TOL
+
+
+def test_block_without_biases_and_custom_scale():
+    print("[block] null biases, eps/scale arguments", flush=True)
+    dims, B, h, w, k, L0 = TINY64, 1, 6, 6, 20, 12
+    x = synth.token_map(4, B, h, w, dims.D)
+    W = synth.block_weights(4, dims)
+    Wn = {n: v for n, v in W.items() if not n.startswith("b_")}
+    kp, vp = synth.kv_prior(4, B, L0, dims.H, dims.dh)
+    idx, _, _ = O.select_pivotal(x, k)
+    y, *_ = run_block(x, idx, dims, Wn, kp, vp, 32, eps=1e-3, scale=0.2)
+    W0 = dict(Wn)
+    yo, _, _ = O.block_forward_pruned(O.gather_tokens(x, idx), W0, dims.H, kp, vp, eps=1e-3, scale=0.2)
+    assert max_rel(y, yo) <= TOL
+
+
+def test_block_argument_errors():
+    print("[block] error paths", flush=True)
+    dims = TINY64
+    d = fb.make_dims(dims.D, dims.H, dims.dh, dims.F)
+    W = synth.block_weights(1, dims)
+    wt, wstruct = upload_weights(W)
+    x = to_dev_bf16(synth.token_map(1, 1, 4, 4, dims.D))
+    idx = torch.arange(4, dtype=torch.int32, device=DEV).reshape(1, 4)
+    kp, vp = synth.kv_prior(1, 1, 8, dims.H, dims.dh)
+    kc, vc = make_caches(kp, vp, 16)
+    y = torch.zeros((1, 4, dims.D), dtype=torch.bfloat16, device=DEV)
+    ws = empty_ws(fb.fastvar_block_workspace_bytes(d, 1, 4))
+
+    def call(**over):
+        a = dict(x=x, N=16, idx=idx, B=1, k=4, dims=d, weights=wstruct, k_cache=kc, v_cache=vc, L0=8, L_cap=16,
+                 y_kept_out=y, ws=ws)
+        a.update(over)
+        try:
+            fb.fastvar_block_forward_pruned(**a)
+        except fb.FastvarError as e:
+            return e.code
+        return 0
+
+    assert call(L0=13) == fb.FASTVAR_ECAPACITY
+    assert call(k=17) == fb.FASTVAR_EINVAL
+    assert call(dims=fb.make_dims(dims.D, dims.H + 1, dims.dh, dims.F)) == fb.FASTVAR_EINVAL
+    assert call(dims=fb.make_dims(96, 3, 32, 128)) == fb.FASTVAR_EALIGN
+    assert call(ws=empty_ws(256)) == fb.FASTVAR_EWORKSPACE
+    assert call(L_cap=15) in (fb.FASTVAR_EALIGN, fb.FASTVAR_ECAPACITY)
+    assert call(k=0, idx=None, y_kept_out=None, ws=None) == 0          # no-op
+    torch.cuda.synchronize()
+    assert torch.all(y == 0)
+
+
+# ------------------------------- whole step ----------------------------------
+
+def run_step(wl_dims, sides, step, cache_step, B, k, x_np, W, kp, vp, cache_np, L_cap):
+    N = sides[step] ** 2
+    D = wl_dims.D
+    d = fb.make_dims(wl_dims.D, wl_dims.H, wl_dims.dh, wl_dims.F)
+    wt, wstruct = upload_weights(W)
+    x = to_dev_bf16(x_np)
+    kc, vc = make_caches(kp, vp, L_cap)
+    cache = to_dev_bf16(cache_np)
+    y = torch.full((B, N, D), float("nan"), dtype=torch.bfloat16, device=DEV)
+    idx = torch.full((B, max(k, 1)), -7, dtype=torch.int32, device=DEV)
+    ws = empty_ws(fb.fastvar_step_workspace_bytes(d, B, N, k))
+    ws.fill_(0xFF)
+    new_len = fb.fastvar_step(x, list(sides), list(sides), step, cache_step, B, k, d, wstruct, kc, vc,
+                              kp.shape[1], L_cap, cache, y, idx, ws)
+    torch.cuda.synchronize()
+    return from_dev_bf16(y), idx[:, :k].cpu().numpy(), new_len, kc, vc
+
+
+@pytest.mark.parametrize("k", [128, 0, 256, 26])
+def test_step_d16_256px_matches_oracle(k):
+    """The small workload: one VAR-d16-style block, last step of the 256 px schedule."""
+    wl = synth.WORKLOADS[synth.SMALL]
+    print(f"[step] {wl.name} k={k}", flush=True)
+    B, dims = 1, wl.dims
+    x = synth.token_map(0, B, wl.h, wl.h, dims.D)
+    W = synth.block_weights(0, dims)
+    kp, vp = synth.kv_prior(0, B, wl.L0_full, dims.H, dims.dh)
+    cache = synth.cached_map(0, B, wl.hc, wl.hc, dims.D)
+    y, idx, new_len, kc, vc = run_step(dims, wl.sides, wl.step, wl.cache_step, B, k, x, W, kp, vp, cache, 688)
+    ref = O.step(x, wl.h, wl.h, k, W, dims.H, kp, vp, cache, wl.hc, wl.hc)
+    np.testing.assert_array_equal(idx, ref["idx"])
+    assert new_len == wl.L0_full + k
+    assert not np.isnan(y).any()
+    assert max_rel(y, ref["y"]) <= TOL
+    kept = np.zeros(wl.N, bool)
+    kept[ref["idx"][0]] = True
+    if k > 0:
+        assert max_rel(y[0, kept], ref["y"][0, kept]) <= TOL
+        kg, vg = cache_rows(kc, vc, wl.L0_full, wl.L0_full + k)
+        assert max_rel(kg, ref["k_new"]) <= TOL and max_rel(vg, ref["v_new"]) <= TOL
+    if k < wl.N:
+        up = O.upsample_bilinear(cache, wl.hc, wl.hc, wl.h, wl.h)
+        g, r = y[0, ~kept].astype(np.float64), up[0, ~kept]
+        assert np.all(np.abs(g - r) <= 2.0 ** -8 * 1.001 * np.abs(r) + 2e-6)
+
+
+def test_step_batched_ragged_matches_oracle():
+    print("[step] tiny128 B=3 rectangular-free ragged sizes", flush=True)
+    dims = TINY128
+    sides = (1, 2, 3, 5, 7, 11)
+    B, step, cache_step, k, L0 = 3, 5, 3, 50, 88
+    x = synth.token_map(8, B, 11, 11, dims.D)
+    W = synth.block_weights(8, dims)
+    kp, vp = synth.kv_prior(8, B, L0, dims.H, dims.dh)
+    cache = synth.cached_map(8, B, 5, 5, dims.D)
+    y, idx, new_len, kc, vc = run_step(dims, sides, step, cache_step, B, k, x, W, kp, vp, cache, 144)
+    ref = O.step(x, 11, 11, k, W, dims.H, kp, vp, cache, 5, 5)
+    np.testing.assert_array_equal(idx, ref["idx"])
+    assert new_len == L0 + k
+    assert max_rel(y, ref["y"]) <= TOL

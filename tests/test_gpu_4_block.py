@@ -1,9 +1,11 @@
 """GPU parity: fastvar_block_forward_pruned and fastvar_step vs the CPU oracle.
 
 Bar for floating-point outputs: max |gpu - oracle| / max |oracle| <= 2e-2 per
-tensor (bf16 kernels vs the fp64 oracle), also asserted on the two residual
-branches (h1 - xk is not observable from outside, so the branch check is on
-y - xk, whose magnitude is that of the branches, not of the O(1) residual).
+tensor (bf16 kernels vs the fp64 oracle).  The residual branches are checked
+too (on y - xk, since h1 is not observable from outside): their error, after
+allowing for the two bf16 roundings of the residual stream itself (2^-7 of
+max|y|), must be within 2e-2 of the branch magnitude, so that the O(1)
+residual cannot hide a wrong GEMM.
 Appended K/V rows are compared the same way; cache rows outside [L0, L0+k)
 must be untouched bit for bit.
 """
@@ -55,7 +57,11 @@ def check_block(name, dims, B, h, w, k, L0, L_cap, seed=0, rows=None, kind="smoo
         xk = xk[:, rows]
     assert not np.isnan(y).any(), name
     e_y = max_rel(y, yo)
-    e_br = max_rel(y.astype(np.float64) - xk, yo - xk)
+    # branch check: the residual stream is stored in bf16 twice (h1 and y), half an
+    # ulp (<= 2^-8 |v|) each, i.e. up to 2^-7 * max|y| absolute; what exceeds that must be
+    # within TOL of the branch magnitude.
+    br_err = np.max(np.abs((y.astype(np.float64) - xk) - (yo - xk)))
+    e_br = max(0.0, br_err - 2.0 ** -7 * float(np.max(np.abs(yo)))) / float(np.max(np.abs(yo - xk)))
     kg, vg = cache_rows(kc, vc, L0, L0 + k)
     e_k, e_v = max_rel(kg, kn), max_rel(vg, vn)
     print(f"    max-rel: y {e_y:.2e}  branches {e_br:.2e}  k_new {e_k:.2e}  v_new {e_v:.2e}", flush=True)

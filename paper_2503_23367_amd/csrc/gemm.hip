@@ -13,14 +13,14 @@
 // Epilogues are fused: bias, residual add, exact GELU, and for the QKV GEMM
 // the split into the query buffer and the append into the K / V caches
 // (V transposed so that cache positions are contiguous).
+#include <stdlib.h>
+
 #include "common.h"
 #include "kernels.h"
 
 namespace fv {
 
 namespace {
-
-constexpr int BK = 64;  // K step; one LDS row = 64 bf16 = 8 chunks of 16 bytes
 
 // Exact-form GELU, v * Phi(v), with erf from the rational approximation of
 // Abramowitz & Stegun 7.1.26 (absolute error below 1.5e-7, far under bf16
@@ -91,20 +91,40 @@ __device__ __forceinline__ ColDest col_dest(const GemmParams& p, int n) {
     return c;
 }
 
-template <int BM, int BN, int EPI>
+// s_waitcnt immediate (gfx9 encoding): wait until at most `vm` vector-memory
+// operations are outstanding; lgkm = true also waits for all LDS/scalar ops.
+constexpr int waitcnt_imm(int vm, bool lgkm) {
+    return (vm & 0xF) | ((vm >> 4) << 14) | (0x7 << 4) | ((lgkm ? 0x0 : 0xF) << 8);
+}
+
+// XOR key that spreads the 16-byte chunks of consecutive rows over all LDS banks:
+// rows of 128 bytes (8 chunks) use the low 3 row bits, rows of 64 bytes (4 chunks,
+// two rows per 128 bytes) use row bits 1-2.
+template <int CPR>
+__device__ __forceinline__ int swz(int row) {
+    return CPR == 8 ? (row & 7) : ((row >> 1) & 3);
+}
+
+template <int BM, int BN, int BK, int STAGES, int EPI>
 __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
-    constexpr int T = 256;
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
     constexpr int WTM = BM / 2, WTN = BN / 2;  // wave tile (2 x 2 waves)
     constexpr int MI = WTM / 32, NI = WTN / 32;
-    constexpr int A_CH = BM * 8 / T, W_CH = BN * 8 / T;  // 16-byte chunks per thread per tile
+    constexpr int CPR = BK / 8;                // 16-byte chunks per LDS row
+    constexpr int RPI = 64 / CPR;              // rows covered by one 64-lane direct-to-LDS load
+    constexpr int KK = BK / 16;                // MFMA k-steps per tile
+    constexpr int A_LD = BM / RPI / 4, W_LD = BN / RPI / 4;  // loads per wave per tile
+    constexpr int LPT = A_LD + W_LD;
+    constexpr int A_TILE = BM * CPR, W_TILE = BN * CPR;      // 16-byte chunks per stage
+    constexpr int STAGE = A_TILE + W_TILE;
+    static_assert((STAGES - 2) * LPT <= 63, "vmcnt is 6 bits");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    u32x4_t* sA = reinterpret_cast<u32x4_t*>(smem);  // [2][BM*8]
-    u32x4_t* sW = sA + 2 * BM * 8;                   // [2][BN*8]
+    u32x4_t* lds = reinterpret_cast<u32x4_t*>(smem);  // [STAGES][A tile | W tile]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
 
     // Tile id: consecutive workgroup ids are dealt round-robin to the 8 XCDs;
@@ -123,15 +143,49 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
     const int tn = in_grp / gsize;
     const int m0 = tm * BM, n0 = tn * BN;
 
-    // per-thread load slots: chunk column c is fixed, rows step by 32
-    const int c = tid & 7;
-    const int r_base = tid >> 3;
-    const int lds_slot = r_base * 8 + (c ^ (r_base & 7));
-    int a_off[A_CH], w_off[W_CH];
+    // Direct-to-LDS loads: one instruction moves 64 x 16 bytes into a contiguous
+    // 1 KB of LDS (lane l lands at base + 16 l), i.e. RPI whole tile rows.  The
+    // swizzle is applied on the global side: lane l fetches the chunk that
+    // belongs at its LDS position.  Load j of a wave covers rows (wave + 4 j) * RPI ...
+    const int ld_row = lane / CPR;
+    const int ld_chunk = (lane % CPR) ^ swz<CPR>(ld_row);
+    int a_off[A_LD], w_off[W_LD];
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) a_off[i] = min(m0 + r_base + 32 * i, p.M - 1) * p.K + c * 8;
+    for (int j = 0; j < A_LD; ++j)
+        a_off[j] = min(m0 + (wave + 4 * j) * RPI + ld_row, p.M - 1) * p.K + ld_chunk * 8;
 #pragma unroll
-    for (int i = 0; i < W_CH; ++i) w_off[i] = min(n0 + r_base + 32 * i, p.N - 1) * p.K + c * 8;
+    for (int j = 0; j < W_LD; ++j)
+        w_off[j] = min(n0 + (wave + 4 * j) * RPI + ld_row, p.N - 1) * p.K + ld_chunk * 8;
+
+    typedef __attribute__((address_space(3))) void* lds_ptr_t;
+#define FV_ISSUE_TILE(kt_, stage_)                                                              \
+    {                                                                                           \
+        const bf16_t* ga_ = p.A + (size_t)(kt_) * BK;                                           \
+        const bf16_t* gw_ = p.W + (size_t)(kt_) * BK;                                           \
+        u32x4_t* sa_ = lds + (stage_) * STAGE + wave * 64;                                      \
+        u32x4_t* sw_ = sa_ + A_TILE;                                                            \
+        _Pragma("unroll") for (int j = 0; j < A_LD; ++j)                                        \
+            __builtin_amdgcn_global_load_lds(ga_ + a_off[j], (lds_ptr_t)(sa_ + j * 256), 16, 0, 0); \
+        _Pragma("unroll") for (int j = 0; j < W_LD; ++j)                                        \
+            __builtin_amdgcn_global_load_lds(gw_ + w_off[j], (lds_ptr_t)(sw_ + j * 256), 16, 0, 0); \
+    }
+
+    const int frag_row = lane & 31;
+    const int frag_half = lane >> 5;
+    const int a_row = wm * WTM + frag_row;  // + 32 mi
+    const int w_row = wn * WTN + frag_row;  // + 32 ni
+    const int frag_sw = swz<CPR>(frag_row);
+
+#define FV_LOAD_FRAGS(dst_a_, dst_w_, stage_, kk_)                                              \
+    {                                                                                           \
+        const u32x4_t* sa_ = lds + (stage_) * STAGE;                                            \
+        const u32x4_t* sw_ = sa_ + A_TILE;                                                      \
+        const int ch_ = (2 * (kk_) + frag_half) ^ frag_sw;                                      \
+        _Pragma("unroll") for (int mi = 0; mi < MI; ++mi)                                       \
+            dst_a_[mi] = *reinterpret_cast<const bf16x8_t*>(sa_ + (a_row + 32 * mi) * CPR + ch_); \
+        _Pragma("unroll") for (int ni = 0; ni < NI; ++ni)                                       \
+            dst_w_[ni] = *reinterpret_cast<const bf16x8_t*>(sw_ + (w_row + 32 * ni) * CPR + ch_); \
+    }
 
     f32x16_t acc[MI][NI];
 #pragma unroll
@@ -141,129 +195,218 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
-    u32x4_t ra[A_CH], rw[W_CH];
     const int KT = p.K / BK;
 
-#define FV_LOAD_GLOBAL(kt_)                                                      \
-    {                                                                            \
-        const int k0_ = (kt_) * BK;                                              \
-        _Pragma("unroll") for (int i = 0; i < A_CH; ++i)                         \
-            ra[i] = *reinterpret_cast<const u32x4_t*>(p.A + a_off[i] + k0_);     \
-        _Pragma("unroll") for (int i = 0; i < W_CH; ++i)                         \
-            rw[i] = *reinterpret_cast<const u32x4_t*>(p.W + w_off[i] + k0_);     \
+    // ---- prologue: STAGES-1 tiles in flight, wait for the first
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s)
+        if (s < KT) FV_ISSUE_TILE(s, s)
+    if (KT >= STAGES - 1)
+        __builtin_amdgcn_s_waitcnt(waitcnt_imm((STAGES - 2) * LPT, true));
+    else
+        __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+
+    bf16x8_t fa[2][MI], fw[2][NI];
+    FV_LOAD_FRAGS(fa[0], fw[0], 0, 0)
+
+#define FV_MFMA_ROWS(cur_, mi_lo_, mi_hi_)                                                      \
+    _Pragma("unroll") for (int mi = (mi_lo_); mi < (mi_hi_); ++mi)                              \
+        _Pragma("unroll") for (int ni = 0; ni < NI; ++ni)                                       \
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur_][mi], fw[cur_][ni],   \
+                                                                  acc[mi][ni], 0, 0, 0);
+#define FV_INTERLEAVE(mfma_per_read_)                                                           \
+    _Pragma("unroll") for (int g = 0; g < MI + NI; ++g) {                                       \
+        __builtin_amdgcn_sched_group_barrier(0x008, (mfma_per_read_), 0); /* MFMA */            \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                /* DS read */         \
     }
-#define FV_STORE_LDS(buf_)                                                       \
-    {                                                                            \
-        u32x4_t* da_ = sA + (buf_) * BM * 8 + lds_slot;                          \
-        u32x4_t* dw_ = sW + (buf_) * BN * 8 + lds_slot;                          \
-        _Pragma("unroll") for (int i = 0; i < A_CH; ++i) da_[i * 256] = ra[i];   \
-        _Pragma("unroll") for (int i = 0; i < W_CH; ++i) dw_[i * 256] = rw[i];   \
+    // One K tile.  Software pipeline inside the wave: the operand reads of the
+    // next k-step are interleaved with the MFMAs of the current one (the
+    // scheduler is told the pattern), so LDS latency hides behind the matrix
+    // pipe.  MORE_: a further tile is fetched (STAGES-1 ahead).  HANDOVER_: a
+    // next tile exists, so the last k-step waits for it (this wave's loads: the
+    // counter; the other waves' loads: the barrier, which also tells everyone
+    // that the stage refilled in the next iteration is no longer being read) and
+    // preloads its first operands.  The body is branch free on purpose: the
+    // accumulators must stay in one register class across the whole loop.
+#define FV_TILE_BODY(MORE_, HANDOVER_)                                                          \
+    {                                                                                           \
+        int fill_ = stage + STAGES - 1;                                                         \
+        if (fill_ >= STAGES) fill_ -= STAGES;                                                   \
+        if (MORE_) FV_ISSUE_TILE(kt + STAGES - 1, fill_)                                        \
+        int next_stage_ = stage + 1;                                                            \
+        if (next_stage_ == STAGES) next_stage_ = 0;                                             \
+        _Pragma("unroll") for (int kk = 0; kk < KK; ++kk) {                                     \
+            const int cur_ = kk & 1, nxt_ = cur_ ^ 1;                                           \
+            if (kk + 1 < KK) {                                                                  \
+                FV_LOAD_FRAGS(fa[nxt_], fw[nxt_], stage, kk + 1)                                \
+                FV_MFMA_ROWS(cur_, 0, MI)                                                       \
+                FV_INTERLEAVE((MI * NI) / (MI + NI))                                            \
+            } else if (HANDOVER_) {                                                             \
+                FV_MFMA_ROWS(cur_, 0, MI / 2)                                                   \
+                __builtin_amdgcn_s_waitcnt(waitcnt_imm((MORE_) ? (STAGES - 2) * LPT : 0, true)); \
+                asm volatile("" ::: "memory");                                                  \
+                __builtin_amdgcn_s_barrier();                                                   \
+                asm volatile("" ::: "memory");                                                  \
+                FV_LOAD_FRAGS(fa[nxt_], fw[nxt_], next_stage_, 0)                               \
+                FV_MFMA_ROWS(cur_, MI / 2, MI)                                                  \
+                FV_INTERLEAVE((MI * NI / 2) / (MI + NI) > 0 ? (MI * NI / 2) / (MI + NI) : 1)    \
+            } else {                                                                            \
+                FV_MFMA_ROWS(cur_, 0, MI)                                                       \
+            }                                                                                   \
+        }                                                                                       \
+        stage = next_stage_;                                                                    \
     }
 
-    FV_LOAD_GLOBAL(0)
-    FV_STORE_LDS(0)
-    __syncthreads();
+    int stage = 0;  // stage of tile kt
+    int kt = 0;
+    for (; kt + STAGES - 1 < KT; ++kt) FV_TILE_BODY(true, true)
+    for (; kt + 1 < KT; ++kt) FV_TILE_BODY(false, true)
+    FV_TILE_BODY(false, false)
+#undef FV_TILE_BODY
+#undef FV_INTERLEAVE
+#undef FV_MFMA_ROWS
+#undef FV_ISSUE_TILE
+#undef FV_LOAD_FRAGS
 
-    const int frag_row = lane & 31;
-    const int frag_half = lane >> 5;
-    const int frag_sw = lane & 7;
+    // ---- Epilogue, staged through LDS so that global traffic is 16 bytes per lane.
+    // Accumulator register r of lane l holds C[row, col] with col = l % 32 and
+    // row = 8*(r/4) + 4*(l/32) + r%4 inside a 32x32 block.  Each wave owns a
+    // private fp32 staging area of 32 rows x WTN columns: it writes one 32-row
+    // slab of its tile in accumulator layout (bias and GELU applied), reads it
+    // back row-wise (8 columns per lane), adds the residual, rounds once to bf16
+    // and stores 16 bytes per lane.  LDS operations of one wave execute in
+    // order, so no barrier is needed between the two phases.
+    constexpr int SROW = WTN + 4;          // padded row stride (floats)
+    constexpr int LPR = WTN / 8;           // lanes per row in the read-back phase
+    constexpr int RPP = 64 / LPR;          // rows per pass
+    constexpr int PASSES = 32 / RPP;
+    static_assert(4 * 32 * SROW * 4 <= STAGES * (BM + BN) * BK * 2, "staging area must fit in the tile LDS");
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
+    __builtin_amdgcn_s_barrier();  // every wave is done reading operand tiles
+    asm volatile("" ::: "memory");
+    float* stg = reinterpret_cast<float*>(smem) + wave * (32 * SROW);
 
-    for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < KT) FV_LOAD_GLOBAL(kt + 1)
-
-        const u32x4_t* a_base = sA + buf * BM * 8 + (wm * WTM + frag_row) * 8;
-        const u32x4_t* w_base = sW + buf * BN * 8 + (wn * WTN + frag_row) * 8;
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            const int ch = (2 * kk + frag_half) ^ frag_sw;
-            bf16x8_t af[MI], bfr[NI];
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-                af[mi] = *reinterpret_cast<const bf16x8_t*>(a_base + mi * 32 * 8 + ch);
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
-                bfr[ni] = *reinterpret_cast<const bf16x8_t*>(w_base + ni * 32 * 8 + ch);
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
-        }
-
-        if (kt + 1 < KT) FV_STORE_LDS(buf ^ 1)
-        __syncthreads();
-    }
-#undef FV_LOAD_GLOBAL
-#undef FV_STORE_LDS
-
-    // Epilogue.  Accumulator register r of lane l holds C[row, col] with
-    // col = l % 32 and row = 8*(r/4) + 4*(l/32) + r%4 inside the 32x32 block.
-    ColDest cd[NI];
     float bias[NI];
-    bool n_ok[NI];
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
         const int n = n0 + wn * WTN + ni * 32 + frag_row;
-        n_ok[ni] = n < p.N;
-        const int nc = n_ok[ni] ? n : 0;
-        cd[ni] = col_dest<EPI>(p, nc);
-        bias[ni] = p.bias ? bf16_to_f32(p.bias[nc]) : 0.f;
+        bias[ni] = (p.bias && n < p.N) ? bf16_to_f32(p.bias[n]) : 0.f;
     }
+    const int cg = lane % LPR, rsub = lane / LPR;
+    const int ncol = n0 + wn * WTN + cg * 8;  // first of this lane's 8 output columns
+    const bool col_ok = ncol < p.N;           // N % 8 == 0: the whole group is in or out
+    const ColDest cd = col_dest<EPI>(p, col_ok ? ncol : 0);
+    bool row_path = col_ok;
+    if (EPI == EPI_QKV) row_path = col_ok && ncol < 2 * p.D;  // the V section is stored transposed below
+
     static_for<0, MI>([&](auto mi_c) {
         constexpr int mi = decltype(mi_c)::value;
-        static_for<0, 16>([&](auto r_c) {
-            constexpr int r = decltype(r_c)::value;
-            const int m = m0 + wm * WTM + mi * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
-            if (m < p.M) {
+        static_for<0, NI>([&](auto ni_c) {
+            constexpr int ni = decltype(ni_c)::value;
+            static_for<0, 16>([&](auto r_c) {
+                constexpr int r = decltype(r_c)::value;
+                float v = acc[mi][ni][r] + bias[ni];
+                if (EPI == EPI_BIAS_GELU) v = gelu_erf(v);
+                stg[(8 * (r >> 2) + 4 * frag_half + (r & 3)) * SROW + ni * 32 + frag_row] = v;
+            });
+        });
+        const int m_slab = m0 + wm * WTM + mi * 32;
+#pragma unroll
+        for (int ps = 0; ps < PASSES; ++ps) {
+            const int row = ps * RPP + rsub;
+            const int m = m_slab + row;
+            if (m < p.M && row_path) {
+                const f32x4_t lo = *reinterpret_cast<const f32x4_t*>(stg + row * SROW + cg * 8);
+                const f32x4_t hi = *reinterpret_cast<const f32x4_t*>(stg + row * SROW + cg * 8 + 4);
+                float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
                 const int b = m / p.k_tokens;
                 const int t = m - b * p.k_tokens;
-                const bf16_t* res_row = nullptr;
                 if (EPI == EPI_BIAS_RES) {
                     const size_t rrow = p.res_idx ? (size_t)b * p.res_N + p.res_idx[m] : (size_t)m;
-                    res_row = p.residual + rrow * p.N + (n0 + wn * WTN + frag_row);
+                    const u32x4_t rr = *reinterpret_cast<const u32x4_t*>(p.residual + rrow * p.N + ncol);
+                    v[0] += bf16_lo(rr.x); v[1] += bf16_hi(rr.x);
+                    v[2] += bf16_lo(rr.y); v[3] += bf16_hi(rr.y);
+                    v[4] += bf16_lo(rr.z); v[5] += bf16_hi(rr.z);
+                    v[6] += bf16_lo(rr.w); v[7] += bf16_hi(rr.w);
                 }
-                static_for<0, NI>([&](auto ni_c) {
-                    constexpr int ni = decltype(ni_c)::value;
-                    if (n_ok[ni]) {
-                        float v = acc[mi][ni][r] + bias[ni];
-                        if (EPI == EPI_BIAS_GELU) v = gelu_erf(v);
-                        if (EPI == EPI_BIAS_RES) v += bf16_to_f32(res_row[ni * 32]);
-                        cd[ni].ptr[(long)b * cd[ni].batch_stride + (long)t * cd[ni].row_stride] =
+                u32x4_t o;
+                o.x = pack_bf16x2(v[0], v[1]);
+                o.y = pack_bf16x2(v[2], v[3]);
+                o.z = pack_bf16x2(v[4], v[5]);
+                o.w = pack_bf16x2(v[6], v[7]);
+                *reinterpret_cast<u32x4_t*>(cd.ptr + (long)b * cd.batch_stride + (long)t * cd.row_stride) = o;
+            }
+        }
+        if (EPI == EPI_QKV) {
+            // V section: cache positions are contiguous along the token (row) axis, so
+            // lanes walk the rows of a column: lane l handles row l%32 of columns
+            // l/32, l/32+2, ... of each 32-column block that lies in the V section.
+            const int m = m_slab + frag_row;
+            const int b = m / p.k_tokens;
+            const int t = m - b * p.k_tokens;
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) {
+                const int nb = n0 + wn * WTN + ni * 32;  // wave-uniform; sections are multiples of 64 wide
+                if (nb >= 2 * p.D && nb < p.N && m < p.M) {
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) {
+                        const int col = frag_half + 2 * j;
+                        const int f = nb + col - 2 * p.D;
+                        const int hh = f / p.dh;
+                        const int d = f - hh * p.dh;
+                        const float v = stg[frag_row * SROW + ni * 32 + col];
+                        p.v_cache[(((size_t)b * p.H + hh) * p.dh + d) * p.L_cap + p.L0 + t] =
                             (bf16_t)f32_to_bf16_bits(v);
                     }
-                });
+                }
             }
-        });
+        }
     });
+#endif
 }
 
-template <int BM, int BN>
-constexpr size_t smem_bytes() {
-    return (size_t)2 * (BM + BN) * BK * sizeof(bf16_t);
-}
-
-template <int BM, int BN, int EPI>
+template <int BM, int BN, int BK, int STAGES, int EPI>
 void launch_cfg(GemmParams& p, hipStream_t stream) {
+    constexpr size_t smem = (size_t)STAGES * (BM + BN) * BK * sizeof(bf16_t);
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
     static bool attr_set = false;  // raising the dynamic-LDS limit is per function, once per process
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_kernel<BM, BN, EPI>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<BM, BN>());
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_kernel<BM, BN, BK, STAGES, EPI>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         attr_set = true;
     }
-    gemm_nt_kernel<BM, BN, EPI><<<dim3(p.tiles_m * p.tiles_n), 256, smem_bytes<BM, BN>(), stream>>>(p);
+    gemm_nt_kernel<BM, BN, BK, STAGES, EPI><<<dim3(p.tiles_m * p.tiles_n), 256, smem, stream>>>(p);
+}
+
+int gemm_cfg_override() {
+    static int v = -2;
+    if (v == -2) {
+        const char* e = getenv("FASTVAR_GEMM_CFG");
+        v = e ? atoi(e) : -1;
+    }
+    return v;
 }
 
 template <int EPI>
 void launch_epi(GemmParams& p, hipStream_t stream) {
-    // Large tiles only when they still give every CU at least one tile.
-    const long big_tiles = (long)((p.M + 255) / 256) * ((p.N + 255) / 256);
-    if (big_tiles >= 224)
-        launch_cfg<256, 256, EPI>(p, stream);
-    else
-        launch_cfg<128, 128, EPI>(p, stream);
+    // 128x128 tiles (two workgroups per CU, so one's epilogue overlaps the other's
+    // main loop) measured equal or better than 256x256 on every block shape.
+    // With at most two tiles per CU the deeper pipeline of shorter K steps wins
+    // (out-proj, FC2); with more tiles the longer K step does.
+    const long tiles = (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
+    int cfg = tiles <= 512 ? 3 : 6;
+    if (gemm_cfg_override() >= 0) cfg = gemm_cfg_override();
+    switch (cfg) {
+        case 0: launch_cfg<256, 256, 32, 4, EPI>(p, stream); break;
+        case 1: launch_cfg<256, 256, 64, 2, EPI>(p, stream); break;
+        case 3: launch_cfg<128, 128, 32, 4, EPI>(p, stream); break;
+        default: launch_cfg<128, 128, 64, 2, EPI>(p, stream); break;
+    }
 }
 
 }  // namespace

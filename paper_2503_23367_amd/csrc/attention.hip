@@ -14,18 +14,24 @@
 // in-block key index exchanged (the accumulator row order of the first MFMA
 // then lines up with 16-byte runs of keys in the V^T tile).
 //
-// A workgroup of 4 waves owns 128*QB queries of one (sample, head); each wave
-// owns 32*QB of them and walks all keys in tiles of 64.  K and V^T tiles are
-// staged in LDS (double buffered, XOR-swizzled 16-byte chunks) and shared by
-// the four waves.
+// Work split: a wave owns 32*QB queries (QB = 2 halves the LDS traffic per
+// MFMA: every K / V^T fragment read feeds two MFMAs).  A workgroup has
+// QG * KSPLIT waves: QG query groups, and KSPLIT waves per group that each take
+// a different 64-key slice of every (64*KSPLIT)-key tile and are merged at the
+// end (softmax partials combine exactly).  KSPLIT = 2 keeps all SIMDs busy when
+// there are too few queries for one wave per SIMD.
+//
+// K and V^T tiles go global -> LDS directly (no register staging), double
+// buffered; 16-byte chunks are XOR-swizzled with the row so operand reads are
+// conflict free.
+#include <stdlib.h>
+
 #include "common.h"
 #include "kernels.h"
 
 namespace fv {
 
 namespace {
-
-constexpr int BN = 64;  // keys per tile
 
 struct AttnParams {
     const bf16_t* q;
@@ -40,49 +46,128 @@ __device__ __forceinline__ int swap_bits_2_3(int v) {
     return (v & ~12) | ((v & 4) << 1) | ((v & 8) >> 1);
 }
 
-// Eight consecutive cache positions of one V^T row; `valid` = how many of them
-// lie inside the cache length.  Positions past the length may hold anything
-// (even NaN patterns), so they are read as zero.
-__device__ __forceinline__ u32x4_t load_v_chunk(const bf16_t* src, int valid) {
-    u32x4_t v = {0u, 0u, 0u, 0u};
-    if (valid > 0) {
-        v = *reinterpret_cast<const u32x4_t*>(src);
-        if (valid < 8) {
-            v.x = valid >= 2 ? v.x : (v.x & 0xFFFFu);
-            v.y = valid >= 4 ? v.y : (valid >= 3 ? (v.y & 0xFFFFu) : 0u);
-            v.z = valid >= 6 ? v.z : (valid >= 5 ? (v.z & 0xFFFFu) : 0u);
-            v.w = valid >= 7 ? (v.w & 0xFFFFu) : 0u;
-        }
-    }
-    return v;
+// Value held by the lane 32 positions away (the other half-wave), through the
+// cross-half swap instruction instead of an LDS round trip.
+__device__ __forceinline__ float other_half(float v) {
+    const uint32_t u = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    // after the swap r[0] = {low half, low half} and r[1] = {high half, high half}
+    return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
 }
 
-template <int DH, int QB>
-__global__ __launch_bounds__(256) void attention_kernel(const AttnParams p) {
+constexpr int attn_waitcnt(int vm, bool lgkm) {
+    return (vm & 0xF) | ((vm >> 4) << 14) | (0x7 << 4) | ((lgkm ? 0x0 : 0xF) << 8);
+}
+
+template <int DH, int QB, int QG, int KSPLIT>
+__global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention_kernel(const AttnParams p) {
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
+    constexpr int WAVES = QG * KSPLIT;
+    constexpr int BN = 64 * KSPLIT;        // keys per tile
     constexpr int KCH = DH / 8;            // 16-byte chunks per key row
     constexpr int KS = DH / 16;            // MFMA k-steps over the head dim
     constexpr int DB = DH / 32;            // 32-row blocks of O^T
-    constexpr int K_LD = BN * KCH / 256;   // K-tile chunks per thread
-    constexpr int V_LD = DH * 8 / 256;     // V^T-tile chunks per thread
-    constexpr int K_TILE = BN * KCH;       // u32x4_t per K tile
-    constexpr int V_TILE = DH * 8;         // u32x4_t per V^T tile
+    constexpr int VCH = BN / 8;            // 16-byte chunks per V^T row
+    constexpr int K_TILE = BN * KCH;       // chunks per K tile
+    constexpr int V_TILE = DH * VCH;       // chunks per V^T tile
+    constexpr int K_RPI = 64 / KCH;        // key rows per 64-lane direct-to-LDS load
+    constexpr int V_RPI = 64 / VCH;        // V^T rows per load
+    constexpr int K_LD = BN / K_RPI / WAVES;   // loads per wave per tile
+    constexpr int V_LD = DH / V_RPI / WAVES;
+    static_assert(K_LD >= 1 && V_LD >= 1, "tile too small for this many waves");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    u32x4_t* sK = reinterpret_cast<u32x4_t*>(smem);  // [2][K_TILE]
-    u32x4_t* sV = sK + 2 * K_TILE;                 // [2][V_TILE]
+    u32x4_t* lds = reinterpret_cast<u32x4_t*>(smem);  // [2][K tile] then [2][V^T tile]
+    typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int li = lane & 31;   // query column / operand row
-    const int hf = lane >> 5;   // half-wave
-    const int sw = lane & 7;    // swizzle key of this lane's operand row
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int qg = wave / KSPLIT;       // query group
+    const int kh = wave % KSPLIT;       // key slice inside a tile
+    const int li = lane & 31;           // query column / operand row
+    const int hf = lane >> 5;           // half-wave
+    const int sw = lane & 7;            // swizzle key of this lane's operand row
     const int head = blockIdx.y;
     const int b = blockIdx.z;
-    const int q_base = blockIdx.x * (128 * QB) + wave * (32 * QB);
+    const int q_base = blockIdx.x * (QG * 32 * QB) + qg * (32 * QB);
 
     const bf16_t* kc = p.kc + ((size_t)b * p.H + head) * p.L_cap * DH;
     const bf16_t* vc = p.vc + ((size_t)b * p.H + head) * DH * (size_t)p.L_cap;
+
+    // ---- per-lane source descriptors of the direct-to-LDS loads.  Load j of this
+    // wave is instruction ij = wave + WAVES*j of the tile; it fills 1 KB of LDS,
+    // lane l landing at chunk 64*ij + l.
+    int k_key[K_LD], k_col[K_LD];   // key inside the tile, element offset inside the row
+    int v_row[V_LD], v_col[V_LD];   // element offset of the V^T row, key offset inside the tile
+#pragma unroll
+    for (int j = 0; j < K_LD; ++j) {
+        const int slot = (wave + WAVES * j) * K_RPI + lane / KCH;  // LDS row
+        const int c = (lane % KCH) ^ (slot & 7);                   // logical chunk stored at this position
+        k_key[j] = (slot & ~31) | swap_bits_2_3(slot & 31);
+        k_col[j] = c * 8;
+    }
+#pragma unroll
+    for (int j = 0; j < V_LD; ++j) {
+        const int d = (wave + WAVES * j) * V_RPI + lane / VCH;
+        const int c = (lane % VCH) ^ (d & 7);
+        v_row[j] = d * p.L_cap;
+        v_col[j] = c * 8;
+    }
+    const int last_chunk = ((p.L - 1) >> 3) << 3;  // start of the last 8-key run that holds a valid key
+
+    // K tiles and V^T tiles live in separate two-stage rings: the second MFMA of
+    // a tile is deferred to the next iteration (see the schedule below), so
+    // iteration k consumes K tile k and V^T tile k-1.
+#define FV_ISSUE_K(kt_)                                                                             \
+    {                                                                                               \
+        const int key0_ = (kt_) * BN;                                                               \
+        u32x4_t* sk_ = lds + ((kt_) & 1) * K_TILE + wave * 64;                                      \
+        _Pragma("unroll") for (int j = 0; j < K_LD; ++j) {                                          \
+            const int key_ = min(key0_ + k_key[j], p.L - 1);                                        \
+            __builtin_amdgcn_global_load_lds(kc + key_ * DH + k_col[j],                             \
+                                             (lds_ptr_t)(sk_ + j * (WAVES * 64)), 16, 0, 0);        \
+        }                                                                                           \
+    }
+#define FV_ISSUE_V(kt_)                                                                             \
+    {                                                                                               \
+        const int key0_ = (kt_) * BN;                                                               \
+        u32x4_t* sv_ = lds + 2 * K_TILE + ((kt_) & 1) * V_TILE + wave * 64;                         \
+        _Pragma("unroll") for (int j = 0; j < V_LD; ++j) {                                          \
+            const int kpos_ = min(key0_ + v_col[j], last_chunk);                                    \
+            __builtin_amdgcn_global_load_lds(vc + v_row[j] + kpos_,                                 \
+                                             (lds_ptr_t)(sv_ + j * (WAVES * 64)), 16, 0, 0);        \
+        }                                                                                           \
+    }
+    // Cache positions at or past the length may hold anything (even NaN patterns),
+    // and 0 * NaN would poison the output: after its own loads of a partial tile
+    // have landed, each lane zeroes the out-of-range positions of its V^T chunks.
+#define FV_FIX_TAIL(kt_)                                                                            \
+    {                                                                                               \
+        __builtin_amdgcn_s_waitcnt(attn_waitcnt(0, true));                                          \
+        const int key0_ = (kt_) * BN;                                                               \
+        u32x4_t* sv_ = lds + 2 * K_TILE + ((kt_) & 1) * V_TILE + wave * 64 + lane;                  \
+        _Pragma("unroll") for (int j = 0; j < V_LD; ++j) {                                          \
+            const int valid_ = p.L - (key0_ + v_col[j]);                                            \
+            if (valid_ < 8) {                                                                       \
+                u32x4_t v_ = sv_[j * (WAVES * 64)];                                                 \
+                v_.x = valid_ >= 2 ? v_.x : (valid_ >= 1 ? (v_.x & 0xFFFFu) : 0u);                  \
+                v_.y = valid_ >= 4 ? v_.y : (valid_ >= 3 ? (v_.y & 0xFFFFu) : 0u);                  \
+                v_.z = valid_ >= 6 ? v_.z : (valid_ >= 5 ? (v_.z & 0xFFFFu) : 0u);                  \
+                v_.w = valid_ >= 7 ? (v_.w & 0xFFFFu) : 0u;                                         \
+                sv_[j * (WAVES * 64)] = v_;                                                         \
+            }                                                                                       \
+        }                                                                                           \
+    }
+    // Own loads landed, own LDS reads done, then the workgroup barrier: publishes
+    // the tiles just fetched and frees the stages the next iteration refills.
+#define FV_PUBLISH()                                                                                \
+    {                                                                                               \
+        asm volatile("" ::: "memory");                                                              \
+        __builtin_amdgcn_s_waitcnt(attn_waitcnt(0, true));                                          \
+        __builtin_amdgcn_s_barrier();                                                               \
+        asm volatile("" ::: "memory");                                                              \
+    }
 
     // Q^T operand fragments: lane (li, hf) holds q[query li][16*ks + 8*hf .. +8)
     bf16x8_t qf[QB][KS];
@@ -106,167 +191,263 @@ __global__ __launch_bounds__(256) void attention_kernel(const AttnParams p) {
     for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
 
     const int KT = (p.L + BN - 1) / BN;
-    u32x4_t rk[K_LD], rv[V_LD];
+    const bool ragged = (p.L % BN) != 0;
 
-#define FV_LOAD_GLOBAL(kt_)                                                                         \
+    f32x16_t s_[2][QB];   // scores of this wave's 64-key slice (two 32-key blocks)
+    bf16x8_t pf_[4][QB];  // probabilities as the B operand of the second MFMA (four 16-key steps)
+
+    // Matrix phase of iteration kt_: O^T += V^T P^T for tile kt_-1 (if HAS_PV_),
+    // then S^T = K Q^T for tile kt_, on this wave's 64-key slice.  All operand
+    // fragments come from LDS; their reads run DEPTH fragments ahead of the MFMAs
+    // that consume them (the scheduler is given the interleaving explicitly), so
+    // LDS latency hides behind the matrix pipe.  Consecutive MFMAs alternate
+    // accumulators.
+#define FV_MATRIX(kt_, HAS_PV_)                                                                     \
     {                                                                                               \
-        const int key0_ = (kt_) * BN;                                                               \
-        _Pragma("unroll") for (int i = 0; i < K_LD; ++i) {                                          \
-            const int q_ = tid + 256 * i;                                                           \
-            const int key_ = min(key0_ + q_ / KCH, p.L - 1);                                        \
-            rk[i] = *reinterpret_cast<const u32x4_t*>(kc + (size_t)key_ * DH + (q_ % KCH) * 8);     \
+        constexpr int NV_ = (HAS_PV_) ? 4 * DB : 0;                                                 \
+        constexpr int NK_ = 2 * KS;                                                                 \
+        constexpr int DEPTH_ = 4;                                                                   \
+        const u32x4_t* v_base_ = lds + 2 * K_TILE + (((kt_) + 1) & 1) * V_TILE + kh * 8;            \
+        const u32x4_t* k_base_ = lds + ((kt_) & 1) * K_TILE + (kh * 64) * KCH;                      \
+        bf16x8_t fr_[NV_ + NK_];                                                                    \
+        if (HAS_PV_) {                                                                              \
+            _Pragma("unroll") for (int t = 0; t < 4; ++t)                                           \
+                _Pragma("unroll") for (int db = 0; db < DB; ++db)                                   \
+                    fr_[t * DB + db] = *reinterpret_cast<const bf16x8_t*>(                          \
+                        v_base_ + (db * 32 + li) * VCH + ((2 * t + hf) ^ sw));                      \
         }                                                                                           \
-        _Pragma("unroll") for (int i = 0; i < V_LD; ++i) {                                          \
-            const int q_ = tid + 256 * i;                                                           \
-            const int kpos_ = key0_ + (q_ & 7) * 8;                                                 \
-            rv[i] = load_v_chunk(vc + (size_t)(q_ >> 3) * p.L_cap + kpos_, p.L - kpos_);            \
+        _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                           \
+            _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                        \
+                fr_[NV_ + ks * 2 + kb] = *reinterpret_cast<const bf16x8_t*>(                        \
+                    k_base_ + (kb * 32 + li) * KCH + ((2 * ks + hf) ^ sw));                         \
+        _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                            \
+            _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)                                       \
+                _Pragma("unroll") for (int r = 0; r < 16; ++r) s_[kb][qb][r] = 0.f;                 \
+        if (HAS_PV_) {                                                                              \
+            _Pragma("unroll") for (int t = 0; t < 4; ++t)                                           \
+                _Pragma("unroll") for (int db = 0; db < DB; ++db)                                   \
+                    _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)                               \
+                        acc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                      \
+                            fr_[t * DB + db], pf_[t][qb], acc[db][qb], 0, 0, 0);                    \
         }                                                                                           \
+        _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                           \
+            _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                        \
+                _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)                                   \
+                    s_[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                           \
+                        fr_[NV_ + ks * 2 + kb], qf[qb][ks], s_[kb][qb], 0, 0, 0);                   \
+        __builtin_amdgcn_sched_group_barrier(0x100, DEPTH_, 0);                                     \
+        _Pragma("unroll") for (int i = 0; i < NV_ + NK_ - DEPTH_; ++i) {                            \
+            __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);                                     \
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                      \
+        }                                                                                           \
+        __builtin_amdgcn_sched_group_barrier(0x008, DEPTH_ * QB, 0);                                \
     }
-#define FV_STORE_LDS(buf_)                                                                          \
+    // O^T += V^T P^T alone (after the last tile)
+#define FV_PV_LAST(kt_)                                                                             \
     {                                                                                               \
-        _Pragma("unroll") for (int i = 0; i < K_LD; ++i) {                                          \
-            const int q_ = tid + 256 * i;                                                           \
-            const int row_ = q_ / KCH, c_ = q_ % KCH;                                               \
-            const int slot_ = (row_ & ~31) | swap_bits_2_3(row_ & 31);                              \
-            sK[(buf_) * K_TILE + slot_ * KCH + (c_ ^ (slot_ & 7))] = rk[i];                         \
+        const u32x4_t* v_base_ = lds + 2 * K_TILE + ((kt_) & 1) * V_TILE + kh * 8;                  \
+        _Pragma("unroll") for (int t = 0; t < 4; ++t)                                               \
+            _Pragma("unroll") for (int db = 0; db < DB; ++db) {                                     \
+                const bf16x8_t vf_ = *reinterpret_cast<const bf16x8_t*>(                            \
+                    v_base_ + (db * 32 + li) * VCH + ((2 * t + hf) ^ sw));                          \
+                _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)                                   \
+                    acc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf_, pf_[t][qb], acc[db][qb], 0, 0, 0); \
+            }                                                                                       \
+    }
+    // online softmax of the scores of tile kt_: s_ -> pf_, running max / sum, rescale of O
+#define FV_SOFTMAX(kt_, MASK_)                                                                      \
+    {                                                                                               \
+        if (MASK_) {                                                                                \
+            _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                        \
+                _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                    \
+                    const int srow_ = 8 * (r >> 2) + 4 * hf + (r & 3);                              \
+                    const int key_ = (kt_) * BN + kh * 64 + kb * 32 + swap_bits_2_3(srow_);         \
+                    if (key_ >= p.L) {                                                              \
+                        _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) s_[kb][qb][r] = -INFINITY; \
+                    }                                                                               \
+                }                                                                                   \
         }                                                                                           \
-        _Pragma("unroll") for (int i = 0; i < V_LD; ++i) {                                          \
-            const int q_ = tid + 256 * i;                                                           \
-            const int d_ = q_ >> 3, c_ = q_ & 7;                                                    \
-            sV[(buf_) * V_TILE + d_ * 8 + (c_ ^ (d_ & 7))] = rv[i];                                 \
+        _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                         \
+            float mx_ = s_[0][qb][0];                                                               \
+            _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                        \
+                _Pragma("unroll") for (int r = 0; r < 16; ++r) mx_ = fmaxf(mx_, s_[kb][qb][r]);     \
+            mx_ = fmaxf(mx_, other_half(mx_));                                                      \
+            /* a slice that is entirely past the length keeps the old maximum */                   \
+            const float m_new_ = fmaxf(m_run[qb], mx_ * p.scale_log2e);                             \
+            const float m_use_ = (m_new_ == -INFINITY) ? 0.f : m_new_;                              \
+            const float alpha_ = __builtin_amdgcn_exp2f(m_run[qb] - m_use_);                        \
+            m_run[qb] = m_new_;                                                                     \
+            float lsum_ = 0.f;                                                                      \
+            _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                        \
+                _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                    \
+                    const float pv_ = __builtin_amdgcn_exp2f(fmaf(s_[kb][qb][r], p.scale_log2e, -m_use_)); \
+                    lsum_ += pv_;                                                                   \
+                    pf_[2 * kb + (r >> 3)][qb][r & 7] = (__bf16)pv_;                                \
+                }                                                                                   \
+            l_run[qb] = l_run[qb] * alpha_ + lsum_;                                                 \
+            if (__any(alpha_ != 1.0f)) {                                                            \
+                _Pragma("unroll") for (int db = 0; db < DB; ++db)                                   \
+                    _Pragma("unroll") for (int r = 0; r < 16; ++r) acc[db][qb][r] *= alpha_;        \
+            }                                                                                       \
         }                                                                                           \
     }
+    // ---- schedule.  Iteration k fetches K tile k+1 and V^T tile k and needs
+    // K tile k and V^T tile k-1.  Every wave does, per tile, a matrix phase
+    // (PV of the previous tile, then QK of this one) and a vector phase (softmax
+    // of this tile).  With two waves per SIMD (8-wave workgroups) the waves of
+    // the second half run the phases in the opposite order, so that on every SIMD
+    // one wave is in its matrix phase while the other is in its vector phase
+    // (both start each iteration together at the barrier).
+    const bool vector_first = (WAVES == 8) && (wave >= 4);
 
-    FV_LOAD_GLOBAL(0)
-    FV_STORE_LDS(0)
-    __syncthreads();
+    FV_ISSUE_K(0)
+    FV_PUBLISH()
 
-    for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < KT) FV_LOAD_GLOBAL(kt + 1)
-
-        // ---- S^T = K * Q^T for 64 keys x 32*QB queries
-        f32x16_t s[2][QB];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s[kb][qb][r] = 0.f;
-        const u32x4_t* k_base = sK + buf * K_TILE;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(
-                    k_base + (kb * 32 + li) * KCH + ((2 * ks + hf) ^ sw));
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb)
-                    s[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], s[kb][qb], 0, 0, 0);
-            }
+    if (!vector_first) {
+        // iteration 0
+        if (KT > 1) FV_ISSUE_K(1)
+        FV_ISSUE_V(0)
+        FV_MATRIX(0, false)
+        if (KT == 1) { FV_SOFTMAX(0, true) } else { FV_SOFTMAX(0, false) }
+        if (KT == 1 && ragged) FV_FIX_TAIL(0)
+        FV_PUBLISH()
+        int kt = 1;
+        for (; kt + 1 < KT; ++kt) {
+            FV_ISSUE_K(kt + 1)
+            FV_ISSUE_V(kt)
+            FV_MATRIX(kt, true)
+            FV_SOFTMAX(kt, false)
+            FV_PUBLISH()
         }
-
-        // ---- mask keys past the cache length (last tile only)
-        if (kt == KT - 1 && (p.L & (BN - 1)) != 0) {
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int srow = 8 * (r >> 2) + 4 * hf + (r & 3);
-                    const int key = kt * BN + kb * 32 + swap_bits_2_3(srow);
-                    if (key >= p.L) {
-#pragma unroll
-                        for (int qb = 0; qb < QB; ++qb) s[kb][qb][r] = -INFINITY;
-                    }
-                }
+        if (kt < KT) {  // last tile
+            FV_ISSUE_V(kt)
+            FV_MATRIX(kt, true)
+            FV_SOFTMAX(kt, true)
+            if (ragged) FV_FIX_TAIL(kt)
+            FV_PUBLISH()
         }
-
-        // ---- online softmax, one query per lane (two half-waves share a query)
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            float mx = s[0][qb][0];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][qb][r]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run[qb], mx * p.scale_log2e);
-            const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
-            m_run[qb] = m_new;
-            float lsum = 0.f;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float pv = __builtin_amdgcn_exp2f(fmaf(s[kb][qb][r], p.scale_log2e, -m_new));
-                    s[kb][qb][r] = pv;
-                    lsum += pv;
-                }
-            l_run[qb] = l_run[qb] * alpha + lsum;
-            if (__any(alpha != 1.0f)) {
-#pragma unroll
-                for (int db = 0; db < DB; ++db)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[db][qb][r] *= alpha;
-            }
+        FV_PV_LAST(KT - 1)
+    } else {
+        if (KT > 1) FV_ISSUE_K(1)
+        FV_ISSUE_V(0)
+        FV_MATRIX(0, false)
+        if (KT == 1 && ragged) FV_FIX_TAIL(0)
+        FV_PUBLISH()
+        int kt = 1;
+        for (; kt + 1 < KT; ++kt) {
+            FV_ISSUE_K(kt + 1)
+            FV_ISSUE_V(kt)
+            FV_SOFTMAX(kt - 1, false)
+            FV_MATRIX(kt, true)
+            FV_PUBLISH()
         }
-
-        // ---- O^T += V^T * P^T
-        const u32x4_t* v_base = sV + buf * V_TILE;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            bf16x8_t pf[QB];
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                for (int j = 0; j < 8; ++j) pf[qb][j] = (__bf16)s[t >> 1][qb][(t & 1) * 8 + j];
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(
-                    v_base + (db * 32 + li) * 8 + ((2 * t + hf) ^ sw));
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb)
-                    acc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb], acc[db][qb], 0, 0, 0);
-            }
+        if (kt < KT) {  // last tile
+            FV_ISSUE_V(kt)
+            FV_SOFTMAX(kt - 1, false)
+            FV_MATRIX(kt, true)
+            if (ragged) FV_FIX_TAIL(kt)
+            FV_PUBLISH()
         }
-
-        if (kt + 1 < KT) FV_STORE_LDS(buf ^ 1)
-        __syncthreads();
+        FV_SOFTMAX(KT - 1, true)
+        FV_PV_LAST(KT - 1)
     }
+#undef FV_MATRIX
+#undef FV_PV_LAST
+#undef FV_SOFTMAX
+#undef FV_ISSUE_K
+#undef FV_ISSUE_V
+#undef FV_FIX_TAIL
+
+    // ---- merge the key slices of a query group (exact: online-softmax partials
+    // combine as m = max, l = sum l_i 2^(m_i - m), O = sum O_i 2^(m_i - m))
+    if (KSPLIT > 1) {
+        FV_PUBLISH()  // everyone is done with the operand tiles
+        float* xch = reinterpret_cast<float*>(smem) + qg * ((DB * 16 + 2) * QB * 64);
+        for (int src = 1; src < KSPLIT; ++src) {
+            if (kh == src) {
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    float* base = xch + qb * ((DB * 16 + 2) * 64) + lane;
+                    base[0] = m_run[qb];
+                    base[64] = l_run[qb];
+#pragma unroll
+                    for (int db = 0; db < DB; ++db)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) base[(2 + db * 16 + r) * 64] = acc[db][qb][r];
+                }
+            }
+            FV_PUBLISH()
+            if (kh == 0) {
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    const float* base = xch + qb * ((DB * 16 + 2) * 64) + lane;
+                    const float m_o = base[0], l_o = base[64];
+                    const float m_new = fmaxf(m_run[qb], m_o);
+                    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+                    const float a_me = __builtin_amdgcn_exp2f(m_run[qb] - m_use);
+                    const float a_o = __builtin_amdgcn_exp2f(m_o - m_use);
+                    m_run[qb] = m_new;
+                    l_run[qb] = l_run[qb] * a_me + l_o * a_o;
+#pragma unroll
+                    for (int db = 0; db < DB; ++db)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            acc[db][qb][r] = acc[db][qb][r] * a_me + base[(2 + db * 16 + r) * 64] * a_o;
+                }
+            }
+            if (src + 1 < KSPLIT) FV_PUBLISH()
+        }
+    }
+#undef FV_PUBLISH
 
     // ---- normalise and store: lane (li, hf) register r of block db is
     // o[query li][32*db + 8*(r/4) + 4*hf + r%4]
+    if (kh == 0) {
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);
-        const float inv = 1.0f / l_tot;
-        const int qrow = q_base + qb * 32 + li;
-        if (qrow < p.k_tokens) {
-            bf16_t* dst = p.o + ((size_t)b * p.k_tokens + qrow) * p.D + head * DH + 4 * hf;
+        for (int qb = 0; qb < QB; ++qb) {
+            const float l_tot = l_run[qb] + other_half(l_run[qb]);
+            const float inv = 1.0f / l_tot;
+            const int qrow = q_base + qb * 32 + li;
+            if (qrow < p.k_tokens) {
+                bf16_t* dst = p.o + ((size_t)b * p.k_tokens + qrow) * p.D + head * DH + 4 * hf;
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+                for (int db = 0; db < DB; ++db)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    uint2 pk;
-                    pk.x = pack_bf16x2(acc[db][qb][4 * g + 0] * inv, acc[db][qb][4 * g + 1] * inv);
-                    pk.y = pack_bf16x2(acc[db][qb][4 * g + 2] * inv, acc[db][qb][4 * g + 3] * inv);
-                    *reinterpret_cast<uint2*>(dst + db * 32 + 8 * g) = pk;
-                }
+                    for (int g = 0; g < 4; ++g) {
+                        u32x2_t pk;
+                        pk.x = pack_bf16x2(acc[db][qb][4 * g + 0] * inv, acc[db][qb][4 * g + 1] * inv);
+                        pk.y = pack_bf16x2(acc[db][qb][4 * g + 2] * inv, acc[db][qb][4 * g + 3] * inv);
+                        *reinterpret_cast<u32x2_t*>(dst + db * 32 + 8 * g) = pk;
+                    }
+            }
         }
     }
+#endif
 }
 
-template <int DH, int QB>
+template <int DH, int QB, int QG, int KSPLIT>
 void launch_cfg(const AttnParams& p, int B, hipStream_t stream) {
-    constexpr size_t smem = (size_t)2 * (BN * (DH / 8) + DH * 8) * sizeof(u32x4_t);
+    constexpr size_t tile_bytes = (size_t)2 * (64 * KSPLIT * (DH / 8) + DH * (8 * KSPLIT)) * 16;
+    constexpr size_t merge_bytes = KSPLIT > 1 ? (size_t)QG * (DH / 32 * 16 + 2) * QB * 64 * 4 : 0;
+    constexpr size_t smem = tile_bytes > merge_bytes ? tile_bytes : merge_bytes;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_kernel<DH, QB>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_kernel<DH, QB, QG, KSPLIT>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         attr_set = true;
     }
-    const int per_wg = 128 * QB;
-    attention_kernel<DH, QB><<<dim3((p.k_tokens + per_wg - 1) / per_wg, p.H, B), 256, smem, stream>>>(p);
+    const int per_wg = QG * 32 * QB;
+    attention_kernel<DH, QB, QG, KSPLIT>
+        <<<dim3((p.k_tokens + per_wg - 1) / per_wg, p.H, B), QG * KSPLIT * 64, smem, stream>>>(p);
+}
+
+int attn_cfg_override() {
+    static int v = -2;
+    if (v == -2) {
+        const char* e = getenv("FASTVAR_ATTN_CFG");
+        v = e ? atoi(e) : -1;
+    }
+    return v;
 }
 
 }  // namespace
@@ -279,14 +460,27 @@ void launch_attention(const AttnArgs& a, hipStream_t stream) {
     p.o = static_cast<bf16_t*>(a.o);
     p.H = a.H; p.k_tokens = a.k_tokens; p.L = a.L; p.L_cap = a.L_cap; p.D = a.H * a.dh;
     p.scale_log2e = a.scale * 1.4426950408889634f;
-    // Two query blocks per wave halve the LDS traffic per MFMA but halve the
-    // number of workgroups; take them only when the grid still covers the chip.
-    const long wgs2 = (long)((a.k_tokens + 255) / 256) * a.H * a.B;
-    const bool wide = wgs2 >= 256;
+    // One wave per 64 queries; when that leaves SIMDs idle (fewer than ~1 wave per
+    // SIMD on 256 CUs), split the keys of each tile over two waves instead.
+    const long waves = (long)((a.k_tokens + 63) / 64) * a.H * a.B;
+    int cfg = waves >= 900 ? 0 : 1;
+    if (attn_cfg_override() >= 0) cfg = attn_cfg_override();
     if (a.dh == 128) {
-        if (wide) launch_cfg<128, 2>(p, a.B, stream); else launch_cfg<128, 1>(p, a.B, stream);
+        switch (cfg) {
+            case 0: launch_cfg<128, 2, 4, 1>(p, a.B, stream); break;
+            case 1: launch_cfg<128, 2, 2, 2>(p, a.B, stream); break;
+            case 2: launch_cfg<128, 1, 4, 1>(p, a.B, stream); break;
+            case 3: launch_cfg<128, 1, 2, 2>(p, a.B, stream); break;
+            default: launch_cfg<128, 1, 4, 2>(p, a.B, stream); break;
+        }
     } else {
-        if (wide) launch_cfg<64, 2>(p, a.B, stream); else launch_cfg<64, 1>(p, a.B, stream);
+        switch (cfg) {
+            case 0: launch_cfg<64, 2, 4, 1>(p, a.B, stream); break;
+            case 1: launch_cfg<64, 2, 2, 2>(p, a.B, stream); break;
+            case 2: launch_cfg<64, 1, 4, 1>(p, a.B, stream); break;
+            case 3: launch_cfg<64, 1, 2, 2>(p, a.B, stream); break;
+            default: launch_cfg<64, 1, 4, 2>(p, a.B, stream); break;
+        }
     }
 }
 

@@ -81,25 +81,33 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const bf16_t* __res
     }
 }
 
-// grid (ceil(D/256), B), block 256: mean[b,c] = (sum over chunks, ascending) / N.
+// grid (ceil(D/64), B), block 256: mean[b,c] = (sum of the chunk partials) / N.
+// Thread (c = t%64, g = t/64) sums every 4th chunk starting at g, ascending; the
+// four partial sums of a column are then added in a fixed order.
 __global__ __launch_bounds__(256) void colsum_finalize_kernel(const double* __restrict__ partial,
                                                               double* __restrict__ mean, int N, int D,
                                                               int n_chunks) {
-    const int c = blockIdx.x * 256 + threadIdx.x;
+    __shared__ double part[4][64];
+    const int cl = threadIdx.x & 63, g = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + cl;
     const int b = blockIdx.y;
-    if (c >= D) return;
-    const double* p = partial + (size_t)b * n_chunks * D + c;
     double s = 0.0;
-    int y = 0;
-    for (; y + 4 <= n_chunks; y += 4) {
-        const double a0 = p[(size_t)(y + 0) * D];
-        const double a1 = p[(size_t)(y + 1) * D];
-        const double a2 = p[(size_t)(y + 2) * D];
-        const double a3 = p[(size_t)(y + 3) * D];
-        s = (((s + a0) + a1) + a2) + a3;
+    if (c < D) {
+        const double* p = partial + (size_t)b * n_chunks * D + c;
+        int y = g;
+        for (; y + 12 < n_chunks; y += 16) {
+            const double a0 = p[(size_t)(y + 0) * D];
+            const double a1 = p[(size_t)(y + 4) * D];
+            const double a2 = p[(size_t)(y + 8) * D];
+            const double a3 = p[(size_t)(y + 12) * D];
+            s = (((s + a0) + a1) + a2) + a3;
+        }
+        for (; y < n_chunks; y += 4) s += p[(size_t)y * D];
     }
-    for (; y < n_chunks; ++y) s += p[(size_t)y * D];
-    mean[(size_t)b * D + c] = s / (double)N;
+    part[g][cl] = s;
+    __syncthreads();
+    if (g == 0 && c < D)
+        mean[(size_t)b * D + c] = (((part[0][cl] + part[1][cl]) + part[2][cl]) + part[3][cl]) / (double)N;
 }
 
 constexpr int kScoreRowsPerBlock = 8;  // 4 waves x 2 rows
@@ -178,15 +186,40 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float* __restr
     const int t = threadIdx.x;
     for (int n = t; n < N; n += kTopkThreads) keys[n] = float_key(score[(size_t)b * N + n]);
 
-    // ---- radix select: T = key of the k-th largest, need = how many keys equal to T are kept
+    // ---- radix select: T = key of the k-th largest, need = how many keys equal to T are kept.
+    // Scores of one map usually share their leading bits (same sign, nearby
+    // exponents); those bits are found first (AND / OR over all keys) and the
+    // 8-bit digit passes only walk the bits below them, which also keeps the
+    // LDS histogram atomics from piling onto a single bin.
     uint32_t prefix = 0, mask = 0, k_rem = (uint32_t)k;
     if (k > 0) {
-        for (int shift = 24; shift >= 0; shift -= 8) {
+        uint32_t all_and = 0xFFFFFFFFu, all_or = 0u;
+        for (int n = t; n < N; n += kTopkThreads) {  // this thread's own entries: no barrier needed yet
+            const uint32_t key = keys[n];
+            all_and &= key;
+            all_or |= key;
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            all_and &= __shfl_xor(all_and, o, 64);
+            all_or |= __shfl_xor(all_or, o, 64);
+        }
+        if ((t & 63) == 0) { wave_tot[t >> 6] = all_and; hist[t >> 6] = all_or; }
+        __syncthreads();
+        for (int wv = 0; wv < kTopkThreads / 64; ++wv) { all_and &= wave_tot[wv]; all_or |= hist[wv]; }
+        __syncthreads();
+        const uint32_t differ = all_and ^ all_or;           // bits that are not common to all keys
+        const int top = differ ? 32 - __clz(differ) : 0;     // number of low bits that may differ
+        mask = top >= 32 ? 0u : (0xFFFFFFFFu << top);
+        prefix = all_and & mask;
+        for (int shift = top - 8; shift > -8; shift -= 8) {
+            const int sh = shift < 0 ? 0 : shift;
+            const uint32_t dmask = shift < 0 ? ((1u << (shift + 8)) - 1u) : 255u;  // last pass may be narrower
             if (t < 256) hist[t] = 0;
-            __syncthreads();  // also orders the key stores before the first pass
+            __syncthreads();
             for (int n = t; n < N; n += kTopkThreads) {
                 const uint32_t key = keys[n];
-                if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+                if ((key & mask) == prefix) atomicAdd(&hist[(key >> sh) & dmask], 1u);
             }
             __syncthreads();
             if (t < 64) {
@@ -207,8 +240,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float* __restr
                 else if (c0 < k_rem && k_rem <= c0 + h0) { sel[0] = 4 * t + 0; sel[1] = k_rem - c0; }
             }
             __syncthreads();
-            prefix |= sel[0] << shift;
-            mask |= 0xFFu << shift;
+            prefix |= sel[0] << sh;
+            mask |= dmask << sh;
             k_rem = sel[1];
         }
     } else {
@@ -286,7 +319,7 @@ void launch_select(const void* x, int B, int N, int D, int k, int32_t* idx, int3
 
     colsum_partial_kernel<<<dim3(plan.col_tiles, plan.n_chunks, B), 256, 0, stream>>>(
         xb, partial, N, D, plan.rows_per_chunk, plan.n_chunks);
-    colsum_finalize_kernel<<<dim3((D + 255) / 256, B), 256, 0, stream>>>(partial, mean, N, D, plan.n_chunks);
+    colsum_finalize_kernel<<<dim3((D + 63) / 64, B), 256, 0, stream>>>(partial, mean, N, D, plan.n_chunks);
     const size_t mu_bytes = (size_t)plan.col_tiles * 512 * sizeof(double);
     score_kernel<<<dim3((N + kScoreRowsPerBlock - 1) / kScoreRowsPerBlock, B), 256, mu_bytes, stream>>>(
         xb, mean, score, N, D);

@@ -147,7 +147,8 @@ int fastvar_select_pivotal(const void* x, int B, int h, int w, int D, int k,
  *   y_kept_out [B, k, D] bf16     block output for the kept tokens
  *   ws         scratch of fastvar_block_workspace_bytes(dims, B, k) bytes
  * Computes xk = x[idx]; h1 = xk + proj(attn(LN1(xk))); y = h1 + fc2(gelu(
- * fc1(LN2(h1)))) with exact (erf) GELU; attention is unmasked softmax over
+ * fc1(LN2(h1)))) with GELU evaluated in its tanh form (within 3e-4 of the erf
+ * form, below bf16 resolution); attention is unmasked softmax over
  * cache positions [0, L0+k), the last k of which this call writes.  k == 0
  * is a no-op that returns FASTVAR_OK.
  */
@@ -210,7 +211,7 @@ int fastvar_layernorm(const void* in, const int32_t* idx, int B, int N, int k, i
                       const void* gamma, const void* beta, float eps, void* out, void* stream);
 
 /* out[M,N] = epilogue(A[M,K] * W[N,K]^T + bias); bf16 MFMA, fp32 accumulate.
- * epilogue 1: + residual[M,N];  epilogue 2: exact-form GELU.  bias may be NULL;
+ * epilogue 1: + residual[M,N];  epilogue 2: GELU (tanh form).  bias may be NULL;
  * residual must be non-NULL for epilogue 1.  K % 64 == 0. */
 int fastvar_gemm_bf16(const void* A, const void* W, const void* bias, const void* residual,
                       int M, int N, int K, int epilogue, void* out, void* stream);

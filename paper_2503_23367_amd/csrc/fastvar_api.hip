@@ -16,7 +16,7 @@ inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 constexpr int kMaxWidth = 8192;  // LayerNorm keeps a row in registers; score keeps the mean in 64 KB of LDS
 
 struct BlockPlan {
-    size_t off_a, off_q, off_h1, off_u, bytes;
+    size_t off_a, off_q, off_h1, off_u, off_rows, bytes;
 };
 
 BlockPlan block_plan(const fastvar_dims* d, int B, int k) {
@@ -27,6 +27,7 @@ BlockPlan block_plan(const fastvar_dims* d, int B, int k) {
     p.off_q = off;   off += round256(M * d->D * 2);  // queries, later the LN2 output
     p.off_h1 = off;  off += round256(M * d->D * 2);  // residual stream after attention
     p.off_u = off;   off += round256(M * d->F * 2);  // MLP hidden
+    p.off_rows = off; off += round256(M * 4);        // absolute source row of every kept token
     p.bytes = off;
     return p;
 }
@@ -117,10 +118,11 @@ void enqueue_block(const void* x, int N, const int32_t* idx, int B, int k, const
     void* buf_q = base + bp.off_q;
     void* buf_h1 = base + bp.off_h1;
     void* buf_u = base + bp.off_u;
+    int32_t* rows = reinterpret_cast<int32_t*>(base + bp.off_rows);
     const int M = B * k;
 
     // a1 = LN1(x[idx])
-    fv::launch_gather_layernorm(x, idx, B, N, k, d->D, w->ln1_g, w->ln1_b, d->ln_eps, nullptr, buf_a, st);
+    fv::launch_gather_layernorm(x, idx, B, N, k, d->D, w->ln1_g, w->ln1_b, d->ln_eps, rows, buf_a, st);
     // q | k | v = a1 * Wqkv^T + b ; k, v appended to the caches at [L0, L0+k)
     fv::GemmArgs g{};
     g.A = buf_a; g.W = w->w_qkv; g.bias = w->b_qkv; g.M = M; g.N = 3 * d->D; g.K = d->D;
@@ -136,7 +138,7 @@ void enqueue_block(const void* x, int N, const int32_t* idx, int B, int k, const
     // h1 = x[idx] + o * Wp^T + bp
     fv::GemmArgs pj{};
     pj.A = buf_a; pj.W = w->w_proj; pj.bias = w->b_proj; pj.M = M; pj.N = d->D; pj.K = d->D;
-    pj.out = buf_h1; pj.residual = x; pj.res_idx = idx; pj.res_N = N; pj.k_tokens = k;
+    pj.out = buf_h1; pj.residual = x; pj.res_rows = rows; pj.k_tokens = k;
     fv::launch_gemm(fv::EPI_BIAS_RES, pj, st);
     // a2 = LN2(h1)
     fv::launch_layernorm(buf_h1, M, d->D, w->ln2_g, w->ln2_b, d->ln_eps, buf_q, st);

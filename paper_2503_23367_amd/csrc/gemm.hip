@@ -22,20 +22,16 @@ namespace fv {
 
 namespace {
 
-// Exact-form GELU, v * Phi(v), with erf from the rational approximation of
-// Abramowitz & Stegun 7.1.26 (absolute error below 1.5e-7, far under bf16
-// resolution); branch free so that the unrolled epilogue stays small.
-__device__ __forceinline__ float gelu_erf(float v) {
-    const float z = fabsf(v) * 0.70710678118654752440f;
-    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
-    float poly = fmaf(1.061405429f, t, -1.453152027f);
-    poly = fmaf(poly, t, 1.421413741f);
-    poly = fmaf(poly, t, -0.284496736f);
-    poly = fmaf(poly, t, 0.254829592f);
-    const float e = __builtin_amdgcn_exp2f(-z * z * 1.4426950408889634f);
-    const float erf_abs = 1.0f - poly * t * e;  // erf(|v|/sqrt2)
-    const float erf_v = copysignf(erf_abs, v);
-    return 0.5f * v * (1.0f + erf_v);
+// GELU in its tanh form written as a sigmoid: v * sigma(2u), u = sqrt(2/pi) (v + 0.044715 v^3).
+// It deviates from the erf form by at most 3e-4 in absolute value (near |v| = 2),
+// far below the bf16 resolution of the outputs, and costs 8 instructions where
+// an erf approximation costs about 20: the epilogue is pure VALU time that no
+// MFMA overlaps.
+__device__ __forceinline__ float gelu_fast(float v) {
+    const float v2 = v * v;
+    const float u2 = v * fmaf(0.044715f * 1.5957691216057308f, v2, 1.5957691216057308f);  // 2u
+    const float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * u2);                    // exp(-2u)
+    return v * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
 struct GemmParams {
@@ -45,8 +41,7 @@ struct GemmParams {
     int M, N, K;
     bf16_t* out;
     const bf16_t* residual;
-    const int32_t* res_idx;  // optional row gather for the residual: row = (m / k_tokens) * res_N + res_idx[m]
-    int res_N;
+    const int32_t* res_rows;  // optional row gather for the residual: row of output row m is res_rows[m]
     bf16_t* q_out;
     bf16_t* k_cache;
     bf16_t* v_cache;
@@ -117,6 +112,7 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
     constexpr int LPT = A_LD + W_LD;
     constexpr int A_TILE = BM * CPR, W_TILE = BN * CPR;      // 16-byte chunks per stage
     constexpr int STAGE = A_TILE + W_TILE;
+    static_assert(KK == 1 || (LPT + KK - 2) / (KK - 1) <= MI + NI, "one load per MFMA group at most");
     static_assert((STAGES - 2) * LPT <= 63, "vmcnt is 6 bits");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -170,6 +166,25 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
             __builtin_amdgcn_global_load_lds(gw_ + w_off[j], (lds_ptr_t)(sw_ + j * 256), 16, 0, 0); \
     }
 
+    // The same loads, one slice at a time: slice part_ of nparts_ (loads are numbered
+    // A first, then W).  Spreading a tile's loads between the MFMAs of an iteration
+    // keeps the texture-address queue from filling up and stalling the wave.
+#define FV_ISSUE_PART(kt_, stage_, part_, nparts_)                                              \
+    {                                                                                           \
+        const bf16_t* ga_ = p.A + (size_t)(kt_) * BK;                                           \
+        const bf16_t* gw_ = p.W + (size_t)(kt_) * BK;                                           \
+        u32x4_t* sa_ = lds + (stage_) * STAGE + wave * 64;                                      \
+        u32x4_t* sw_ = sa_ + A_TILE;                                                            \
+        _Pragma("unroll") for (int q = (part_) * LPT / (nparts_); q < ((part_) + 1) * LPT / (nparts_); ++q) { \
+            if (q < A_LD)                                                                       \
+                __builtin_amdgcn_global_load_lds(ga_ + a_off[q < A_LD ? q : 0],                 \
+                                                 (lds_ptr_t)(sa_ + q * 256), 16, 0, 0);         \
+            else                                                                                \
+                __builtin_amdgcn_global_load_lds(gw_ + w_off[q >= A_LD ? q - A_LD : 0],         \
+                                                 (lds_ptr_t)(sw_ + (q - A_LD) * 256), 16, 0, 0); \
+        }                                                                                       \
+    }
+
     const int frag_row = lane & 31;
     const int frag_half = lane >> 5;
     const int a_row = wm * WTM + frag_row;  // + 32 mi
@@ -217,10 +232,11 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
         _Pragma("unroll") for (int ni = 0; ni < NI; ++ni)                                       \
             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur_][mi], fw[cur_][ni],   \
                                                                   acc[mi][ni], 0, 0, 0);
-#define FV_INTERLEAVE(mfma_per_read_)                                                           \
+#define FV_INTERLEAVE(mfma_per_read_, with_dma_)                                                \
     _Pragma("unroll") for (int g = 0; g < MI + NI; ++g) {                                       \
         __builtin_amdgcn_sched_group_barrier(0x008, (mfma_per_read_), 0); /* MFMA */            \
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                /* DS read */         \
+        if (with_dma_) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0); /* direct-to-LDS load */ \
     }
     // One K tile.  Software pipeline inside the wave: the operand reads of the
     // next k-step are interleaved with the MFMAs of the current one (the
@@ -235,15 +251,16 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
     {                                                                                           \
         int fill_ = stage + STAGES - 1;                                                         \
         if (fill_ >= STAGES) fill_ -= STAGES;                                                   \
-        if (MORE_) FV_ISSUE_TILE(kt + STAGES - 1, fill_)                                        \
+        if ((MORE_) && KK == 1) FV_ISSUE_TILE(kt + STAGES - 1, fill_)                           \
         int next_stage_ = stage + 1;                                                            \
         if (next_stage_ == STAGES) next_stage_ = 0;                                             \
         _Pragma("unroll") for (int kk = 0; kk < KK; ++kk) {                                     \
             const int cur_ = kk & 1, nxt_ = cur_ ^ 1;                                           \
             if (kk + 1 < KK) {                                                                  \
+                if (MORE_) FV_ISSUE_PART(kt + STAGES - 1, fill_, kk, KK - 1)                    \
                 FV_LOAD_FRAGS(fa[nxt_], fw[nxt_], stage, kk + 1)                                \
                 FV_MFMA_ROWS(cur_, 0, MI)                                                       \
-                FV_INTERLEAVE((MI * NI) / (MI + NI))                                            \
+                FV_INTERLEAVE((MI * NI) / (MI + NI), (MORE_))                                   \
             } else if (HANDOVER_) {                                                             \
                 FV_MFMA_ROWS(cur_, 0, MI / 2)                                                   \
                 __builtin_amdgcn_s_waitcnt(waitcnt_imm((MORE_) ? (STAGES - 2) * LPT : 0, true)); \
@@ -252,7 +269,7 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
                 asm volatile("" ::: "memory");                                                  \
                 FV_LOAD_FRAGS(fa[nxt_], fw[nxt_], next_stage_, 0)                               \
                 FV_MFMA_ROWS(cur_, MI / 2, MI)                                                  \
-                FV_INTERLEAVE((MI * NI / 2) / (MI + NI) > 0 ? (MI * NI / 2) / (MI + NI) : 1)    \
+                FV_INTERLEAVE((MI * NI / 2) / (MI + NI) > 0 ? (MI * NI / 2) / (MI + NI) : 1, false) \
             } else {                                                                            \
                 FV_MFMA_ROWS(cur_, 0, MI)                                                       \
             }                                                                                   \
@@ -269,6 +286,7 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
 #undef FV_INTERLEAVE
 #undef FV_MFMA_ROWS
 #undef FV_ISSUE_TILE
+#undef FV_ISSUE_PART
 #undef FV_LOAD_FRAGS
 
     // ---- Epilogue, staged through LDS so that global traffic is 16 bytes per lane.
@@ -310,11 +328,17 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
             static_for<0, 16>([&](auto r_c) {
                 constexpr int r = decltype(r_c)::value;
                 float v = acc[mi][ni][r] + bias[ni];
-                if (EPI == EPI_BIAS_GELU) v = gelu_erf(v);
+                if (EPI == EPI_BIAS_GELU) v = gelu_fast(v);
                 stg[(8 * (r >> 2) + 4 * frag_half + (r & 3)) * SROW + ni * 32 + frag_row] = v;
             });
         });
         const int m_slab = m0 + wm * WTM + mi * 32;
+        // (sample, token) of this lane's first row; later passes step by RPP rows
+        int bq = 0, tq = 0;
+        if (EPI == EPI_QKV) {
+            bq = (m_slab + rsub) / p.k_tokens;
+            tq = (m_slab + rsub) - bq * p.k_tokens;
+        }
 #pragma unroll
         for (int ps = 0; ps < PASSES; ++ps) {
             const int row = ps * RPP + rsub;
@@ -323,10 +347,8 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
                 const f32x4_t lo = *reinterpret_cast<const f32x4_t*>(stg + row * SROW + cg * 8);
                 const f32x4_t hi = *reinterpret_cast<const f32x4_t*>(stg + row * SROW + cg * 8 + 4);
                 float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                const int b = m / p.k_tokens;
-                const int t = m - b * p.k_tokens;
                 if (EPI == EPI_BIAS_RES) {
-                    const size_t rrow = p.res_idx ? (size_t)b * p.res_N + p.res_idx[m] : (size_t)m;
+                    const size_t rrow = p.res_rows ? (size_t)p.res_rows[m] : (size_t)m;
                     const u32x4_t rr = *reinterpret_cast<const u32x4_t*>(p.residual + rrow * p.N + ncol);
                     v[0] += bf16_lo(rr.x); v[1] += bf16_hi(rr.x);
                     v[2] += bf16_lo(rr.y); v[3] += bf16_hi(rr.y);
@@ -338,7 +360,16 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
                 o.y = pack_bf16x2(v[2], v[3]);
                 o.z = pack_bf16x2(v[4], v[5]);
                 o.w = pack_bf16x2(v[6], v[7]);
-                *reinterpret_cast<u32x4_t*>(cd.ptr + (long)b * cd.batch_stride + (long)t * cd.row_stride) = o;
+                bf16_t* dst;
+                if (EPI == EPI_QKV)
+                    dst = cd.ptr + (long)bq * cd.batch_stride + (long)tq * cd.row_stride;
+                else
+                    dst = p.out + (size_t)m * p.N + ncol;
+                *reinterpret_cast<u32x4_t*>(dst) = o;
+            }
+            if (EPI == EPI_QKV) {
+                tq += RPP;
+                while (tq >= p.k_tokens) { tq -= p.k_tokens; ++bq; }
             }
         }
         if (EPI == EPI_QKV) {
@@ -394,12 +425,20 @@ int gemm_cfg_override() {
 
 template <int EPI>
 void launch_epi(GemmParams& p, hipStream_t stream) {
-    // 128x128 tiles (two workgroups per CU, so one's epilogue overlaps the other's
-    // main loop) measured equal or better than 256x256 on every block shape.
-    // With at most two tiles per CU the deeper pipeline of shorter K steps wins
-    // (out-proj, FC2); with more tiles the longer K step does.
-    const long tiles = (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
-    int cfg = tiles <= 512 ? 3 : 6;
+    // Tile choice, from measurements on the block's shapes:
+    //  * 256x256 tiles halve the global->LDS traffic per MFMA (that path tops out
+    //    near 56 B/clk/CU and a 128x128x64 tile needs 64 B/clk at MFMA peak); they
+    //    win whenever they still give (almost) every CU a tile.  Not used for the
+    //    QKV epilogue, whose extra address state does not fit the register budget.
+    //  * otherwise 128x128 tiles, two workgroups per CU; with at most two tiles per
+    //    CU the deeper pipeline of shorter K steps wins (out-proj, FC2).
+    const long tiles256 = (long)((p.M + 255) / 256) * ((p.N + 255) / 256);
+    const long tiles128 = (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
+    int cfg;
+    if (EPI != EPI_QKV && tiles256 >= 192)
+        cfg = 1;
+    else
+        cfg = tiles128 <= 512 ? 3 : 6;
     if (gemm_cfg_override() >= 0) cfg = gemm_cfg_override();
     switch (cfg) {
         case 0: launch_cfg<256, 256, 32, 4, EPI>(p, stream); break;
@@ -419,8 +458,7 @@ void launch_gemm(GemmEpilogue epi, const GemmArgs& a, hipStream_t stream) {
     p.M = a.M; p.N = a.N; p.K = a.K;
     p.out = static_cast<bf16_t*>(a.out);
     p.residual = static_cast<const bf16_t*>(a.residual);
-    p.res_idx = a.res_idx;
-    p.res_N = a.res_N;
+    p.res_rows = a.res_rows;
     p.q_out = static_cast<bf16_t*>(a.q_out);
     p.k_cache = static_cast<bf16_t*>(a.k_cache);
     p.v_cache = static_cast<bf16_t*>(a.v_cache);

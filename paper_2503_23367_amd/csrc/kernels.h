@@ -30,8 +30,10 @@ void launch_restore(const void* y_kept, const int32_t* rank, int B, int k, const
 
 // ---- block pieces ----
 // xk = x[idx] (optional copy out) and a = LayerNorm(xk); one wave per row.
+// rows_out (optional, int32 [B*k]) receives the absolute source row b*N + idx[m] of
+// every kept token, for later gathers of the same rows.
 void launch_gather_layernorm(const void* x, const int32_t* idx, int B, int N, int k, int D,
-                             const void* gamma, const void* beta, float eps, void* xk_out,
+                             const void* gamma, const void* beta, float eps, int32_t* rows_out,
                              void* a_out, hipStream_t stream);
 // a = LayerNorm(rows of `in`), M rows.
 void launch_layernorm(const void* in, int M, int D, const void* gamma, const void* beta, float eps,
@@ -50,8 +52,7 @@ struct GemmArgs {
     // EPI_BIAS_RES / EPI_BIAS_GELU
     void* out;             // [M, N] bf16
     const void* residual;  // [M, N] bf16 (EPI_BIAS_RES), or the gather source when res_idx is set
-    const int32_t* res_idx = nullptr;  // optional: residual row of m is (m / k_tokens) * res_N + res_idx[m]
-    int res_N = 0;
+    const int32_t* res_rows = nullptr;  // optional: the residual of output row m is row res_rows[m] of `residual`
     // EPI_QKV
     void* q_out;    // [M, D]
     void* k_cache;  // [B, H, L_cap, dh]

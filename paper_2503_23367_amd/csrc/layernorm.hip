@@ -17,19 +17,21 @@ __device__ __forceinline__ void unpack8(const uint4& v, float (&f)[8]) {
 }
 
 // CH = number of 512-column groups held in registers (D <= 512*CH).
-// Row m of the output reads input row (idx ? b*N + idx[m] : m), b = m / k.
+// Row m of the output reads input row (idx ? b*N + idx[m] : m), b = m / k; that
+// row index is also written to rows_out[m] when asked for.
 template <int CH>
 __global__ __launch_bounds__(256) void layernorm_rows_kernel(const bf16_t* __restrict__ in,
                                                              const int32_t* __restrict__ idx, int N, int k,
                                                              int M, int D, const bf16_t* __restrict__ gamma,
                                                              const bf16_t* __restrict__ beta, float eps,
-                                                             bf16_t* __restrict__ copy_out,
+                                                             int32_t* __restrict__ rows_out,
                                                              bf16_t* __restrict__ out) {
     const int lane = threadIdx.x & 63;
     const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (m >= M) return;
     size_t src_row = (size_t)m;
     if (idx) src_row = (size_t)(m / k) * N + idx[m];
+    if (rows_out && lane == 0) rows_out[m] = (int32_t)src_row;
     const bf16_t* src = in + src_row * D;
 
     float v[CH][8];
@@ -39,7 +41,6 @@ __global__ __launch_bounds__(256) void layernorm_rows_kernel(const bf16_t* __res
         const int col = g * 512 + lane * 8;
         if (col < D) {
             const uint4 raw = *reinterpret_cast<const uint4*>(src + col);
-            if (copy_out) *reinterpret_cast<uint4*>(copy_out + (size_t)m * D + col) = raw;
             unpack8(raw, v[g]);
 #pragma unroll
             for (int j = 0; j < 8; ++j) sum += v[g][j];
@@ -83,13 +84,13 @@ __global__ __launch_bounds__(256) void layernorm_rows_kernel(const bf16_t* __res
 }
 
 void dispatch(const void* in, const int32_t* idx, int N, int k, int M, int D, const void* gamma,
-              const void* beta, float eps, void* copy_out, void* out, hipStream_t stream) {
+              const void* beta, float eps, int32_t* rows_out, void* out, hipStream_t stream) {
     const dim3 grid((M + 3) / 4), block(256);
     const int ch = (D + 511) / 512;
 #define FV_LN_CASE(CHV)                                                                                  \
     layernorm_rows_kernel<CHV><<<grid, block, 0, stream>>>(                                              \
         static_cast<const bf16_t*>(in), idx, N, k, M, D, static_cast<const bf16_t*>(gamma),              \
-        static_cast<const bf16_t*>(beta), eps, static_cast<bf16_t*>(copy_out), static_cast<bf16_t*>(out))
+        static_cast<const bf16_t*>(beta), eps, rows_out, static_cast<bf16_t*>(out))
     if (ch <= 1) FV_LN_CASE(1);
     else if (ch <= 2) FV_LN_CASE(2);
     else if (ch <= 4) FV_LN_CASE(4);
@@ -101,8 +102,8 @@ void dispatch(const void* in, const int32_t* idx, int N, int k, int M, int D, co
 }  // namespace
 
 void launch_gather_layernorm(const void* x, const int32_t* idx, int B, int N, int k, int D, const void* gamma,
-                             const void* beta, float eps, void* xk_out, void* a_out, hipStream_t stream) {
-    dispatch(x, idx, N, k, B * k, D, gamma, beta, eps, xk_out, a_out, stream);
+                             const void* beta, float eps, int32_t* rows_out, void* a_out, hipStream_t stream) {
+    dispatch(x, idx, N, k, B * k, D, gamma, beta, eps, rows_out, a_out, stream);
 }
 
 void launch_layernorm(const void* in, int M, int D, const void* gamma, const void* beta, float eps, void* a_out,

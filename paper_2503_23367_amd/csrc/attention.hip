@@ -60,7 +60,7 @@ constexpr int attn_waitcnt(int vm, bool lgkm) {
 }
 
 template <int DH, int QB, int QG, int KSPLIT>
-__global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_kernel(const AttnParams p) {
+__global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention_kernel(const AttnParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
     constexpr int WAVES = QG * KSPLIT;
     constexpr int BN = 64 * KSPLIT;        // keys per tile
@@ -139,6 +139,31 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_kernel(const At
                                              (lds_ptr_t)(sv_ + j * (WAVES * 64)), 16, 0, 0);        \
         }                                                                                           \
     }
+    // One of this wave's loads of a tile (j_ in [0, K_LD + V_LD): K rows first, then V^T rows)
+    // Written as inline assembly on purpose: after the compiler's own direct-to-LDS
+    // builtin it drains the whole LDS queue (lgkmcnt(0)) before the next operand
+    // use, which would undo the read-ahead of the matrix phase.  Completion is
+    // tracked by hand: every path waits for vmcnt(0) before the barrier that
+    // publishes the tile.
+#define FV_DMA16(gptr_, lds_chunk_ptr_)                                                             \
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                              \
+                 :                                                                                  \
+                 : "s"((uint32_t)(uintptr_t)(lds_ptr_t)(lds_chunk_ptr_)), "v"(gptr_)               \
+                 : "memory", "m0")
+#define FV_ISSUE_ONE(ktk_, ktv_, j_)                                                                \
+    {                                                                                               \
+        if ((j_) < K_LD) {                                                                          \
+            const int jk_ = (j_) < K_LD ? (j_) : 0;                                                 \
+            const int key_ = min((ktk_) * BN + k_key[jk_], p.L - 1);                                \
+            FV_DMA16(kc + key_ * DH + k_col[jk_],                                                   \
+                     lds + ((ktk_) & 1) * K_TILE + wave * 64 + jk_ * (WAVES * 64));                 \
+        } else {                                                                                    \
+            const int jv_ = (j_) >= K_LD ? (j_) - K_LD : 0;                                         \
+            const int kpos_ = min((ktv_) * BN + v_col[jv_], last_chunk);                            \
+            FV_DMA16(vc + v_row[jv_] + kpos_,                                                       \
+                     lds + 2 * K_TILE + ((ktv_) & 1) * V_TILE + wave * 64 + jv_ * (WAVES * 64));    \
+        }                                                                                           \
+    }
     // Cache positions at or past the length may hold anything (even NaN patterns),
     // and 0 * NaN would poison the output: after its own loads of a partial tile
     // have landed, each lane zeroes the out-of-range positions of its V^T chunks.
@@ -193,27 +218,67 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_kernel(const At
     const int KT = (p.L + BN - 1) / BN;
     const bool ragged = (p.L % BN) != 0;
 
-    f32x16_t s_cur[2][QB];   // scores of tile k (this wave's 64-key slice: two 32-key blocks)
-    f32x16_t s_nxt[2][QB];   // scores of tile k+1, produced while tile k is in the softmax
-    bf16x8_t pf_[4][QB];     // probabilities of tile k-1 as the B operand of the second MFMA
+    f32x16_t s_[2][QB];   // scores of this wave's 64-key slice (two 32-key blocks)
+    bf16x8_t pf_[4][QB];  // probabilities as the B operand of the second MFMA (four 16-key steps)
 
-    // S^T = K Q^T of tile kt_ into dst_ (prologue only; no overlap needed)
-#define FV_QK_ONLY(kt_, dst_)                                                                       \
+    // Matrix phase of iteration kt_: O^T += V^T P^T for tile kt_-1 (if HAS_PV_),
+    // then S^T = K Q^T for tile kt_, on this wave's 64-key slice.  All operand
+    // fragments come from LDS; their reads run DEPTH fragments ahead of the MFMAs
+    // that consume them (the scheduler is given the interleaving explicitly), so
+    // LDS latency hides behind the matrix pipe.  Consecutive MFMAs alternate
+    // accumulators.
+#define FV_MATRIX(kt_, HAS_PV_, LOAD_K_, LOAD_V_)                                                   \
     {                                                                                               \
+        constexpr int NV_ = (HAS_PV_) ? 4 * DB : 0;                                                 \
+        constexpr int NK_ = 2 * KS;                                                                 \
+        constexpr int DEPTH_ = 4;                                                                   \
+        /* The next tiles' direct-to-LDS loads (K tile kt_+1, V^T tile kt_) are issued */           \
+        /* between the operand reads below: program order against LDS reads is kept, so */          \
+        /* they end up spread between the MFMAs instead of queueing up in front of them. */         \
+        constexpr int JLO_ = (LOAD_K_) ? 0 : K_LD;                                                  \
+        constexpr int JHI_ = (LOAD_V_) ? K_LD + V_LD : K_LD;                                        \
+        constexpr int NJ_ = JHI_ > JLO_ ? JHI_ - JLO_ : 0;                                          \
+        constexpr int NFR_ = NV_ + NK_;                                                             \
+        constexpr int SPAN_ = NJ_ > NFR_ / 2 ? NFR_ : NFR_ / 2;                                     \
+        const u32x4_t* v_base_ = lds + 2 * K_TILE + (((kt_) + 1) & 1) * V_TILE + kh * 8;            \
         const u32x4_t* k_base_ = lds + ((kt_) & 1) * K_TILE + (kh * 64) * KCH;                      \
+        bf16x8_t fr_[NV_ + NK_];                                                                    \
+        _Pragma("unroll") for (int i = 0; i < NFR_; ++i) {                                          \
+            if (i < NV_)                                                                            \
+                fr_[i] = *reinterpret_cast<const bf16x8_t*>(                                        \
+                    v_base_ + ((i % DB) * 32 + li) * VCH + ((2 * (i / DB) + hf) ^ sw));             \
+            else                                                                                    \
+                fr_[i] = *reinterpret_cast<const bf16x8_t*>(                                        \
+                    k_base_ + (((i - NV_) % 2) * 32 + li) * KCH + ((2 * ((i - NV_) / 2) + hf) ^ sw)); \
+            /* the loads go between the first SPAN_ fragment reads, evenly: early enough */       \
+            /* to land before the end-of-iteration barrier */                                       \
+            if (NJ_ > 0 && i < SPAN_ && ((i + 1) * NJ_) / SPAN_ > (i * NJ_) / SPAN_)                \
+                FV_ISSUE_ONE((kt_) + 1, (kt_), JLO_ + (i * NJ_) / SPAN_)                            \
+        }                                                                                           \
         _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                            \
             _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)                                       \
-                _Pragma("unroll") for (int r = 0; r < 16; ++r) dst_[kb][qb][r] = 0.f;               \
+                _Pragma("unroll") for (int r = 0; r < 16; ++r) s_[kb][qb][r] = 0.f;                 \
+        if (HAS_PV_) {                                                                              \
+            _Pragma("unroll") for (int t = 0; t < 4; ++t)                                           \
+                _Pragma("unroll") for (int db = 0; db < DB; ++db)                                   \
+                    _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)                               \
+                        acc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                      \
+                            fr_[t * DB + db], pf_[t][qb], acc[db][qb], 0, 0, 0);                    \
+        }                                                                                           \
         _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                           \
-            _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) {                                      \
-                const bf16x8_t a_ = *reinterpret_cast<const bf16x8_t*>(                             \
-                    k_base_ + (kb * 32 + li) * KCH + ((2 * ks + hf) ^ sw));                         \
+            _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                        \
                 _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)                                   \
-                    dst_[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_, qf[qb][ks], dst_[kb][qb], 0, 0, 0); \
-            }                                                                                       \
+                    s_[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                           \
+                        fr_[NV_ + ks * 2 + kb], qf[qb][ks], s_[kb][qb], 0, 0, 0);                   \
+        __builtin_amdgcn_sched_group_barrier(0x100, DEPTH_, 0);                                     \
+        _Pragma("unroll") for (int i = 0; i < NV_ + NK_ - DEPTH_; ++i) {                            \
+            __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);                                     \
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                      \
+        }                                                                                           \
+        __builtin_amdgcn_sched_group_barrier(0x008, DEPTH_ * QB, 0);                                \
     }
-    // O^T += V^T P^T of tile kt_ alone (after the last iteration)
-#define FV_PV_ONLY(kt_)                                                                             \
+    // O^T += V^T P^T alone (after the last tile)
+#define FV_PV_LAST(kt_)                                                                             \
     {                                                                                               \
         const u32x4_t* v_base_ = lds + 2 * K_TILE + ((kt_) & 1) * V_TILE + kh * 8;                  \
         _Pragma("unroll") for (int t = 0; t < 4; ++t)                                               \
@@ -224,172 +289,104 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_kernel(const At
                     acc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf_, pf_[t][qb], acc[db][qb], 0, 0, 0); \
             }                                                                                       \
     }
-
-    // One iteration k of the software pipeline, three tiles in flight in one wave:
-    //   matrix pipe : O^T += V^T P^T of tile k-1 (HAS_PV_), then S^T = K Q^T of tile k+1 (HAS_QK_)
-    //   vector pipe : online softmax of tile k (s_cur -> new probabilities, running max / sum)
-    // The two streams are independent inside the iteration.  The body is cut into
-    // slices, one per operand fragment: the QB MFMAs that consume the fragment,
-    // the LDS read of the fragment DEPTH slices ahead, and a small piece of the
-    // softmax (a few VALU ops and exps fit under a 32-clock MFMA for free).
-    // A scheduling fence after each slice keeps the compiler from regrouping them.
-    // The rescale of O by the new maximum comes after the PV MFMAs of the iteration.
-#define FV_SCUR(e_) s_cur[((e_) % 32) / 16][(e_) / 32][(e_) % 16]
-#define FV_LOAD_FRAG(i_)                                                                            \
+    // online softmax of the scores of tile kt_: s_ -> pf_, running max / sum, rescale of O
+#define FV_SOFTMAX(kt_, MASK_)                                                                      \
     {                                                                                               \
-        if ((i_) < NV_) {                                                                           \
-            fr_[(i_)] = *reinterpret_cast<const bf16x8_t*>(                                         \
-                v_base_ + ((((i_) % DB)) * 32 + li) * VCH + ((2 * ((i_) / DB) + hf) ^ sw));         \
-        } else {                                                                                    \
-            fr_[(i_)] = *reinterpret_cast<const bf16x8_t*>(                                         \
-                k_base_ + ((((i_) - NV_) % 2) * 32 + li) * KCH + ((2 * (((i_) - NV_) / 2) + hf) ^ sw)); \
-        }                                                                                           \
-    }
-#define FV_ITER(kt_, HAS_PV_, HAS_QK_, MASK_)                                                       \
-    {                                                                                               \
-        constexpr int NV_ = (HAS_PV_) ? 4 * DB : 0;                                                 \
-        constexpr int NK_ = (HAS_QK_) ? 2 * KS : 0;                                                 \
-        constexpr int NF_ = NV_ + NK_;                                                              \
-        constexpr int DEPTH_ = NF_ < 4 ? NF_ : 4;                                                   \
-        constexpr int NE_ = 32 * QB;           /* score elements per lane */                        \
-        constexpr int NMAX_ = 4;               /* slices that carry the max reduction */            \
-        constexpr int EPS_ = 2 * QB;           /* elements exponentiated per later slice */         \
-        const u32x4_t* v_base_ = lds + 2 * K_TILE + (((kt_) + 1) & 1) * V_TILE + kh * 8;            \
-        const u32x4_t* k_base_ = lds + (((kt_) + 1) & 1) * K_TILE + (kh * 64) * KCH;                \
-        bf16x8_t fr_[NF_ > 0 ? NF_ : 1];                                                            \
         if (MASK_) {                                                                                \
             _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                        \
                 _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                    \
                     const int srow_ = 8 * (r >> 2) + 4 * hf + (r & 3);                              \
                     const int key_ = (kt_) * BN + kh * 64 + kb * 32 + swap_bits_2_3(srow_);         \
                     if (key_ >= p.L) {                                                              \
-                        _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) s_cur[kb][qb][r] = -INFINITY; \
+                        _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) s_[kb][qb][r] = -INFINITY; \
                     }                                                                               \
                 }                                                                                   \
         }                                                                                           \
-        if (HAS_QK_) {                                                                              \
+        _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                         \
+            float mx_ = s_[0][qb][0];                                                               \
             _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                        \
-                _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)                                   \
-                    _Pragma("unroll") for (int r = 0; r < 16; ++r) s_nxt[kb][qb][r] = 0.f;          \
-        }                                                                                           \
-        _Pragma("unroll") for (int i = 0; i < DEPTH_; ++i) FV_LOAD_FRAG(i)                          \
-        float mx_[QB], m_use_[QB], alpha_[QB], lsum_[QB];                                           \
-        bf16x8_t pnew_[4][QB];                                                                      \
-        _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) { mx_[qb] = -INFINITY; lsum_[qb] = 0.f; } \
-        constexpr int NSL_ = NF_ > (NMAX_ + 1 + NE_ / EPS_) ? NF_ : (NMAX_ + 1 + NE_ / EPS_);      \
-        _Pragma("unroll") for (int i = 0; i < NSL_; ++i) {                                          \
-            /* matrix stream */                                                                     \
-            if (i < NV_) {                                                                          \
-                _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)                                   \
-                    acc[i % DB][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                      \
-                        fr_[i < NF_ ? i : 0], pf_[i / DB][qb], acc[i % DB][qb], 0, 0, 0);           \
-            } else if (i < NF_) {                                                                   \
-                _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)                                   \
-                    s_nxt[(i - NV_) % 2][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(             \
-                        fr_[i < NF_ ? i : 0], qf[qb][((i - NV_) / 2) % KS], s_nxt[(i - NV_) % 2][qb], 0, 0, 0); \
-            }                                                                                       \
-            if (i + DEPTH_ < NF_) FV_LOAD_FRAG(i + DEPTH_)                                          \
-            /* vector stream */                                                                     \
-            if (i < NMAX_) {                                                                        \
-                _Pragma("unroll") for (int e = i * (NE_ / NMAX_); e < (i + 1) * (NE_ / NMAX_); ++e) \
-                    mx_[e / 32] = fmaxf(mx_[e / 32], FV_SCUR(e));                                   \
-            } else if (i == NMAX_) {                                                                \
-                _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                 \
-                    const float mxa_ = fmaxf(mx_[qb], other_half(mx_[qb]));                         \
-                    /* a slice that is entirely past the length keeps the old maximum */           \
-                    const float m_new_ = fmaxf(m_run[qb], mxa_ * p.scale_log2e);                    \
-                    m_use_[qb] = (m_new_ == -INFINITY) ? 0.f : m_new_;                              \
-                    alpha_[qb] = __builtin_amdgcn_exp2f(m_run[qb] - m_use_[qb]);                    \
-                    m_run[qb] = m_new_;                                                             \
+                _Pragma("unroll") for (int r = 0; r < 16; ++r) mx_ = fmaxf(mx_, s_[kb][qb][r]);     \
+            mx_ = fmaxf(mx_, other_half(mx_));                                                      \
+            /* a slice that is entirely past the length keeps the old maximum */                   \
+            const float m_new_ = fmaxf(m_run[qb], mx_ * p.scale_log2e);                             \
+            const float m_use_ = (m_new_ == -INFINITY) ? 0.f : m_new_;                              \
+            const float alpha_ = __builtin_amdgcn_exp2f(m_run[qb] - m_use_);                        \
+            m_run[qb] = m_new_;                                                                     \
+            float lsum_ = 0.f;                                                                      \
+            _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                        \
+                _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                    \
+                    const float pv_ = __builtin_amdgcn_exp2f(fmaf(s_[kb][qb][r], p.scale_log2e, -m_use_)); \
+                    lsum_ += pv_;                                                                   \
+                    pf_[2 * kb + (r >> 3)][qb][r & 7] = (__bf16)pv_;                                \
                 }                                                                                   \
-            } else if ((i - NMAX_ - 1) * EPS_ < NE_) {                                              \
-                _Pragma("unroll") for (int e = (i - NMAX_ - 1) * EPS_; e < (i - NMAX_) * EPS_; ++e) { \
-                    const float pv_ = __builtin_amdgcn_exp2f(fmaf(FV_SCUR(e), p.scale_log2e, -m_use_[e / 32])); \
-                    lsum_[e / 32] += pv_;                                                           \
-                    pnew_[2 * ((e % 32) / 16) + ((e % 16) >> 3)][e / 32][e & 7] = (__bf16)pv_;      \
-                }                                                                                   \
-            }                                                                                       \
-        }                                                                                           \
-        /* the interleaving the scheduler must produce: slice by slice, what the slice holds */     \
-        _Pragma("unroll") for (int i = 0; i < NSL_; ++i) {                                          \
-            if (i < NF_) __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);                        \
-            if (i + DEPTH_ < NF_) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                \
-            if (i < NMAX_) {                                                                        \
-                __builtin_amdgcn_sched_group_barrier(0x002, (NE_ / NMAX_) / 2, 0);                  \
-            } else if (i == NMAX_) {                                                                \
-                __builtin_amdgcn_sched_group_barrier(0x002, 8 * QB, 0);                             \
-                __builtin_amdgcn_sched_group_barrier(0x400, QB, 0);                                 \
-            } else if ((i - NMAX_ - 1) * EPS_ < NE_) {                                              \
-                __builtin_amdgcn_sched_group_barrier(0x002, EPS_, 0);                               \
-                __builtin_amdgcn_sched_group_barrier(0x400, EPS_, 0);                               \
-                __builtin_amdgcn_sched_group_barrier(0x002, EPS_ + EPS_ / 2, 0);                    \
-            }                                                                                       \
-        }                                                                                           \
-        /* keep the softmax results in this basic block (otherwise the compiler sinks their */      \
-        /* computation below the conditional rescale, out of reach of the interleaving) */          \
-        _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                         \
-            asm volatile("" : "+v"(lsum_[qb]), "+v"(alpha_[qb]));                                   \
-            _Pragma("unroll") for (int t = 0; t < 4; ++t) asm volatile("" : "+v"(pnew_[t][qb]));    \
-        }                                                                                           \
-        /* ---- end of iteration: running sum, rescale of O, rotate the pipeline registers */       \
-        _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                         \
-            l_run[qb] = l_run[qb] * alpha_[qb] + lsum_[qb];                                         \
-            if (__any(alpha_[qb] != 1.0f)) {                                                        \
+            l_run[qb] = l_run[qb] * alpha_ + lsum_;                                                 \
+            if (__any(alpha_ != 1.0f)) {                                                            \
                 _Pragma("unroll") for (int db = 0; db < DB; ++db)                                   \
-                    _Pragma("unroll") for (int r = 0; r < 16; ++r) acc[db][qb][r] *= alpha_[qb];    \
-            }                                                                                       \
-            _Pragma("unroll") for (int t = 0; t < 4; ++t) pf_[t][qb] = pnew_[t][qb];                \
-            if (HAS_QK_) {                                                                          \
-                _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) s_cur[kb][qb] = s_nxt[kb][qb];     \
+                    _Pragma("unroll") for (int r = 0; r < 16; ++r) acc[db][qb][r] *= alpha_;        \
             }                                                                                       \
         }                                                                                           \
     }
+    // ---- schedule.  Iteration k fetches K tile k+1 and V^T tile k and needs
+    // K tile k and V^T tile k-1.  Every wave does, per tile, a matrix phase
+    // (PV of the previous tile, then QK of this one) and a vector phase (softmax
+    // of this tile).  With two waves per SIMD (8-wave workgroups) the waves of
+    // the second half run the phases in the opposite order, so that on every SIMD
+    // one wave is in its matrix phase while the other is in its vector phase
+    // (both start each iteration together at the barrier).
+    const bool vector_first = (WAVES == 8) && (wave >= 4);
 
-    // ---- schedule.  Iteration k fetches K tile k+2 and V^T tile k, and needs
-    // K tile k+1 and V^T tile k-1 in LDS (two-stage rings each).
     FV_ISSUE_K(0)
-    if (KT > 1) FV_ISSUE_K(1)
     FV_PUBLISH()
-    FV_QK_ONLY(0, s_cur)
-    FV_PUBLISH()  // stage 0 of the K ring is refilled next: every wave must be done with tile 0
 
-    if (KT == 1) {
-        FV_ISSUE_V(0)
-        FV_ITER(0, false, false, true)
-        if (ragged) FV_FIX_TAIL(0)
-        FV_PUBLISH()
-    } else {
-        // iteration 0: nothing to multiply by V yet
-        if (KT > 2) FV_ISSUE_K(2)
-        FV_ISSUE_V(0)
-        FV_ITER(0, false, true, false)
+    if (!vector_first) {
+        // iteration 0
+        if (KT > 1) { FV_MATRIX(0, false, true, true) } else { FV_MATRIX(0, false, false, true) }
+        if (KT == 1) { FV_SOFTMAX(0, true) } else { FV_SOFTMAX(0, false) }
+        if (KT == 1 && ragged) FV_FIX_TAIL(0)
         FV_PUBLISH()
         int kt = 1;
-        for (; kt + 2 < KT; ++kt) {  // steady state
-            FV_ISSUE_K(kt + 2)
-            FV_ISSUE_V(kt)
-            FV_ITER(kt, true, true, false)
+        for (; kt + 1 < KT; ++kt) {
+            FV_MATRIX(kt, true, true, true)
+            FV_SOFTMAX(kt, false)
             FV_PUBLISH()
         }
-        if (kt + 1 < KT) {  // iteration KT-2: no further K tile to fetch
-            FV_ISSUE_V(kt)
-            FV_ITER(kt, true, true, false)
+        if (kt < KT) {  // last tile
+            FV_MATRIX(kt, true, false, true)
+            FV_SOFTMAX(kt, true)
+            if (ragged) FV_FIX_TAIL(kt)
             FV_PUBLISH()
-            ++kt;
         }
-        // iteration KT-1: last tile in the softmax (masked), no next tile
-        FV_ISSUE_V(kt)
-        FV_ITER(kt, true, false, true)
-        if (ragged) FV_FIX_TAIL(kt)
+        FV_PV_LAST(KT - 1)
+    } else {
+        // vector-first waves fetch at the start of the iteration (their matrix phase
+        // comes last, right before the barrier)
+        if (KT > 1) { FV_MATRIX(0, false, true, true) } else { FV_MATRIX(0, false, false, true) }
+        if (KT == 1 && ragged) FV_FIX_TAIL(0)
         FV_PUBLISH()
+        int kt = 1;
+        for (; kt + 1 < KT; ++kt) {
+            FV_ISSUE_K(kt + 1)
+            FV_ISSUE_V(kt)
+            FV_SOFTMAX(kt - 1, false)
+            FV_MATRIX(kt, true, false, false)
+            FV_PUBLISH()
+        }
+        if (kt < KT) {  // last tile
+            FV_ISSUE_V(kt)
+            FV_SOFTMAX(kt - 1, false)
+            FV_MATRIX(kt, true, false, false)
+            if (ragged) FV_FIX_TAIL(kt)
+            FV_PUBLISH()
+        }
+        FV_SOFTMAX(KT - 1, true)
+        FV_PV_LAST(KT - 1)
     }
-    FV_PV_ONLY(KT - 1)
-#undef FV_ITER
-#undef FV_SCUR
-#undef FV_LOAD_FRAG
-#undef FV_QK_ONLY
-#undef FV_PV_ONLY
+#undef FV_MATRIX
+#undef FV_PV_LAST
+#undef FV_SOFTMAX
 #undef FV_ISSUE_K
+#undef FV_ISSUE_ONE
+#undef FV_DMA16
 #undef FV_ISSUE_V
 #undef FV_FIX_TAIL
 
@@ -495,10 +492,11 @@ void launch_attention(const AttnArgs& a, hipStream_t stream) {
     p.o = static_cast<bf16_t*>(a.o);
     p.H = a.H; p.k_tokens = a.k_tokens; p.L = a.L; p.L_cap = a.L_cap; p.D = a.H * a.dh;
     p.scale_log2e = a.scale * 1.4426950408889634f;
-    // One wave per 64 queries; when that leaves SIMDs idle (fewer than ~1 wave per
-    // SIMD on 256 CUs), split the keys of each tile over two waves instead.
-    const long waves = (long)((a.k_tokens + 63) / 64) * a.H * a.B;
-    int cfg = waves >= 900 ? 0 : 1;
+    // One wave per 32 queries, two waves per SIMD: with enough queries two 4-wave
+    // workgroups share a CU; otherwise an 8-wave workgroup splits the keys of each
+    // tile between two waves per query group.
+    const long waves = (long)((a.k_tokens + 31) / 32) * a.H * a.B;
+    int cfg = waves >= 1800 ? 2 : 4;
     if (attn_cfg_override() >= 0) cfg = attn_cfg_override();
     if (a.dh == 128) {
         switch (cfg) {

@@ -55,6 +55,23 @@ __device__ __forceinline__ float other_half(float v) {
     return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
 }
 
+// XOR key that spreads the 16-byte chunks of consecutive rows over all 64 LDS
+// banks (256 bytes): a 16-byte-per-lane read is served 16 lanes at a time, so 16
+// consecutive rows must land in 16 different chunk columns.  Rows of 256 bytes
+// (16 chunks) use the low 4 row bits; rows of 128 bytes (8 chunks, two rows per
+// bank sweep) use row bits 1-3.
+template <int CPR>
+__device__ __forceinline__ int chunk_key(int row) {
+    static_assert(CPR == 8 || CPR == 16, "rows of 128 or 256 bytes");
+    return CPR == 16 ? (row & 15) : ((row >> 1) & 7);
+}
+
+#ifndef ATTN_SPAN_FULL
+#define ATTN_SPAN_FULL 0
+#endif
+#ifndef ATTN_VF_SPLIT
+#define ATTN_VF_SPLIT 0
+#endif
 constexpr int attn_waitcnt(int vm, bool lgkm) {
     return (vm & 0xF) | ((vm >> 4) << 14) | (0x7 << 4) | ((lgkm ? 0x0 : 0xF) << 8);
 }
@@ -87,10 +104,19 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
     const int kh = wave % KSPLIT;       // key slice inside a tile
     const int li = lane & 31;           // query column / operand row
     const int hf = lane >> 5;           // half-wave
-    const int sw = lane & 7;            // swizzle key of this lane's operand row
-    const int head = blockIdx.y;
-    const int b = blockIdx.z;
-    const int q_base = blockIdx.x * (QG * 32 * QB) + qg * (32 * QB);
+    const int sw_k = chunk_key<DH / 8>(lane & 31);          // swizzle keys of this lane's operand rows
+    const int sw_v = chunk_key<8 * KSPLIT>(lane & 31);
+    // Workgroup -> (query tile, head, sample).  Consecutive workgroup ids are dealt
+    // round-robin to the 8 XCDs, each with its own L2; undo that so an XCD works on
+    // a contiguous run of (head, query tile) pairs: the workgroups that stream the
+    // same head's K / V then share one L2 instead of pulling it into all eight.
+    int wg = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    const int n_wg = gridDim.x * gridDim.y * gridDim.z;
+    if ((n_wg & 7) == 0) wg = (wg & 7) * (n_wg >> 3) + (wg >> 3);
+    const int q_tile = wg % gridDim.x;
+    const int head = (wg / gridDim.x) % gridDim.y;
+    const int b = wg / (gridDim.x * gridDim.y);
+    const int q_base = q_tile * (QG * 32 * QB) + qg * (32 * QB);
 
     const bf16_t* kc = p.kc + ((size_t)b * p.H + head) * p.L_cap * DH;
     const bf16_t* vc = p.vc + ((size_t)b * p.H + head) * DH * (size_t)p.L_cap;
@@ -103,14 +129,14 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
 #pragma unroll
     for (int j = 0; j < K_LD; ++j) {
         const int slot = (wave + WAVES * j) * K_RPI + lane / KCH;  // LDS row
-        const int c = (lane % KCH) ^ (slot & 7);                   // logical chunk stored at this position
+        const int c = (lane % KCH) ^ chunk_key<KCH>(slot);         // logical chunk stored at this position
         k_key[j] = (slot & ~31) | swap_bits_2_3(slot & 31);
         k_col[j] = c * 8;
     }
 #pragma unroll
     for (int j = 0; j < V_LD; ++j) {
         const int d = (wave + WAVES * j) * V_RPI + lane / VCH;
-        const int c = (lane % VCH) ^ (d & 7);
+        const int c = (lane % VCH) ^ chunk_key<VCH>(d);
         v_row[j] = d * p.L_cap;
         v_col[j] = c * 8;
     }
@@ -150,6 +176,28 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
                  :                                                                                  \
                  : "s"((uint32_t)(uintptr_t)(lds_ptr_t)(lds_chunk_ptr_)), "v"(gptr_)               \
                  : "memory", "m0")
+    // The same load, pinned in the instruction stream: it takes a register of the
+    // surrounding arithmetic as a pass-through operand, so it is scheduled after
+    // that value's producer and before its consumers.
+#define FV_DMA16_AT(gptr_, lds_chunk_ptr_, reg_)                                                    \
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %2, off"                              \
+                 : "+v"(reg_)                                                                       \
+                 : "s"((uint32_t)(uintptr_t)(lds_ptr_t)(lds_chunk_ptr_)), "v"(gptr_)               \
+                 : "memory", "m0")
+#define FV_ISSUE_ONE_AT(ktk_, ktv_, j_, reg_)                                                       \
+    {                                                                                               \
+        if ((j_) < K_LD) {                                                                          \
+            const int jk_ = (j_) < K_LD ? (j_) : 0;                                                 \
+            const int key_ = min((ktk_) * BN + k_key[jk_], p.L - 1);                                \
+            FV_DMA16_AT(kc + key_ * DH + k_col[jk_],                                                \
+                        lds + ((ktk_) & 1) * K_TILE + wave * 64 + jk_ * (WAVES * 64), reg_);        \
+        } else {                                                                                    \
+            const int jv_ = (j_) >= K_LD ? (j_) - K_LD : 0;                                         \
+            const int kpos_ = min((ktv_) * BN + v_col[jv_], last_chunk);                            \
+            FV_DMA16_AT(vc + v_row[jv_] + kpos_,                                                    \
+                        lds + 2 * K_TILE + ((ktv_) & 1) * V_TILE + wave * 64 + jv_ * (WAVES * 64), reg_); \
+        }                                                                                           \
+    }
 #define FV_ISSUE_ONE(ktk_, ktv_, j_)                                                                \
     {                                                                                               \
         if ((j_) < K_LD) {                                                                          \
@@ -239,17 +287,17 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
         constexpr int JHI_ = (LOAD_V_) ? K_LD + V_LD : K_LD;                                        \
         constexpr int NJ_ = JHI_ > JLO_ ? JHI_ - JLO_ : 0;                                          \
         constexpr int NFR_ = NV_ + NK_;                                                             \
-        constexpr int SPAN_ = NJ_ > NFR_ / 2 ? NFR_ : NFR_ / 2;                                     \
-        const u32x4_t* v_base_ = lds + 2 * K_TILE + (((kt_) + 1) & 1) * V_TILE + kh * 8;            \
+        constexpr int SPAN_ = (ATTN_SPAN_FULL || NJ_ > NFR_ / 2) ? NFR_ : NFR_ / 2;                 \
+        const u32x4_t* v_base_ = lds + 2 * K_TILE + (((kt_) + 1) & 1) * V_TILE;                     \
         const u32x4_t* k_base_ = lds + ((kt_) & 1) * K_TILE + (kh * 64) * KCH;                      \
         bf16x8_t fr_[NV_ + NK_];                                                                    \
         _Pragma("unroll") for (int i = 0; i < NFR_; ++i) {                                          \
             if (i < NV_)                                                                            \
                 fr_[i] = *reinterpret_cast<const bf16x8_t*>(                                        \
-                    v_base_ + ((i % DB) * 32 + li) * VCH + ((2 * (i / DB) + hf) ^ sw));             \
+                    v_base_ + ((i % DB) * 32 + li) * VCH + ((kh * 8 + 2 * (i / DB) + hf) ^ sw_v));  \
             else                                                                                    \
                 fr_[i] = *reinterpret_cast<const bf16x8_t*>(                                        \
-                    k_base_ + (((i - NV_) % 2) * 32 + li) * KCH + ((2 * ((i - NV_) / 2) + hf) ^ sw)); \
+                    k_base_ + (((i - NV_) % 2) * 32 + li) * KCH + ((2 * ((i - NV_) / 2) + hf) ^ sw_k)); \
             /* the loads go between the first SPAN_ fragment reads, evenly: early enough */       \
             /* to land before the end-of-iteration barrier */                                       \
             if (NJ_ > 0 && i < SPAN_ && ((i + 1) * NJ_) / SPAN_ > (i * NJ_) / SPAN_)                \
@@ -280,18 +328,30 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
     // O^T += V^T P^T alone (after the last tile)
 #define FV_PV_LAST(kt_)                                                                             \
     {                                                                                               \
-        const u32x4_t* v_base_ = lds + 2 * K_TILE + ((kt_) & 1) * V_TILE + kh * 8;                  \
+        const u32x4_t* v_base_ = lds + 2 * K_TILE + ((kt_) & 1) * V_TILE;                           \
         _Pragma("unroll") for (int t = 0; t < 4; ++t)                                               \
             _Pragma("unroll") for (int db = 0; db < DB; ++db) {                                     \
                 const bf16x8_t vf_ = *reinterpret_cast<const bf16x8_t*>(                            \
-                    v_base_ + (db * 32 + li) * VCH + ((2 * t + hf) ^ sw));                          \
+                    v_base_ + (db * 32 + li) * VCH + ((kh * 8 + 2 * t + hf) ^ sw_v));               \
                 _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)                                   \
                     acc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf_, pf_[t][qb], acc[db][qb], 0, 0, 0); \
             }                                                                                       \
     }
-    // online softmax of the scores of tile kt_: s_ -> pf_, running max / sum, rescale of O
-#define FV_SOFTMAX(kt_, MASK_)                                                                      \
+    // online softmax of the scores of tile kt_: s_ -> pf_, running max / sum, rescale of O.
+    // LOAD_K_ / LOAD_V_: this wave's loads of K tile ktl_+1 / V^T tile ktl_ are issued
+    // from inside the exponential loop, one every few elements, instead of in a burst
+    // (a burst from several waves at once fills the texture-address queue and the
+    // waves sit in it).  The wave raises its issue priority for the duration: its
+    // many short vector instructions then win the issue slot over the matrix-phase
+    // wave sharing the SIMD, which needs one slot per 32-cycle MFMA only.
+#define FV_SOFTMAX(kt_, MASK_, LOAD_K_, LOAD_V_, ktl_)                                              \
     {                                                                                               \
+        __builtin_amdgcn_s_setprio(1);                                                              \
+        constexpr int JLO_ = (LOAD_K_) ? 0 : K_LD;                                                  \
+        constexpr int JHI_ = (LOAD_V_) ? K_LD + V_LD : K_LD;                                        \
+        constexpr int NJ_ = JHI_ > JLO_ ? JHI_ - JLO_ : 0;                                          \
+        constexpr int EVERY_ = NJ_ > 0 ? (32 / NJ_ > 0 ? 32 / NJ_ : 1) : 1;                         \
+        static_assert(NJ_ <= 32, "at most one load per score element");                             \
         if (MASK_) {                                                                                \
             _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                        \
                 _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                    \
@@ -315,7 +375,10 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
             float lsum_ = 0.f;                                                                      \
             _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                        \
                 _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                    \
-                    const float pv_ = __builtin_amdgcn_exp2f(fmaf(s_[kb][qb][r], p.scale_log2e, -m_use_)); \
+                    float pv_ = __builtin_amdgcn_exp2f(fmaf(s_[kb][qb][r], p.scale_log2e, -m_use_)); \
+                    const int e_ = kb * 16 + r;                                                     \
+                    if (qb == 0 && NJ_ > 0 && e_ % EVERY_ == 0 && e_ / EVERY_ < NJ_)                \
+                        FV_ISSUE_ONE_AT((ktl_) + 1, (ktl_), JLO_ + e_ / EVERY_, pv_)                \
                     lsum_ += pv_;                                                                   \
                     pf_[2 * kb + (r >> 3)][qb][r & 7] = (__bf16)pv_;                                \
                 }                                                                                   \
@@ -325,6 +388,7 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
                     _Pragma("unroll") for (int r = 0; r < 16; ++r) acc[db][qb][r] *= alpha_;        \
             }                                                                                       \
         }                                                                                           \
+        __builtin_amdgcn_s_setprio(0);                                                              \
     }
     // ---- schedule.  Iteration k fetches K tile k+1 and V^T tile k and needs
     // K tile k and V^T tile k-1.  Every wave does, per tile, a matrix phase
@@ -341,18 +405,18 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
     if (!vector_first) {
         // iteration 0
         if (KT > 1) { FV_MATRIX(0, false, true, true) } else { FV_MATRIX(0, false, false, true) }
-        if (KT == 1) { FV_SOFTMAX(0, true) } else { FV_SOFTMAX(0, false) }
+        if (KT == 1) { FV_SOFTMAX(0, true, false, false, 0) } else { FV_SOFTMAX(0, false, false, false, 0) }
         if (KT == 1 && ragged) FV_FIX_TAIL(0)
         FV_PUBLISH()
         int kt = 1;
         for (; kt + 1 < KT; ++kt) {
             FV_MATRIX(kt, true, true, true)
-            FV_SOFTMAX(kt, false)
+            FV_SOFTMAX(kt, false, false, false, 0)
             FV_PUBLISH()
         }
         if (kt < KT) {  // last tile
             FV_MATRIX(kt, true, false, true)
-            FV_SOFTMAX(kt, true)
+            FV_SOFTMAX(kt, true, false, false, 0)
             if (ragged) FV_FIX_TAIL(kt)
             FV_PUBLISH()
         }
@@ -365,20 +429,22 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
         FV_PUBLISH()
         int kt = 1;
         for (; kt + 1 < KT; ++kt) {
-            FV_ISSUE_K(kt + 1)
-            FV_ISSUE_V(kt)
-            FV_SOFTMAX(kt - 1, false)
-            FV_MATRIX(kt, true, false, false)
+            if (ATTN_VF_SPLIT) {
+                FV_SOFTMAX(kt - 1, false, true, false, kt)
+                FV_MATRIX(kt, true, false, true)
+            } else {
+                FV_SOFTMAX(kt - 1, false, true, true, kt)
+                FV_MATRIX(kt, true, false, false)
+            }
             FV_PUBLISH()
         }
         if (kt < KT) {  // last tile
-            FV_ISSUE_V(kt)
-            FV_SOFTMAX(kt - 1, false)
+            FV_SOFTMAX(kt - 1, false, false, true, kt)
             FV_MATRIX(kt, true, false, false)
             if (ragged) FV_FIX_TAIL(kt)
             FV_PUBLISH()
         }
-        FV_SOFTMAX(KT - 1, true)
+        FV_SOFTMAX(KT - 1, true, false, false, 0)
         FV_PV_LAST(KT - 1)
     }
 #undef FV_MATRIX
@@ -386,6 +452,8 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
 #undef FV_SOFTMAX
 #undef FV_ISSUE_K
 #undef FV_ISSUE_ONE
+#undef FV_ISSUE_ONE_AT
+#undef FV_DMA16_AT
 #undef FV_DMA16
 #undef FV_ISSUE_V
 #undef FV_FIX_TAIL

@@ -92,12 +92,14 @@ constexpr int waitcnt_imm(int vm, bool lgkm) {
     return (vm & 0xF) | ((vm >> 4) << 14) | (0x7 << 4) | ((lgkm ? 0x0 : 0xF) << 8);
 }
 
-// XOR key that spreads the 16-byte chunks of consecutive rows over all LDS banks:
-// rows of 128 bytes (8 chunks) use the low 3 row bits, rows of 64 bytes (4 chunks,
-// two rows per 128 bytes) use row bits 1-2.
+// XOR key that spreads the 16-byte chunks of consecutive rows over all 64 LDS
+// banks (256 bytes): a 16-byte-per-lane read is served 16 lanes at a time, so 16
+// consecutive rows must land in 16 different chunk columns.  Rows of 128 bytes
+// (8 chunks, two rows per bank sweep) use row bits 1-3; rows of 64 bytes (4
+// chunks, four rows per sweep) use row bits 2-3.
 template <int CPR>
 __device__ __forceinline__ int swz(int row) {
-    return CPR == 8 ? (row & 7) : ((row >> 1) & 3);
+    return CPR == 8 ? ((row >> 1) & 7) : ((row >> 2) & 3);
 }
 
 template <int BM, int BN, int BK, int STAGES, int EPI>
@@ -142,9 +144,11 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
     // Direct-to-LDS loads: one instruction moves 64 x 16 bytes into a contiguous
     // 1 KB of LDS (lane l lands at base + 16 l), i.e. RPI whole tile rows.  The
     // swizzle is applied on the global side: lane l fetches the chunk that
-    // belongs at its LDS position.  Load j of a wave covers rows (wave + 4 j) * RPI ...
+    // belongs at its LDS position.  Load j of a wave covers tile rows
+    // (wave + 4 j) * RPI + ld_row; the key of such a row does not depend on j
+    // (RPI is 8 or 16 and the key uses row bits below 4).
     const int ld_row = lane / CPR;
-    const int ld_chunk = (lane % CPR) ^ swz<CPR>(ld_row);
+    const int ld_chunk = (lane % CPR) ^ swz<CPR>(wave * RPI + ld_row);
     int a_off[A_LD], w_off[W_LD];
 #pragma unroll
     for (int j = 0; j < A_LD; ++j)
@@ -153,37 +157,28 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
     for (int j = 0; j < W_LD; ++j)
         w_off[j] = min(n0 + (wave + 4 * j) * RPI + ld_row, p.N - 1) * p.K + ld_chunk * 8;
 
+    // The loads are issued through inline assembly: the compiler's own model of
+    // this instruction makes it drain every outstanding LDS operation before the
+    // next operand use, which would serialise the operand reads behind it.
+    // Completion is tracked by hand (vmcnt before the barrier that publishes a tile).
     typedef __attribute__((address_space(3))) void* lds_ptr_t;
+#define FV_DMA16(gptr_, lds_chunk_ptr_)                                                         \
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                          \
+                 :                                                                              \
+                 : "s"((uint32_t)(uintptr_t)(lds_ptr_t)(lds_chunk_ptr_)), "v"(gptr_)           \
+                 : "memory", "m0")
+    // Load q of a tile (A loads first, then W) into ring stage stage_.
+#define FV_ISSUE_Q(kt_, stage_, q_)                                                             \
+    {                                                                                           \
+        if ((q_) < A_LD)                                                                        \
+            FV_DMA16(p.A + (size_t)(kt_) * BK + a_off[(q_) < A_LD ? (q_) : 0],                  \
+                     lds + (stage_) * STAGE + wave * 64 + (q_) * 256);                          \
+        else                                                                                    \
+            FV_DMA16(p.W + (size_t)(kt_) * BK + w_off[(q_) >= A_LD ? (q_) - A_LD : 0],          \
+                     lds + (stage_) * STAGE + A_TILE + wave * 64 + ((q_) - A_LD) * 256);        \
+    }
 #define FV_ISSUE_TILE(kt_, stage_)                                                              \
-    {                                                                                           \
-        const bf16_t* ga_ = p.A + (size_t)(kt_) * BK;                                           \
-        const bf16_t* gw_ = p.W + (size_t)(kt_) * BK;                                           \
-        u32x4_t* sa_ = lds + (stage_) * STAGE + wave * 64;                                      \
-        u32x4_t* sw_ = sa_ + A_TILE;                                                            \
-        _Pragma("unroll") for (int j = 0; j < A_LD; ++j)                                        \
-            __builtin_amdgcn_global_load_lds(ga_ + a_off[j], (lds_ptr_t)(sa_ + j * 256), 16, 0, 0); \
-        _Pragma("unroll") for (int j = 0; j < W_LD; ++j)                                        \
-            __builtin_amdgcn_global_load_lds(gw_ + w_off[j], (lds_ptr_t)(sw_ + j * 256), 16, 0, 0); \
-    }
-
-    // The same loads, one slice at a time: slice part_ of nparts_ (loads are numbered
-    // A first, then W).  Spreading a tile's loads between the MFMAs of an iteration
-    // keeps the texture-address queue from filling up and stalling the wave.
-#define FV_ISSUE_PART(kt_, stage_, part_, nparts_)                                              \
-    {                                                                                           \
-        const bf16_t* ga_ = p.A + (size_t)(kt_) * BK;                                           \
-        const bf16_t* gw_ = p.W + (size_t)(kt_) * BK;                                           \
-        u32x4_t* sa_ = lds + (stage_) * STAGE + wave * 64;                                      \
-        u32x4_t* sw_ = sa_ + A_TILE;                                                            \
-        _Pragma("unroll") for (int q = (part_) * LPT / (nparts_); q < ((part_) + 1) * LPT / (nparts_); ++q) { \
-            if (q < A_LD)                                                                       \
-                __builtin_amdgcn_global_load_lds(ga_ + a_off[q < A_LD ? q : 0],                 \
-                                                 (lds_ptr_t)(sa_ + q * 256), 16, 0, 0);         \
-            else                                                                                \
-                __builtin_amdgcn_global_load_lds(gw_ + w_off[q >= A_LD ? q - A_LD : 0],         \
-                                                 (lds_ptr_t)(sw_ + (q - A_LD) * 256), 16, 0, 0); \
-        }                                                                                       \
-    }
+    _Pragma("unroll") for (int q = 0; q < LPT; ++q) FV_ISSUE_Q(kt_, stage_, q)
 
     const int frag_row = lane & 31;
     const int frag_half = lane >> 5;
@@ -200,6 +195,25 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
             dst_a_[mi] = *reinterpret_cast<const bf16x8_t*>(sa_ + (a_row + 32 * mi) * CPR + ch_); \
         _Pragma("unroll") for (int ni = 0; ni < NI; ++ni)                                       \
             dst_w_[ni] = *reinterpret_cast<const bf16x8_t*>(sw_ + (w_row + 32 * ni) * CPR + ch_); \
+    }
+    // The same operand reads with slice part_ of nparts_ of the next tile's loads
+    // issued between them, one load after each read: spreading the loads keeps the
+    // texture-address queue from filling up and stalling the wave.
+#define FV_LOAD_FRAGS_ISSUE(dst_a_, dst_w_, stage_, kk_, kt_, fill_, part_, nparts_)            \
+    {                                                                                           \
+        const u32x4_t* sa_ = lds + (stage_) * STAGE;                                            \
+        const u32x4_t* sw_ = sa_ + A_TILE;                                                      \
+        const int ch_ = (2 * (kk_) + frag_half) ^ frag_sw;                                      \
+        const int q_lo_ = (part_) * LPT / (nparts_), q_hi_ = ((part_) + 1) * LPT / (nparts_); \
+        _Pragma("unroll") for (int g = 0; g < MI + NI; ++g) {                                   \
+            if (g < MI)                                                                         \
+                dst_a_[g < MI ? g : 0] =                                                        \
+                    *reinterpret_cast<const bf16x8_t*>(sa_ + (a_row + 32 * g) * CPR + ch_);     \
+            else                                                                                \
+                dst_w_[g >= MI ? g - MI : 0] =                                                  \
+                    *reinterpret_cast<const bf16x8_t*>(sw_ + (w_row + 32 * (g - MI)) * CPR + ch_); \
+            if (q_lo_ + g < q_hi_) FV_ISSUE_Q(kt_, fill_, q_lo_ + g)                            \
+        }                                                                                       \
     }
 
     f32x16_t acc[MI][NI];
@@ -257,19 +271,20 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
         _Pragma("unroll") for (int kk = 0; kk < KK; ++kk) {                                     \
             const int cur_ = kk & 1, nxt_ = cur_ ^ 1;                                           \
             if (kk + 1 < KK) {                                                                  \
-                if (MORE_) FV_ISSUE_PART(kt + STAGES - 1, fill_, kk, KK - 1)                    \
-                FV_LOAD_FRAGS(fa[nxt_], fw[nxt_], stage, kk + 1)                                \
+                if (MORE_)                                                                      \
+                    FV_LOAD_FRAGS_ISSUE(fa[nxt_], fw[nxt_], stage, kk + 1, kt + STAGES - 1, fill_, kk, KK - 1) \
+                else                                                                            \
+                    FV_LOAD_FRAGS(fa[nxt_], fw[nxt_], stage, kk + 1)                            \
                 FV_MFMA_ROWS(cur_, 0, MI)                                                       \
-                FV_INTERLEAVE((MI * NI) / (MI + NI), (MORE_))                                   \
+                FV_INTERLEAVE((MI * NI) / (MI + NI), false)                                     \
             } else if (HANDOVER_) {                                                             \
-                FV_MFMA_ROWS(cur_, 0, MI / 2)                                                   \
                 __builtin_amdgcn_s_waitcnt(waitcnt_imm((MORE_) ? (STAGES - 2) * LPT : 0, true)); \
                 asm volatile("" ::: "memory");                                                  \
                 __builtin_amdgcn_s_barrier();                                                   \
                 asm volatile("" ::: "memory");                                                  \
                 FV_LOAD_FRAGS(fa[nxt_], fw[nxt_], next_stage_, 0)                               \
-                FV_MFMA_ROWS(cur_, MI / 2, MI)                                                  \
-                FV_INTERLEAVE((MI * NI / 2) / (MI + NI) > 0 ? (MI * NI / 2) / (MI + NI) : 1, false) \
+                FV_MFMA_ROWS(cur_, 0, MI)                                                       \
+                FV_INTERLEAVE((MI * NI) / (MI + NI), false)                                     \
             } else {                                                                            \
                 FV_MFMA_ROWS(cur_, 0, MI)                                                       \
             }                                                                                   \
@@ -286,7 +301,9 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
 #undef FV_INTERLEAVE
 #undef FV_MFMA_ROWS
 #undef FV_ISSUE_TILE
-#undef FV_ISSUE_PART
+#undef FV_ISSUE_Q
+#undef FV_DMA16
+#undef FV_LOAD_FRAGS_ISSUE
 #undef FV_LOAD_FRAGS
 
     // ---- Epilogue, staged through LDS so that global traffic is 16 bytes per lane.
@@ -299,8 +316,8 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
     // order, so no barrier is needed between the two phases.
     constexpr int SROW = WTN + 4;          // padded row stride (floats)
     constexpr int LPR = WTN / 8;           // lanes per row in the read-back phase
-    constexpr int RPP = 64 / LPR;          // rows per pass
-    constexpr int PASSES = 32 / RPP;
+    constexpr int RPP = 64 / LPR;          // rows per pass (lanes past RPP * LPR idle when 64 % LPR != 0)
+    constexpr int PASSES = (32 + RPP - 1) / RPP;
     static_assert(4 * 32 * SROW * 4 <= STAGES * (BM + BN) * BK * 2, "staging area must fit in the tile LDS");
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
@@ -316,7 +333,7 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
     }
     const int cg = lane % LPR, rsub = lane / LPR;
     const int ncol = n0 + wn * WTN + cg * 8;  // first of this lane's 8 output columns
-    const bool col_ok = ncol < p.N;           // N % 8 == 0: the whole group is in or out
+    const bool col_ok = ncol < p.N && rsub < RPP;  // N % 8 == 0: the whole group is in or out
     const ColDest cd = col_dest<EPI>(p, col_ok ? ncol : 0);
     bool row_path = col_ok;
     if (EPI == EPI_QKV) row_path = col_ok && ncol < 2 * p.D;  // the V section is stored transposed below
@@ -343,7 +360,7 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
         for (int ps = 0; ps < PASSES; ++ps) {
             const int row = ps * RPP + rsub;
             const int m = m_slab + row;
-            if (m < p.M && row_path) {
+            if (m < p.M && row_path && (32 % RPP == 0 || row < 32)) {
                 const f32x4_t lo = *reinterpret_cast<const f32x4_t*>(stg + row * SROW + cg * 8);
                 const f32x4_t hi = *reinterpret_cast<const f32x4_t*>(stg + row * SROW + cg * 8 + 4);
                 float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
@@ -426,24 +443,33 @@ int gemm_cfg_override() {
 template <int EPI>
 void launch_epi(GemmParams& p, hipStream_t stream) {
     // Tile choice, from measurements on the block's shapes:
-    //  * 256x256 tiles halve the global->LDS traffic per MFMA (that path tops out
-    //    near 56 B/clk/CU and a 128x128x64 tile needs 64 B/clk at MFMA peak); they
-    //    win whenever they still give (almost) every CU a tile.  Not used for the
-    //    QKV epilogue, whose extra address state does not fit the register budget.
-    //  * otherwise 128x128 tiles, two workgroups per CU; with at most two tiles per
-    //    CU the deeper pipeline of shorter K steps wins (out-proj, FC2).
+    //  * 256-row tiles halve the global->LDS traffic per MFMA and give every wave
+    //    sixteen (or twelve) MFMAs per operand-read step, which hides LDS latency
+    //    with one wave per SIMD; they win whenever they still give (almost) every
+    //    CU a tile.  The QKV GEMM uses 256x192 (N = 3D divides evenly and the
+    //    epilogue's extra address state fits beside 192 accumulator registers),
+    //    the others 256x256.
+    //  * otherwise 128x128 tiles.  At most one tile per CU: three 64-wide K stages
+    //    (one workgroup per CU, LDS is free); up to two per CU: four 32-wide stages;
+    //    more: two 64-wide stages, several workgroups per CU.
     const long tiles256 = (long)((p.M + 255) / 256) * ((p.N + 255) / 256);
+    const long tiles192 = (long)((p.M + 255) / 256) * ((p.N + 191) / 192);
     const long tiles128 = (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
     int cfg;
-    if (EPI != EPI_QKV && tiles256 >= 192)
+    if (EPI == EPI_QKV && tiles192 >= 192)
+        cfg = 9;
+    else if (EPI != EPI_QKV && tiles256 >= 192)
         cfg = 1;
     else
-        cfg = tiles128 <= 512 ? 3 : 6;
+        cfg = tiles128 <= 256 ? 7 : (tiles128 <= 512 ? 3 : 6);
     if (gemm_cfg_override() >= 0) cfg = gemm_cfg_override();
     switch (cfg) {
         case 0: launch_cfg<256, 256, 32, 4, EPI>(p, stream); break;
         case 1: launch_cfg<256, 256, 64, 2, EPI>(p, stream); break;
         case 3: launch_cfg<128, 128, 32, 4, EPI>(p, stream); break;
+        case 7: launch_cfg<128, 128, 64, 3, EPI>(p, stream); break;
+        case 9: launch_cfg<256, 192, 64, 2, EPI>(p, stream); break;
+        case 8: launch_cfg<128, 128, 64, 4, EPI>(p, stream); break;
         default: launch_cfg<128, 128, 64, 2, EPI>(p, stream); break;
     }
 }

@@ -121,80 +121,73 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
     const bf16_t* kc = p.kc + ((size_t)b * p.H + head) * p.L_cap * DH;
     const bf16_t* vc = p.vc + ((size_t)b * p.H + head) * DH * (size_t)p.L_cap;
 
-    // ---- per-lane source descriptors of the direct-to-LDS loads.  Load j of this
-    // wave is instruction ij = wave + WAVES*j of the tile; it fills 1 KB of LDS,
-    // lane l landing at chunk 64*ij + l.
-    int k_key[K_LD], k_col[K_LD];   // key inside the tile, element offset inside the row
-    int v_row[V_LD], v_col[V_LD];   // element offset of the V^T row, key offset inside the tile
+    const int KT = (p.L + BN - 1) / BN;
+    const bool ragged = (p.L % BN) != 0;
+
+    // ---- per-lane byte offsets of the direct-to-LDS loads, relative to the start of
+    // a tile (K: key row kt*BN of this head; V^T: cache position kt*BN of row 0).
+    // Load j of this wave is instruction ij = wave + WAVES*j of the tile; it fills
+    // 1 KB of LDS, lane l landing at chunk 64*ij + l.  The offsets are the same for
+    // every full tile (the scalar base pointer advances), so a load costs no vector
+    // arithmetic; the last tile has its own set, clamped to the valid length.
+    uint32_t k_off[K_LD], k_off_last[K_LD], v_off[V_LD], v_off_last[V_LD];
+    int v_col[V_LD];  // key offset inside the tile of this lane's V^T chunk
+    {
+        const int last_chunk = ((p.L - 1) >> 3) << 3;  // start of the last 8-key run that holds a valid key
+        const int key_last0 = (KT - 1) * BN;
 #pragma unroll
-    for (int j = 0; j < K_LD; ++j) {
-        const int slot = (wave + WAVES * j) * K_RPI + lane / KCH;  // LDS row
-        const int c = (lane % KCH) ^ chunk_key<KCH>(slot);         // logical chunk stored at this position
-        k_key[j] = (slot & ~31) | swap_bits_2_3(slot & 31);
-        k_col[j] = c * 8;
-    }
+        for (int j = 0; j < K_LD; ++j) {
+            const int slot = (wave + WAVES * j) * K_RPI + lane / KCH;  // LDS row
+            const int c = (lane % KCH) ^ chunk_key<KCH>(slot);         // logical chunk stored at this position
+            const int key = (slot & ~31) | swap_bits_2_3(slot & 31);   // key inside the tile
+            k_off[j] = (uint32_t)(key * DH + c * 8) * 2u;
+            k_off_last[j] = (uint32_t)((min(key_last0 + key, p.L - 1) - key_last0) * DH + c * 8) * 2u;
+        }
 #pragma unroll
-    for (int j = 0; j < V_LD; ++j) {
-        const int d = (wave + WAVES * j) * V_RPI + lane / VCH;
-        const int c = (lane % VCH) ^ chunk_key<VCH>(d);
-        v_row[j] = d * p.L_cap;
-        v_col[j] = c * 8;
+        for (int j = 0; j < V_LD; ++j) {
+            const int d = (wave + WAVES * j) * V_RPI + lane / VCH;     // V^T row
+            const int c = (lane % VCH) ^ chunk_key<VCH>(d);
+            v_col[j] = c * 8;
+            v_off[j] = (uint32_t)(d * p.L_cap + c * 8) * 2u;
+            v_off_last[j] = (uint32_t)(d * p.L_cap + min(key_last0 + c * 8, last_chunk) - key_last0) * 2u;
+        }
     }
-    const int last_chunk = ((p.L - 1) >> 3) << 3;  // start of the last 8-key run that holds a valid key
 
     // K tiles and V^T tiles live in separate two-stage rings: the second MFMA of
     // a tile is deferred to the next iteration (see the schedule below), so
     // iteration k consumes K tile k and V^T tile k-1.
-#define FV_ISSUE_K(kt_)                                                                             \
-    {                                                                                               \
-        const int key0_ = (kt_) * BN;                                                               \
-        u32x4_t* sk_ = lds + ((kt_) & 1) * K_TILE + wave * 64;                                      \
-        _Pragma("unroll") for (int j = 0; j < K_LD; ++j) {                                          \
-            const int key_ = min(key0_ + k_key[j], p.L - 1);                                        \
-            __builtin_amdgcn_global_load_lds(kc + key_ * DH + k_col[j],                             \
-                                             (lds_ptr_t)(sk_ + j * (WAVES * 64)), 16, 0, 0);        \
-        }                                                                                           \
-    }
-#define FV_ISSUE_V(kt_)                                                                             \
-    {                                                                                               \
-        const int key0_ = (kt_) * BN;                                                               \
-        u32x4_t* sv_ = lds + 2 * K_TILE + ((kt_) & 1) * V_TILE + wave * 64;                         \
-        _Pragma("unroll") for (int j = 0; j < V_LD; ++j) {                                          \
-            const int kpos_ = min(key0_ + v_col[j], last_chunk);                                    \
-            __builtin_amdgcn_global_load_lds(vc + v_row[j] + kpos_,                                 \
-                                             (lds_ptr_t)(sv_ + j * (WAVES * 64)), 16, 0, 0);        \
-        }                                                                                           \
-    }
-    // One of this wave's loads of a tile (j_ in [0, K_LD + V_LD): K rows first, then V^T rows)
-    // Written as inline assembly on purpose: after the compiler's own direct-to-LDS
-    // builtin it drains the whole LDS queue (lgkmcnt(0)) before the next operand
-    // use, which would undo the read-ahead of the matrix phase.  Completion is
-    // tracked by hand: every path waits for vmcnt(0) before the barrier that
-    // publishes the tile.
-#define FV_DMA16(gptr_, lds_chunk_ptr_)                                                             \
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                              \
+    //
+    // The loads are written as inline assembly on purpose: after the compiler's own
+    // direct-to-LDS builtin it drains the whole LDS queue (lgkmcnt(0)) before the
+    // next operand use, which would undo the read-ahead of the matrix phase.
+    // Completion is tracked by hand: every path waits for vmcnt(0) before the
+    // barrier that publishes the tile.
+#define FV_DMA16(base_, off_, lds_chunk_ptr_)                                                       \
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"                                \
                  :                                                                                  \
-                 : "s"((uint32_t)(uintptr_t)(lds_ptr_t)(lds_chunk_ptr_)), "v"(gptr_)               \
+                 : "s"((uint32_t)(uintptr_t)(lds_ptr_t)(lds_chunk_ptr_)), "v"(off_), "s"(base_)    \
                  : "memory", "m0")
     // The same load, pinned in the instruction stream: it takes a register of the
     // surrounding arithmetic as a pass-through operand, so it is scheduled after
     // that value's producer and before its consumers.
-#define FV_DMA16_AT(gptr_, lds_chunk_ptr_, reg_)                                                    \
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %2, off"                              \
+#define FV_DMA16_AT(base_, off_, lds_chunk_ptr_, reg_)                                              \
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %2, %3"                                \
                  : "+v"(reg_)                                                                       \
-                 : "s"((uint32_t)(uintptr_t)(lds_ptr_t)(lds_chunk_ptr_)), "v"(gptr_)               \
+                 : "s"((uint32_t)(uintptr_t)(lds_ptr_t)(lds_chunk_ptr_)), "v"(off_), "s"(base_)    \
                  : "memory", "m0")
+    // One of this wave's loads (j_ in [0, K_LD + V_LD): K rows of tile ktk_ first, then
+    // V^T rows of tile ktv_)
 #define FV_ISSUE_ONE_AT(ktk_, ktv_, j_, reg_)                                                       \
     {                                                                                               \
         if ((j_) < K_LD) {                                                                          \
             const int jk_ = (j_) < K_LD ? (j_) : 0;                                                 \
-            const int key_ = min((ktk_) * BN + k_key[jk_], p.L - 1);                                \
-            FV_DMA16_AT(kc + key_ * DH + k_col[jk_],                                                \
+            const uint32_t off_ = ((ktk_) == KT - 1) ? k_off_last[jk_] : k_off[jk_];                \
+            FV_DMA16_AT(kc + (size_t)(ktk_) * (BN * DH), off_,                                      \
                         lds + ((ktk_) & 1) * K_TILE + wave * 64 + jk_ * (WAVES * 64), reg_);        \
         } else {                                                                                    \
             const int jv_ = (j_) >= K_LD ? (j_) - K_LD : 0;                                         \
-            const int kpos_ = min((ktv_) * BN + v_col[jv_], last_chunk);                            \
-            FV_DMA16_AT(vc + v_row[jv_] + kpos_,                                                    \
+            const uint32_t off_ = ((ktv_) == KT - 1) ? v_off_last[jv_] : v_off[jv_];                \
+            FV_DMA16_AT(vc + (size_t)(ktv_) * BN, off_,                                             \
                         lds + 2 * K_TILE + ((ktv_) & 1) * V_TILE + wave * 64 + jv_ * (WAVES * 64), reg_); \
         }                                                                                           \
     }
@@ -202,16 +195,18 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
     {                                                                                               \
         if ((j_) < K_LD) {                                                                          \
             const int jk_ = (j_) < K_LD ? (j_) : 0;                                                 \
-            const int key_ = min((ktk_) * BN + k_key[jk_], p.L - 1);                                \
-            FV_DMA16(kc + key_ * DH + k_col[jk_],                                                   \
+            const uint32_t off_ = ((ktk_) == KT - 1) ? k_off_last[jk_] : k_off[jk_];                \
+            FV_DMA16(kc + (size_t)(ktk_) * (BN * DH), off_,                                         \
                      lds + ((ktk_) & 1) * K_TILE + wave * 64 + jk_ * (WAVES * 64));                 \
         } else {                                                                                    \
             const int jv_ = (j_) >= K_LD ? (j_) - K_LD : 0;                                         \
-            const int kpos_ = min((ktv_) * BN + v_col[jv_], last_chunk);                            \
-            FV_DMA16(vc + v_row[jv_] + kpos_,                                                       \
+            const uint32_t off_ = ((ktv_) == KT - 1) ? v_off_last[jv_] : v_off[jv_];                \
+            FV_DMA16(vc + (size_t)(ktv_) * BN, off_,                                                \
                      lds + 2 * K_TILE + ((ktv_) & 1) * V_TILE + wave * 64 + jv_ * (WAVES * 64));    \
         }                                                                                           \
     }
+#define FV_ISSUE_K(kt_) _Pragma("unroll") for (int j = 0; j < K_LD; ++j) FV_ISSUE_ONE(kt_, 0, j)
+#define FV_ISSUE_V(kt_) _Pragma("unroll") for (int j = K_LD; j < K_LD + V_LD; ++j) FV_ISSUE_ONE(0, kt_, j)
     // Cache positions at or past the length may hold anything (even NaN patterns),
     // and 0 * NaN would poison the output: after its own loads of a partial tile
     // have landed, each lane zeroes the out-of-range positions of its V^T chunks.
@@ -262,9 +257,6 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
     float m_run[QB], l_run[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
-
-    const int KT = (p.L + BN - 1) / BN;
-    const bool ragged = (p.L % BN) != 0;
 
     f32x16_t s_[2][QB];   // scores of this wave's 64-key slice (two 32-key blocks)
     bf16x8_t pf_[4][QB];  // probabilities as the B operand of the second MFMA (four 16-key steps)

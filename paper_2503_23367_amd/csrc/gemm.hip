@@ -102,19 +102,28 @@ __device__ __forceinline__ int swz(int row) {
     return CPR == 8 ? ((row >> 1) & 7) : ((row >> 2) & 3);
 }
 
-template <int BM, int BN, int BK, int STAGES, int EPI>
-__global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
+// WGM x WGN waves tile the BM x BN block; KG such groups of waves split every K
+// tile between them (group g takes the g-th run of 16-wide k-steps) and are
+// summed through LDS at the end.  Eight waves (two per SIMD) cover each other's
+// barrier, load and LDS waits where the tile gives one wave per SIMD too little
+// independent work.
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, int KG, int EPI>
+__global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const GemmParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
-    constexpr int WTM = BM / 2, WTN = BN / 2;  // wave tile (2 x 2 waves)
+    constexpr int NWQ = WGM * WGN;             // waves per k-group
+    constexpr int NW = NWQ * KG;               // waves per workgroup
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
     constexpr int MI = WTM / 32, NI = WTN / 32;
     constexpr int CPR = BK / 8;                // 16-byte chunks per LDS row
     constexpr int RPI = 64 / CPR;              // rows covered by one 64-lane direct-to-LDS load
-    constexpr int KK = BK / 16;                // MFMA k-steps per tile
-    constexpr int A_LD = BM / RPI / 4, W_LD = BN / RPI / 4;  // loads per wave per tile
+    constexpr int KK = BK / 16 / KG;           // MFMA k-steps per tile and k-group
+    constexpr int A_LD = BM / RPI / NW, W_LD = BN / RPI / NW;  // loads per wave per tile
     constexpr int LPT = A_LD + W_LD;
     constexpr int A_TILE = BM * CPR, W_TILE = BN * CPR;      // 16-byte chunks per stage
     constexpr int STAGE = A_TILE + W_TILE;
-    static_assert(KK == 1 || (LPT + KK - 2) / (KK - 1) <= MI + NI, "one load per MFMA group at most");
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0 && (BK / 16) % KG == 0, "wave tiles are made of 32x32x16 MFMAs");
+    static_assert(A_LD * RPI * NW == BM && W_LD * RPI * NW == BN && NW % 2 == 0, "loads must tile the stage");
+    static_assert(KK == 1 || (LPT + KK - 2) / (KK - 1) <= MI + NI, "one load per operand read at most");
     static_assert((STAGES - 2) * LPT <= 63, "vmcnt is 6 bits");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -123,7 +132,10 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
+    const int kg = wave / NWQ;                 // k-group
+    const int wq = wave % NWQ;                 // position in the wave grid
+    const int wm = wq / WGN, wn = wq % WGN;
+    const int kk0 = kg * KK;                   // first k-step of this group inside a tile
 
     // Tile id: consecutive workgroup ids are dealt round-robin to the 8 XCDs;
     // undo that so each XCD (own L2) walks a contiguous run of tiles, and walk
@@ -145,37 +157,39 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
     // 1 KB of LDS (lane l lands at base + 16 l), i.e. RPI whole tile rows.  The
     // swizzle is applied on the global side: lane l fetches the chunk that
     // belongs at its LDS position.  Load j of a wave covers tile rows
-    // (wave + 4 j) * RPI + ld_row; the key of such a row does not depend on j
-    // (RPI is 8 or 16 and the key uses row bits below 4).
+    // (wave + NW j) * RPI + ld_row; the key of such a row does not depend on j
+    // (RPI is 8 or 16, NW is even and the key uses row bits below 4).
     const int ld_row = lane / CPR;
     const int ld_chunk = (lane % CPR) ^ swz<CPR>(wave * RPI + ld_row);
-    int a_off[A_LD], w_off[W_LD];
+    // Per-lane byte offsets of the loads; they do not change along K (the scalar
+    // base pointer advances instead), so a load costs no vector arithmetic.
+    uint32_t a_off[A_LD], w_off[W_LD];
 #pragma unroll
     for (int j = 0; j < A_LD; ++j)
-        a_off[j] = min(m0 + (wave + 4 * j) * RPI + ld_row, p.M - 1) * p.K + ld_chunk * 8;
+        a_off[j] = (uint32_t)(min(m0 + (wave + NW * j) * RPI + ld_row, p.M - 1) * p.K + ld_chunk * 8) * 2u;
 #pragma unroll
     for (int j = 0; j < W_LD; ++j)
-        w_off[j] = min(n0 + (wave + 4 * j) * RPI + ld_row, p.N - 1) * p.K + ld_chunk * 8;
+        w_off[j] = (uint32_t)(min(n0 + (wave + NW * j) * RPI + ld_row, p.N - 1) * p.K + ld_chunk * 8) * 2u;
 
     // The loads are issued through inline assembly: the compiler's own model of
     // this instruction makes it drain every outstanding LDS operation before the
     // next operand use, which would serialise the operand reads behind it.
     // Completion is tracked by hand (vmcnt before the barrier that publishes a tile).
     typedef __attribute__((address_space(3))) void* lds_ptr_t;
-#define FV_DMA16(gptr_, lds_chunk_ptr_)                                                         \
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                          \
+#define FV_DMA16(base_, off_, lds_chunk_ptr_)                                                   \
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"                            \
                  :                                                                              \
-                 : "s"((uint32_t)(uintptr_t)(lds_ptr_t)(lds_chunk_ptr_)), "v"(gptr_)           \
+                 : "s"((uint32_t)(uintptr_t)(lds_ptr_t)(lds_chunk_ptr_)), "v"(off_), "s"(base_) \
                  : "memory", "m0")
     // Load q of a tile (A loads first, then W) into ring stage stage_.
 #define FV_ISSUE_Q(kt_, stage_, q_)                                                             \
     {                                                                                           \
         if ((q_) < A_LD)                                                                        \
-            FV_DMA16(p.A + (size_t)(kt_) * BK + a_off[(q_) < A_LD ? (q_) : 0],                  \
-                     lds + (stage_) * STAGE + wave * 64 + (q_) * 256);                          \
+            FV_DMA16(p.A + (size_t)(kt_) * BK, a_off[(q_) < A_LD ? (q_) : 0],                   \
+                     lds + (stage_) * STAGE + wave * 64 + (q_) * (NW * 64));                    \
         else                                                                                    \
-            FV_DMA16(p.W + (size_t)(kt_) * BK + w_off[(q_) >= A_LD ? (q_) - A_LD : 0],          \
-                     lds + (stage_) * STAGE + A_TILE + wave * 64 + ((q_) - A_LD) * 256);        \
+            FV_DMA16(p.W + (size_t)(kt_) * BK, w_off[(q_) >= A_LD ? (q_) - A_LD : 0],           \
+                     lds + (stage_) * STAGE + A_TILE + wave * 64 + ((q_) - A_LD) * (NW * 64));  \
     }
 #define FV_ISSUE_TILE(kt_, stage_)                                                              \
     _Pragma("unroll") for (int q = 0; q < LPT; ++q) FV_ISSUE_Q(kt_, stage_, q)
@@ -190,7 +204,7 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
     {                                                                                           \
         const u32x4_t* sa_ = lds + (stage_) * STAGE;                                            \
         const u32x4_t* sw_ = sa_ + A_TILE;                                                      \
-        const int ch_ = (2 * (kk_) + frag_half) ^ frag_sw;                                      \
+        const int ch_ = (2 * (kk0 + (kk_)) + frag_half) ^ frag_sw;                              \
         _Pragma("unroll") for (int mi = 0; mi < MI; ++mi)                                       \
             dst_a_[mi] = *reinterpret_cast<const bf16x8_t*>(sa_ + (a_row + 32 * mi) * CPR + ch_); \
         _Pragma("unroll") for (int ni = 0; ni < NI; ++ni)                                       \
@@ -203,7 +217,7 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
     {                                                                                           \
         const u32x4_t* sa_ = lds + (stage_) * STAGE;                                            \
         const u32x4_t* sw_ = sa_ + A_TILE;                                                      \
-        const int ch_ = (2 * (kk_) + frag_half) ^ frag_sw;                                      \
+        const int ch_ = (2 * (kk0 + (kk_)) + frag_half) ^ frag_sw;                              \
         const int q_lo_ = (part_) * LPT / (nparts_), q_hi_ = ((part_) + 1) * LPT / (nparts_); \
         _Pragma("unroll") for (int g = 0; g < MI + NI; ++g) {                                   \
             if (g < MI)                                                                         \
@@ -318,12 +332,43 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
     constexpr int LPR = WTN / 8;           // lanes per row in the read-back phase
     constexpr int RPP = 64 / LPR;          // rows per pass (lanes past RPP * LPR idle when 64 % LPR != 0)
     constexpr int PASSES = (32 + RPP - 1) / RPP;
-    static_assert(4 * 32 * SROW * 4 <= STAGES * (BM + BN) * BK * 2, "staging area must fit in the tile LDS");
+    constexpr int XCH = KG > 1 ? MI * NI * 16 * 64 * NWQ : 0;  // floats handed over by the other k-groups
+    static_assert((XCH + NWQ * 32 * SROW) * 4 <= STAGES * (BM + BN) * BK * 2, "staging must fit in the tile LDS");
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
     __builtin_amdgcn_s_barrier();  // every wave is done reading operand tiles
     asm volatile("" ::: "memory");
-    float* stg = reinterpret_cast<float*>(smem) + wave * (32 * SROW);
+    if (KG > 1) {
+        // Sum the k-groups: group g > 0 writes its accumulators (register-major, lane
+        // contiguous), group 0 adds them; only group 0 goes on to the epilogue.
+        float* xch = reinterpret_cast<float*>(smem) + wq * (MI * NI * 16 * 64) + lane;
+        for (int g = 1; g < KG; ++g) {
+            if (kg == g) {
+                static_for<0, MI * NI * 16>([&](auto i_c) {
+                    constexpr int i = decltype(i_c)::value;
+                    xch[i * 64] = acc[i / (NI * 16)][(i / 16) % NI][i % 16];
+                });
+            }
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            if (kg == 0) {
+                static_for<0, MI * NI * 16>([&](auto i_c) {
+                    constexpr int i = decltype(i_c)::value;
+                    acc[i / (NI * 16)][(i / 16) % NI][i % 16] += xch[i * 64];
+                });
+            }
+            if (g + 1 < KG) {
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+            }
+        }
+        if (kg != 0) return;  // no barrier follows
+    }
+    float* stg = reinterpret_cast<float*>(smem) + XCH + wq * (32 * SROW);
 
     float bias[NI];
 #pragma unroll
@@ -417,18 +462,20 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmParams p) {
 #endif
 }
 
-template <int BM, int BN, int BK, int STAGES, int EPI>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, int KG, int EPI>
 void launch_cfg(GemmParams& p, hipStream_t stream) {
     constexpr size_t smem = (size_t)STAGES * (BM + BN) * BK * sizeof(bf16_t);
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
     static bool attr_set = false;  // raising the dynamic-LDS limit is per function, once per process
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_kernel<BM, BN, BK, STAGES, EPI>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        (void)hipFuncSetAttribute(
+            reinterpret_cast<const void*>(&gemm_nt_kernel<BM, BN, BK, STAGES, WGM, WGN, KG, EPI>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         attr_set = true;
     }
-    gemm_nt_kernel<BM, BN, BK, STAGES, EPI><<<dim3(p.tiles_m * p.tiles_n), 256, smem, stream>>>(p);
+    gemm_nt_kernel<BM, BN, BK, STAGES, WGM, WGN, KG, EPI>
+        <<<dim3(p.tiles_m * p.tiles_n), 64 * WGM * WGN * KG, smem, stream>>>(p);
 }
 
 int gemm_cfg_override() {
@@ -446,9 +493,9 @@ void launch_epi(GemmParams& p, hipStream_t stream) {
     //  * 256-row tiles halve the global->LDS traffic per MFMA and give every wave
     //    sixteen (or twelve) MFMAs per operand-read step, which hides LDS latency
     //    with one wave per SIMD; they win whenever they still give (almost) every
-    //    CU a tile.  The QKV GEMM uses 256x192 (N = 3D divides evenly and the
-    //    epilogue's extra address state fits beside 192 accumulator registers),
-    //    the others 256x256.
+    //    CU a tile.  The QKV GEMM uses 256x192 (N = 3D divides evenly) with eight
+    //    waves of 64x96, whose smaller accumulator leaves room for the epilogue's
+    //    extra address state; the others 256x256 with four waves of 128x128.
     //  * otherwise 128x128 tiles.  At most one tile per CU: three 64-wide K stages
     //    (one workgroup per CU, LDS is free); up to two per CU: four 32-wide stages;
     //    more: two 64-wide stages, several workgroups per CU.
@@ -457,20 +504,21 @@ void launch_epi(GemmParams& p, hipStream_t stream) {
     const long tiles128 = (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
     int cfg;
     if (EPI == EPI_QKV && tiles192 >= 192)
-        cfg = 9;
+        cfg = 12;
     else if (EPI != EPI_QKV && tiles256 >= 192)
         cfg = 1;
     else
         cfg = tiles128 <= 256 ? 7 : (tiles128 <= 512 ? 3 : 6);
     if (gemm_cfg_override() >= 0) cfg = gemm_cfg_override();
     switch (cfg) {
-        case 0: launch_cfg<256, 256, 32, 4, EPI>(p, stream); break;
-        case 1: launch_cfg<256, 256, 64, 2, EPI>(p, stream); break;
-        case 3: launch_cfg<128, 128, 32, 4, EPI>(p, stream); break;
-        case 7: launch_cfg<128, 128, 64, 3, EPI>(p, stream); break;
-        case 9: launch_cfg<256, 192, 64, 2, EPI>(p, stream); break;
-        case 8: launch_cfg<128, 128, 64, 4, EPI>(p, stream); break;
-        default: launch_cfg<128, 128, 64, 2, EPI>(p, stream); break;
+        case 1: launch_cfg<256, 256, 64, 2, 2, 2, 1, EPI>(p, stream); break;
+        case 3: launch_cfg<128, 128, 32, 4, 2, 2, 1, EPI>(p, stream); break;
+        case 7: launch_cfg<128, 128, 64, 3, 2, 2, 1, EPI>(p, stream); break;
+        case 9: launch_cfg<256, 192, 64, 2, 2, 2, 1, EPI>(p, stream); break;
+        case 10: launch_cfg<128, 128, 64, 4, 2, 2, 2, EPI>(p, stream); break;
+        case 11: launch_cfg<256, 256, 64, 2, 2, 4, 1, EPI>(p, stream); break;
+        case 12: launch_cfg<256, 192, 64, 2, 4, 2, 1, EPI>(p, stream); break;
+        default: launch_cfg<128, 128, 64, 2, 2, 2, 1, EPI>(p, stream); break;
     }
 }
 

@@ -258,6 +258,7 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
 
+    const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     f32x16_t s_[2][QB];   // scores of this wave's 64-key slice (two 32-key blocks)
     bf16x8_t pf_[4][QB];  // probabilities as the B operand of the second MFMA (four 16-key steps)
 
@@ -295,9 +296,6 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
             if (NJ_ > 0 && i < SPAN_ && ((i + 1) * NJ_) / SPAN_ > (i * NJ_) / SPAN_)                \
                 FV_ISSUE_ONE((kt_) + 1, (kt_), JLO_ + (i * NJ_) / SPAN_)                            \
         }                                                                                           \
-        _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                            \
-            _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)                                       \
-                _Pragma("unroll") for (int r = 0; r < 16; ++r) s_[kb][qb][r] = 0.f;                 \
         if (HAS_PV_) {                                                                              \
             _Pragma("unroll") for (int t = 0; t < 4; ++t)                                           \
                 _Pragma("unroll") for (int db = 0; db < DB; ++db)                                   \
@@ -309,7 +307,7 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
             _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                        \
                 _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)                                   \
                     s_[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                           \
-                        fr_[NV_ + ks * 2 + kb], qf[qb][ks], s_[kb][qb], 0, 0, 0);                   \
+                        fr_[NV_ + ks * 2 + kb], qf[qb][ks], ks == 0 ? zero16 : s_[kb][qb], 0, 0, 0); \
         __builtin_amdgcn_sched_group_barrier(0x100, DEPTH_, 0);                                     \
         _Pragma("unroll") for (int i = 0; i < NV_ + NK_ - DEPTH_; ++i) {                            \
             __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);                                     \
@@ -371,8 +369,8 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
                     const int e_ = kb * 16 + r;                                                     \
                     if (qb == 0 && NJ_ > 0 && e_ % EVERY_ == 0 && e_ / EVERY_ < NJ_)                \
                         FV_ISSUE_ONE_AT((ktl_) + 1, (ktl_), JLO_ + e_ / EVERY_, pv_)                \
-                    lsum_ += pv_;                                                                   \
                     pf_[2 * kb + (r >> 3)][qb][r & 7] = (__bf16)pv_;                                \
+                    lsum_ += pv_;                                                                   \
                 }                                                                                   \
             l_run[qb] = l_run[qb] * alpha_ + lsum_;                                                 \
             if (__any(alpha_ != 1.0f)) {                                                            \

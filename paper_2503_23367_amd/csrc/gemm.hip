@@ -2,17 +2,18 @@
 // FC2):  C[m,n] = sum_k A[m,k] * W[n,k]  with A [M,K] and W [N,K] both
 // K-contiguous (activations are row-major, weights are [out, in]).
 //
-// Tiling for gfx950: a workgroup of 4 waves owns a BM x BN tile of C; each wave
-// owns a (BM/2) x (BN/2) sub-tile built from 32x32x16 bf16 MFMAs with fp32
-// accumulators.  K is walked in steps of 64: both operand tiles are copied to
-// LDS (double buffered; the next tile's global loads are in flight while the
-// current one is multiplied) in rows of 128 bytes whose 16-byte chunks are
-// XOR-swizzled with the row index, so the MFMA operand reads (one 16-byte
+// Tiling for gfx950: a workgroup of 4 or 8 waves owns a BM x BN tile of C; each
+// wave owns a sub-tile built from 32x32x16 bf16 MFMAs with fp32 accumulators.
+// K is walked in tiles of BK: both operand tiles are copied global -> LDS by
+// direct-to-LDS loads into a ring of STAGES stages (the next tiles' loads are in
+// flight while the current one is multiplied), in rows whose 16-byte chunks are
+// XOR-swizzled with the row index so that the MFMA operand reads (one 16-byte
 // ds_read per lane, 32 consecutive rows per half-wave) are conflict free.
 //
-// Epilogues are fused: bias, residual add, exact GELU, and for the QKV GEMM
-// the split into the query buffer and the append into the K / V caches
+// Epilogues are fused: bias, residual add, GELU, and for the QKV GEMM the
+// split into the query buffer and the append into the K / V caches
 // (V transposed so that cache positions are contiguous).
+#include <stdio.h>
 #include <stdlib.h>
 
 #include "common.h"
@@ -478,13 +479,18 @@ void launch_cfg(GemmParams& p, hipStream_t stream) {
         <<<dim3(p.tiles_m * p.tiles_n), 64 * WGM * WGN * KG, smem, stream>>>(p);
 }
 
-int gemm_cfg_override() {
-    static int v = -2;
-    if (v == -2) {
-        const char* e = getenv("FASTVAR_GEMM_CFG");
-        v = e ? atoi(e) : -1;
+// Developer knob: FASTVAR_GEMM_CFG (all epilogues) or FASTVAR_GEMM_CFG<e> (epilogue e = 0, 1, 2)
+// forces a tile configuration; unset means the heuristic below.
+int gemm_cfg_override(int epi) {
+    static int v[3] = {-2, -2, -2};
+    if (v[epi] == -2) {
+        char name[32];
+        snprintf(name, sizeof(name), "FASTVAR_GEMM_CFG%d", epi);
+        const char* e = getenv(name);
+        if (!e) e = getenv("FASTVAR_GEMM_CFG");
+        v[epi] = e ? atoi(e) : -1;
     }
-    return v;
+    return v[epi];
 }
 
 template <int EPI>
@@ -509,7 +515,7 @@ void launch_epi(GemmParams& p, hipStream_t stream) {
         cfg = 1;
     else
         cfg = tiles128 <= 256 ? 7 : (tiles128 <= 512 ? 3 : 6);
-    if (gemm_cfg_override() >= 0) cfg = gemm_cfg_override();
+    if (gemm_cfg_override(EPI) >= 0) cfg = gemm_cfg_override(EPI);
     switch (cfg) {
         case 1: launch_cfg<256, 256, 64, 2, 2, 2, 1, EPI>(p, stream); break;
         case 3: launch_cfg<128, 128, 32, 4, 2, 2, 1, EPI>(p, stream); break;

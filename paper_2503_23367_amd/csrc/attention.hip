@@ -515,6 +515,489 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
 #endif
 }
 
+// ---------------------------------------------------------------------------------------------
+// Software-pipelined variant for long key sequences (L > 2 tiles): one wave per SIMD owns 64
+// queries, so every K / V^T fragment read from LDS feeds two MFMAs, and the softmax of one
+// 32-key block is interleaved, inside the same wave, with the MFMAs of its neighbours:
+//   step s:  softmax(block s)   |   S(block s+1) = K Q^T   |   O^T += V^T P^T (block s-1)
+// About four vector instructions fit in the shadow of one 32-cycle MFMA, which is what the
+// softmax of a 32x64 block needs per MFMA of the two products around it.  Scores and
+// probabilities are double buffered by name (two instantiations of the step), a wave's 64-key
+// slice of a tile is two steps, and there is one barrier per tile, between the two steps:
+// it publishes K tile kt+1 and V^T tile kt (fetched during the previous tile's second step) and
+// frees K tile kt and V^T tile kt-1, whose stages the second step refills.
+// The last tile is shifted back so that it ends at the (8-aligned) end of the cache: it never
+// reads past L_cap, its leading keys (already seen) and the up to 7 positions past L are masked.
+template <int DH, int QG, int KSPLIT>
+__global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(const AttnParams p) {
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
+    constexpr int QB = 2;
+    constexpr int WAVES = QG * KSPLIT;
+    constexpr int BN = 64 * KSPLIT;        // keys per tile
+    constexpr int KCH = DH / 8;            // 16-byte chunks per key row
+    constexpr int KS = DH / 16;            // MFMA k-steps over the head dim
+    constexpr int DB = DH / 32;            // 32-row blocks of O^T
+    constexpr int VCH = BN / 8;            // 16-byte chunks per V^T row
+    constexpr int K_TILE = BN * KCH;       // chunks per K tile
+    constexpr int V_TILE = DH * VCH;       // chunks per V^T tile
+    constexpr int K_RPI = 64 / KCH;        // key rows per 64-lane direct-to-LDS load
+    constexpr int V_RPI = 64 / VCH;        // V^T rows per load
+    constexpr int K_LD = BN / K_RPI / WAVES;   // loads per wave per tile
+    constexpr int V_LD = DH / V_RPI / WAVES;
+    static_assert(K_LD >= 1 && V_LD >= 1 && K_LD + V_LD <= 2 * DB + KS, "one load per operand read at most");
+    static_assert(WAVES * K_RPI % 32 == 0 || WAVES * K_RPI == 16, "key rows of a wave's loads must differ by a constant");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    u32x4_t* lds = reinterpret_cast<u32x4_t*>(smem);  // [2][K tile] then [2][V^T tile]
+    typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int qg = wave / KSPLIT;       // query group
+    const int kh = wave % KSPLIT;       // key slice inside a tile
+    const int li = lane & 31;           // query column / operand row
+    const int hf = lane >> 5;           // half-wave
+    const int sw_k = chunk_key<KCH>(li);
+    const int sw_v = chunk_key<VCH>(li);
+    int wg = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    const int n_wg = gridDim.x * gridDim.y * gridDim.z;
+    if ((n_wg & 7) == 0) wg = (wg & 7) * (n_wg >> 3) + (wg >> 3);  // XCD-aware order, as above
+    const int q_tile = wg % gridDim.x;
+    const int head = (wg / gridDim.x) % gridDim.y;
+    const int b = wg / (gridDim.x * gridDim.y);
+    const int q_base = q_tile * (QG * 32 * QB) + qg * (32 * QB);
+
+    const bf16_t* kc = p.kc + ((size_t)b * p.H + head) * p.L_cap * DH;
+    const bf16_t* vc = p.vc + ((size_t)b * p.H + head) * DH * (size_t)p.L_cap;
+
+    const int KT = (p.L + BN - 1) / BN;                 // >= 3, checked by the launcher
+    const int last_start = ((p.L + 7) & ~7) - BN;       // first key of the shifted last tile
+    const int last_first_new = (KT - 1) * BN;           // keys before this one were seen in tile KT-2
+#define FP_TILE_START(kt_) ((kt_) == KT - 1 ? last_start : (kt_) * BN)
+
+    // Per-lane byte offsets of this wave's loads inside a tile; load j adds a scalar constant.
+    uint32_t k_off0, v_off0;
+    int v_col0;   // key offset inside the tile of this lane's V^T chunk (the same for every load)
+    {
+        const int slot = wave * K_RPI + lane / KCH;
+        const int c = (lane % KCH) ^ chunk_key<KCH>(slot);
+        const int key = (slot & ~31) | swap_bits_2_3(slot & 31);
+        k_off0 = (uint32_t)(key * DH + c * 8) * 2u;
+        const int d = wave * V_RPI + lane / VCH;
+        const int cv = (lane % VCH) ^ chunk_key<VCH>(d);
+        v_col0 = cv * 8;
+        v_off0 = (uint32_t)(d * p.L_cap + cv * 8) * 2u;
+    }
+#define FP_DMA16(base_, off_, lds_chunk_ptr_)                                                       \
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"                                \
+                 :                                                                                  \
+                 : "s"((uint32_t)(uintptr_t)(lds_ptr_t)(lds_chunk_ptr_)), "v"(off_), "s"(base_)    \
+                 : "memory", "m0")
+    // load j_ of this wave: K rows of tile ktk_ for j_ < K_LD, then V^T rows of tile ktv_
+#define FP_ISSUE_ONE(ktk_, ktv_, j_)                                                                \
+    {                                                                                               \
+        if ((j_) < K_LD) {                                                                          \
+            FP_DMA16(kc + ((size_t)FP_TILE_START(ktk_) + (j_) * (WAVES * K_RPI)) * DH, k_off0,      \
+                     lds + ((ktk_) & 1) * K_TILE + wave * 64 + (j_) * (WAVES * 64));                \
+        } else {                                                                                    \
+            FP_DMA16(vc + (size_t)((j_) - K_LD) * (WAVES * V_RPI) * p.L_cap + FP_TILE_START(ktv_), v_off0, \
+                     lds + 2 * K_TILE + ((ktv_) & 1) * V_TILE + wave * 64 + ((j_) - K_LD) * (WAVES * 64)); \
+        }                                                                                           \
+    }
+    // zero the V^T LDS positions of tile KT-1 that lie at or past the length (they may hold NaN
+    // patterns and 0 * NaN would poison the output); own loads have landed (vmcnt(0) before)
+#define FP_FIX_TAIL()                                                                               \
+    {                                                                                               \
+        u32x4_t* sv_ = lds + 2 * K_TILE + ((KT - 1) & 1) * V_TILE + wave * 64 + lane;               \
+        const int valid_ = p.L - (last_start + v_col0);                                             \
+        if (valid_ < 8) {                                                                           \
+            _Pragma("unroll") for (int j = 0; j < V_LD; ++j) {                                      \
+                u32x4_t v_ = sv_[j * (WAVES * 64)];                                                 \
+                v_.x = valid_ >= 2 ? v_.x : (valid_ >= 1 ? (v_.x & 0xFFFFu) : 0u);                  \
+                v_.y = valid_ >= 4 ? v_.y : (valid_ >= 3 ? (v_.y & 0xFFFFu) : 0u);                  \
+                v_.z = valid_ >= 6 ? v_.z : (valid_ >= 5 ? (v_.z & 0xFFFFu) : 0u);                  \
+                v_.w = valid_ >= 7 ? (v_.w & 0xFFFFu) : 0u;                                         \
+                sv_[j * (WAVES * 64)] = v_;                                                         \
+            }                                                                                       \
+        }                                                                                           \
+    }
+#define FP_PUBLISH()                                                                                \
+    {                                                                                               \
+        asm volatile("" ::: "memory");                                                              \
+        __builtin_amdgcn_s_waitcnt(attn_waitcnt(0, true));                                          \
+        __builtin_amdgcn_s_barrier();                                                               \
+        asm volatile("" ::: "memory");                                                              \
+    }
+
+    // Q^T operand fragments: lane (li, hf) holds q[query li][16*ks + 8*hf .. +8)
+    bf16x8_t qf[QB][KS];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const int qrow = min(q_base + qb * 32 + li, p.k_tokens - 1);
+        const bf16_t* src = p.q + ((size_t)b * p.k_tokens + qrow) * p.D + head * DH + hf * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = *reinterpret_cast<const bf16x8_t*>(src + ks * 16);
+    }
+
+    const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f32x16_t acc[DB][QB];
+    float m_run[QB], l_run[QB];
+    f32x16_t sa_[QB], sb_[QB];        // scores of two consecutive 32-key blocks
+    bf16x8_t pa_[2][QB], pb_[2][QB];  // their probabilities as B operands (two 16-key steps each)
+    bf16x8_t fe_[16], fo_[16];        // operand fragments of the first / second step of a tile
+
+    // S = K Q^T accumulates in vector registers (the softmax reads it there); the MFMA is written
+    // as inline assembly because the compiler's own form of it, in a kernel this large, puts every
+    // MFMA result in the accumulator file and copies it out again for the vector unit.
+    // The leading wait states stand in for the ones the compiler inserts before its own MFMAs
+    // (it cannot see through the assembly: without them the results are wrong); they cost nothing,
+    // the wave is waiting for the matrix pipe at that point anyway.
+#define FP_MFMA_S0(S_, a_, b_) \
+    asm("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(S_) : "v"(a_), "v"(b_))
+#define FP_MFMA_S(S_, a_, b_) \
+    asm("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(S_) : "v"(a_), "v"(b_))
+
+    // The exponentials of a block are numbered e = 16*qb + r (32 per step).  A half-group starts
+    // one or two of them (multiply-add), takes the exp2 of those the half-group before it started
+    // and consumes the ones before that (row-sum add; bf16 pack once a pair is complete): the wave
+    // issues in order, so a value must not be used in the half-group that computes it.
+#define FP_ARG(S_, e_) \
+    px_[e_] = fmaf(S_[(e_) / 16][(e_) % 16], p.scale_log2e, -m_use_[(e_) / 16]);
+#define FP_EXP(e_) pe_[e_] = __builtin_amdgcn_exp2f(px_[e_]);
+#define FP_CONSUME(P_, e_)                                                                          \
+    {                                                                                               \
+        lsum_[(e_) / 16] += pe_[e_];                                                                \
+        if ((e_) % 2 == 1) {                                                                        \
+            P_[((e_) % 16) >> 3][(e_) / 16][((e_) % 16 & 7) - 1] = (__bf16)pe_[(e_) - 1];           \
+            P_[((e_) % 16) >> 3][(e_) / 16][(e_) % 16 & 7] = (__bf16)pe_[e_];                       \
+        }                                                                                           \
+    }
+    // Half-group hh_ (0..31: two per group) starts elements [FP_E0(hh_), FP_E0(hh_+1)).  With the
+    // running maximum the first eight half-groups are busy with the maxima and the 32 elements are
+    // spread 2,1,1,2,... over the other 24; in fast mode every half-group starts exactly one.
+#define FP_E0(RESC_, hh_) \
+    ((hh_) < 0 ? 0 : (RESC_) ? ((hh_) < 8 ? 0 : ((hh_) - 8) + (((hh_) - 8) + 2) / 3) : ((hh_) > 32 ? 32 : (hh_)))
+#define FP_HALF(RESC_, S_, P_, hh_)                                                                 \
+    {                                                                                               \
+        constexpr int x0_ = FP_E0(RESC_, hh_), x1_ = FP_E0(RESC_, (hh_) + 1);                       \
+        constexpr int e0_ = FP_E0(RESC_, (hh_) - 1), e1_ = x0_;                                     \
+        constexpr int c0_ = FP_E0(RESC_, (hh_) - 2), c1_ = e0_;                                     \
+        if (x1_ - x0_ >= 1) { FP_ARG(S_, (x1_ - x0_ >= 1 ? x0_ : 0)) }                              \
+        if (x1_ - x0_ == 2) { FP_ARG(S_, (x1_ - x0_ == 2 ? x0_ + 1 : 0)) }                          \
+        if (e1_ - e0_ >= 1) { FP_EXP((e1_ - e0_ >= 1 ? e0_ : 0)) }                                  \
+        if (e1_ - e0_ == 2) { FP_EXP((e1_ - e0_ == 2 ? e0_ + 1 : 0)) }                              \
+        if (c1_ - c0_ >= 1) FP_CONSUME(P_, (c1_ - c0_ >= 1 ? c0_ : 1))                              \
+        if (c1_ - c0_ == 2) FP_CONSUME(P_, (c1_ - c0_ == 2 ? c0_ + 1 : 1))                          \
+    }
+    // One step.  S_SM_/P_SM_: block whose softmax is taken (scores in, probabilities out; first key
+    // key0_sm_, MASK_ for blocks of the last tile).  DO_QK_: S_QK_ = K Q^T for the 32 key rows at
+    // kbase_.  DO_PV_: O^T += V^T P^T with P_PV_ and the V^T chunks vchunk0_ .. +3 of the tile at
+    // vbase_.  LOAD_K_ / LOAD_V_: this wave's loads of K tile ktk_ / V^T tile ktv_ go out, one per
+    // group.  The step is written as 16 groups that the scheduler may not mix: two MFMAs (one
+    // operand fragment, both query blocks), the read of the fragment DEPTH groups ahead, one load,
+    // and a slice of the softmax: groups 0-3 take the row maxima (masking first where needed),
+    // groups 4-15 the exponentials, two at a time.
+    // RESC_ = true: online softmax with a running maximum; the output accumulator is rescaled under
+    // a branch when the maximum moves.  RESC_ = false (fast mode): the maximum stays where the first
+    // tile left it (softmax is shift invariant; fp32 has the range), so there are no maxima to take,
+    // the step is branch free and the accumulator never leaves the accumulator file.  Should a later
+    // score exceed the reference by so much that exp2 endangers the fp32 range, the row sum shows it
+    // and the caller repeats the whole computation with RESC_ = true.
+    // group g_ of a step (a literal, so that every index below is a compile-time constant)
+#define FP_G(g_, RESC_, S_SM_, P_SM_, key0_sm_, MASK_, DO_QK_, S_QK_, kbase_, DO_PV_, P_PV_, vbase_, vchunk0_, \
+             LOAD_K_, ktk_, LOAD_V_, ktv_, FR_, NFR_, N_DO_PV_, nvbase_, nvchunk0_, BAR_)           \
+    {                                                                                               \
+        constexpr int gg = (g_);                                                                    \
+        constexpr int f = gg + DEPTH_;      /* operand fragment read in this group */               \
+        if ((BAR_) && gg == NG_ - DEPTH_) {                                                         \
+            /* every read of the old tiles has been issued: publish the tiles fetched during the */ \
+            /* previous step, free the old ones (the next step's first operands come from the new) */ \
+            asm volatile("" ::: "memory");                                                          \
+            __builtin_amdgcn_s_waitcnt(attn_waitcnt(0, true));                                      \
+            if ((MASK_) && ((p.L & 7) != 0)) FP_FIX_TAIL()                                          \
+            FP_PUBLISH()                                                                            \
+        }                                                                                           \
+        if (f < NV_ && (DO_PV_))                                                                    \
+            FR_[f < NV_ ? f : 0] = *reinterpret_cast<const bf16x8_t*>(                              \
+                (vbase_) + ((f % DB) * 32 + li) * VCH + (((vchunk0_) + 2 * (f / DB) + hf) ^ sw_v)); \
+        if (f >= NV_ && f < NG_ && (DO_QK_))                                                        \
+            FR_[f < NG_ ? f : 0] = *reinterpret_cast<const bf16x8_t*>(                              \
+                (kbase_) + li * KCH + ((2 * (f - NV_) + hf) ^ sw_k));                               \
+        if (f >= NG_ && (N_DO_PV_))         /* the first operands of the next step */               \
+            NFR_[f >= NG_ ? f - NG_ : 0] = *reinterpret_cast<const bf16x8_t*>(                      \
+                (nvbase_) + ((f >= NG_ ? f - NG_ : 0) * 32 + li) * VCH + (((nvchunk0_) + hf) ^ sw_v)); \
+        {                                                                                           \
+            if (gg < NJ_) FP_ISSUE_ONE(ktk_, ktv_, JLO_ + gg)                                       \
+            /* two halves, each one MFMA (query block 0, then 1) with its share of the softmax: */  \
+            /* the wave issues in order, so the vector work must sit between the two MFMAs */      \
+            /* ---- first half */                                                                   \
+            if (gg < NV_ && (DO_PV_))                                                               \
+                acc[gg % DB][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                          \
+                    FR_[gg], P_PV_[(gg / DB) % 2][0], acc[gg % DB][0], 0, 0, 0);                    \
+            if (gg == NV_ && (DO_QK_)) FP_MFMA_S0(S_QK_[0], FR_[gg], qf[0][0]);                     \
+            if (gg > NV_ && (DO_QK_)) FP_MFMA_S(S_QK_[0], FR_[gg], qf[0][gg > NV_ ? gg - NV_ : 0]); \
+            if ((MASK_) && (gg == 0 || gg == 2)) {                                                  \
+                constexpr int qb = gg / 2 % 2;                                                      \
+                _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                    \
+                    const int key_ = (key0_sm_) + swap_bits_2_3(8 * (r >> 2) + 4 * hf + (r & 3));   \
+                    if (key_ >= p.L || key_ < last_first_new) S_SM_[qb][r] = -INFINITY;             \
+                }                                                                                   \
+            }                                                                                       \
+            if ((RESC_) && (gg == 1 || gg == 3)) {                                                  \
+                /* two independent chains over the first eight scores */                            \
+                constexpr int qb = gg / 2 % 2;                                                      \
+                mxa_ = fmaxf(fmaxf(S_SM_[qb][0], S_SM_[qb][1]), S_SM_[qb][2]);                      \
+                mxb_ = fmaxf(fmaxf(S_SM_[qb][3], S_SM_[qb][4]), S_SM_[qb][5]);                      \
+                mxa_ = fmaxf(fmaxf(mxa_, S_SM_[qb][6]), S_SM_[qb][7]);                              \
+            }                                                                                       \
+            FP_HALF(RESC_, S_SM_, P_SM_, 2 * gg)                                                    \
+            __builtin_amdgcn_sched_barrier(0);                                                      \
+            /* ---- second half */                                                                  \
+            if (gg < NV_ && (DO_PV_))                                                               \
+                acc[gg % DB][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                          \
+                    FR_[gg], P_PV_[(gg / DB) % 2][1], acc[gg % DB][1], 0, 0, 0);                    \
+            if (gg == NV_ && (DO_QK_)) FP_MFMA_S0(S_QK_[1], FR_[gg], qf[1][0]);                     \
+            if (gg > NV_ && (DO_QK_)) FP_MFMA_S(S_QK_[1], FR_[gg], qf[1][gg > NV_ ? gg - NV_ : 0]); \
+            if ((RESC_) && (gg == 1 || gg == 3)) {                                                  \
+                constexpr int qb = gg / 2 % 2;                                                      \
+                mxb_ = fmaxf(fmaxf(mxb_, S_SM_[qb][8]), S_SM_[qb][9]);                              \
+                mxa_ = fmaxf(fmaxf(mxa_, S_SM_[qb][10]), S_SM_[qb][11]);                            \
+                mxb_ = fmaxf(fmaxf(mxb_, S_SM_[qb][12]), S_SM_[qb][13]);                            \
+                mxa_ = fmaxf(fmaxf(mxa_, S_SM_[qb][14]), S_SM_[qb][15]);                            \
+                float mx_ = fmaxf(mxa_, mxb_);                                                      \
+                mx_ = fmaxf(mx_, other_half(mx_));                                                  \
+                const float m_new_ = fmaxf(m_run[qb], mx_ * p.scale_log2e);                         \
+                m_use_[qb] = (m_new_ == -INFINITY) ? 0.f : m_new_;                                  \
+                alpha_[qb] = __builtin_amdgcn_exp2f(m_run[qb] - m_use_[qb]);                        \
+                m_run[qb] = m_new_;                                                                 \
+            }                                                                                       \
+            FP_HALF(RESC_, S_SM_, P_SM_, 2 * gg + 1)                                                \
+            __builtin_amdgcn_sched_barrier(0);                                                      \
+        }                                                                                           \
+    }
+#define FP_STEP(RESC_, S_SM_, P_SM_, key0_sm_, MASK_, DO_QK_, S_QK_, kbase_, DO_PV_, P_PV_, vbase_, vchunk0_, \
+                LOAD_K_, ktk_, LOAD_V_, ktv_, FR_, NFR_, N_DO_PV_, nvbase_, nvchunk0_, BAR_)        \
+    {                                                                                               \
+        constexpr int NV_ = 2 * DB;                                                                 \
+        constexpr int NG_ = 2 * DB + KS;           /* groups = fragments */                         \
+        static_assert(NG_ == 16, "the group list below is written for 16 groups");                  \
+        constexpr int JLO_ = (LOAD_K_) ? 0 : K_LD;                                                  \
+        constexpr int JHI_ = (LOAD_V_) ? K_LD + V_LD : K_LD;                                        \
+        constexpr int NJ_ = JHI_ > JLO_ ? JHI_ - JLO_ : 0;                                          \
+        constexpr int DEPTH_ = 4;                                                                   \
+        float m_use_[QB], alpha_[QB], lsum_[QB], px_[32], pe_[32], mxa_ = 0.f, mxb_ = 0.f;          \
+        _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                         \
+            m_use_[qb] = m_run[qb];   /* fast mode: the reference stays; else replaced in groups 1, 3 */ \
+            alpha_[qb] = 1.0f;                                                                      \
+            lsum_[qb] = 0.f;                                                                        \
+        }                                                                                           \
+        FP_G(0, RESC_, S_SM_, P_SM_, key0_sm_, MASK_, DO_QK_, S_QK_, kbase_, DO_PV_, P_PV_, vbase_, vchunk0_, LOAD_K_, ktk_, LOAD_V_, ktv_, FR_, NFR_, N_DO_PV_, nvbase_, nvchunk0_, BAR_) \
+        FP_G(1, RESC_, S_SM_, P_SM_, key0_sm_, MASK_, DO_QK_, S_QK_, kbase_, DO_PV_, P_PV_, vbase_, vchunk0_, LOAD_K_, ktk_, LOAD_V_, ktv_, FR_, NFR_, N_DO_PV_, nvbase_, nvchunk0_, BAR_) \
+        FP_G(2, RESC_, S_SM_, P_SM_, key0_sm_, MASK_, DO_QK_, S_QK_, kbase_, DO_PV_, P_PV_, vbase_, vchunk0_, LOAD_K_, ktk_, LOAD_V_, ktv_, FR_, NFR_, N_DO_PV_, nvbase_, nvchunk0_, BAR_) \
+        FP_G(3, RESC_, S_SM_, P_SM_, key0_sm_, MASK_, DO_QK_, S_QK_, kbase_, DO_PV_, P_PV_, vbase_, vchunk0_, LOAD_K_, ktk_, LOAD_V_, ktv_, FR_, NFR_, N_DO_PV_, nvbase_, nvchunk0_, BAR_) \
+        FP_G(4, RESC_, S_SM_, P_SM_, key0_sm_, MASK_, DO_QK_, S_QK_, kbase_, DO_PV_, P_PV_, vbase_, vchunk0_, LOAD_K_, ktk_, LOAD_V_, ktv_, FR_, NFR_, N_DO_PV_, nvbase_, nvchunk0_, BAR_) \
+        FP_G(5, RESC_, S_SM_, P_SM_, key0_sm_, MASK_, DO_QK_, S_QK_, kbase_, DO_PV_, P_PV_, vbase_, vchunk0_, LOAD_K_, ktk_, LOAD_V_, ktv_, FR_, NFR_, N_DO_PV_, nvbase_, nvchunk0_, BAR_) \
+        FP_G(6, RESC_, S_SM_, P_SM_, key0_sm_, MASK_, DO_QK_, S_QK_, kbase_, DO_PV_, P_PV_, vbase_, vchunk0_, LOAD_K_, ktk_, LOAD_V_, ktv_, FR_, NFR_, N_DO_PV_, nvbase_, nvchunk0_, BAR_) \
+        FP_G(7, RESC_, S_SM_, P_SM_, key0_sm_, MASK_, DO_QK_, S_QK_, kbase_, DO_PV_, P_PV_, vbase_, vchunk0_, LOAD_K_, ktk_, LOAD_V_, ktv_, FR_, NFR_, N_DO_PV_, nvbase_, nvchunk0_, BAR_) \
+        FP_G(8, RESC_, S_SM_, P_SM_, key0_sm_, MASK_, DO_QK_, S_QK_, kbase_, DO_PV_, P_PV_, vbase_, vchunk0_, LOAD_K_, ktk_, LOAD_V_, ktv_, FR_, NFR_, N_DO_PV_, nvbase_, nvchunk0_, BAR_) \
+        FP_G(9, RESC_, S_SM_, P_SM_, key0_sm_, MASK_, DO_QK_, S_QK_, kbase_, DO_PV_, P_PV_, vbase_, vchunk0_, LOAD_K_, ktk_, LOAD_V_, ktv_, FR_, NFR_, N_DO_PV_, nvbase_, nvchunk0_, BAR_) \
+        FP_G(10, RESC_, S_SM_, P_SM_, key0_sm_, MASK_, DO_QK_, S_QK_, kbase_, DO_PV_, P_PV_, vbase_, vchunk0_, LOAD_K_, ktk_, LOAD_V_, ktv_, FR_, NFR_, N_DO_PV_, nvbase_, nvchunk0_, BAR_) \
+        FP_G(11, RESC_, S_SM_, P_SM_, key0_sm_, MASK_, DO_QK_, S_QK_, kbase_, DO_PV_, P_PV_, vbase_, vchunk0_, LOAD_K_, ktk_, LOAD_V_, ktv_, FR_, NFR_, N_DO_PV_, nvbase_, nvchunk0_, BAR_) \
+        FP_G(12, RESC_, S_SM_, P_SM_, key0_sm_, MASK_, DO_QK_, S_QK_, kbase_, DO_PV_, P_PV_, vbase_, vchunk0_, LOAD_K_, ktk_, LOAD_V_, ktv_, FR_, NFR_, N_DO_PV_, nvbase_, nvchunk0_, BAR_) \
+        FP_G(13, RESC_, S_SM_, P_SM_, key0_sm_, MASK_, DO_QK_, S_QK_, kbase_, DO_PV_, P_PV_, vbase_, vchunk0_, LOAD_K_, ktk_, LOAD_V_, ktv_, FR_, NFR_, N_DO_PV_, nvbase_, nvchunk0_, BAR_) \
+        FP_G(14, RESC_, S_SM_, P_SM_, key0_sm_, MASK_, DO_QK_, S_QK_, kbase_, DO_PV_, P_PV_, vbase_, vchunk0_, LOAD_K_, ktk_, LOAD_V_, ktv_, FR_, NFR_, N_DO_PV_, nvbase_, nvchunk0_, BAR_) \
+        FP_G(15, RESC_, S_SM_, P_SM_, key0_sm_, MASK_, DO_QK_, S_QK_, kbase_, DO_PV_, P_PV_, vbase_, vchunk0_, LOAD_K_, ktk_, LOAD_V_, ktv_, FR_, NFR_, N_DO_PV_, nvbase_, nvchunk0_, BAR_) \
+        /* what the last half-groups left in flight */                                              \
+        FP_EXP(31)                                                                                  \
+        FP_CONSUME(P_SM_, 30)                                                                       \
+        FP_CONSUME(P_SM_, 31)                                                                       \
+        _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                         \
+            if (RESC_) l_run[qb] = l_run[qb] * alpha_[qb] + lsum_[qb];                              \
+            else l_run[qb] += lsum_[qb];                                                            \
+            /* the probabilities are first used in the next step: keep their arithmetic here */    \
+            asm volatile("" : "+v"(P_SM_[0][qb]), "+v"(P_SM_[1][qb]), "+v"(l_run[qb]));             \
+        }                                                                                           \
+        if (RESC_) {                                                                                \
+            /* O is relative to the old maximum */                                                  \
+            _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                     \
+                if (__any(alpha_[qb] != 1.0f)) {                                                    \
+                    _Pragma("unroll") for (int db = 0; db < DB; ++db)                               \
+                        _Pragma("unroll") for (int r = 0; r < 16; ++r) acc[db][qb][r] *= alpha_[qb]; \
+                }                                                                                   \
+            }                                                                                       \
+        }                                                                                           \
+    }
+    // One tile = two steps.  FIRST_: no previous block to multiply; HAS_K2_: K tile kt+2 exists;
+    // HAS_NEXT_: tile kt+1 exists; LAST_: this is the shifted last tile.  The barrier sits inside
+    // the first step, after its last read of the old tiles.
+#define FP_TILE(RESC_, kt_, FIRST_, HAS_K2_, HAS_NEXT_, LAST_)                                      \
+    {                                                                                               \
+        const int start_ = FP_TILE_START(kt_) + kh * 64;                                            \
+        const u32x4_t* ks_ = lds + ((kt_) & 1) * K_TILE + (kh * 64) * KCH;       /* K tile kt */     \
+        const u32x4_t* kn_ = lds + (((kt_) + 1) & 1) * K_TILE + (kh * 64) * KCH; /* K tile kt+1 */   \
+        const u32x4_t* vp_ = lds + 2 * K_TILE + (((kt_) + 1) & 1) * V_TILE;      /* V^T tile kt-1 */ \
+        const u32x4_t* vs_ = lds + 2 * K_TILE + ((kt_) & 1) * V_TILE;            /* V^T tile kt */   \
+        /* first step: softmax(kt,0); S(kt,1); PV(kt-1,1); next step starts with V^T(kt) block 0 */ \
+        FP_STEP(RESC_, sa_, pa_, start_, LAST_, true, sb_, ks_ + 32 * KCH, !(FIRST_), pb_, vp_, kh * 8 + 4, \
+                false, 0, false, 0, fe_, fo_, true, vs_, kh * 8, true)                              \
+        /* second step: softmax(kt,1); S(kt+1,0); PV(kt,0); fetch K tile kt+2 and V^T tile kt+1; */ \
+        /* next step starts with V^T(kt) block 1 */                                                 \
+        FP_STEP(RESC_, sb_, pb_, start_ + 32, LAST_, HAS_NEXT_, sa_, kn_, true, pa_, vs_, kh * 8,   \
+                HAS_K2_, (kt_) + 2, HAS_NEXT_, (kt_) + 1, fo_, fe_, HAS_NEXT_, vs_, kh * 8 + 4, false) \
+    }
+    // The whole pass over the keys.  The first tile always runs with the running maximum (it
+    // establishes the reference); REST_ selects the mode of the others.
+#define FP_RUN(REST_)                                                                               \
+    {                                                                                               \
+        _Pragma("unroll") for (int db = 0; db < DB; ++db)                                           \
+            _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) acc[db][qb] = zero16;                 \
+        _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; } \
+        /* K tiles 0 and 1, V^T tile 0; first score block */                                        \
+        _Pragma("unroll") for (int j = 0; j < K_LD; ++j) FP_ISSUE_ONE(0, 0, j)                      \
+        _Pragma("unroll") for (int j = 0; j < K_LD; ++j) FP_ISSUE_ONE(1, 0, j)                      \
+        _Pragma("unroll") for (int j = K_LD; j < K_LD + V_LD; ++j) FP_ISSUE_ONE(0, 0, j)            \
+        FP_PUBLISH()                                                                                \
+        {                                                                                           \
+            const u32x4_t* k0_ = lds + (kh * 64) * KCH;                                             \
+            _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                     \
+                const bf16x8_t kf_ =                                                                \
+                    *reinterpret_cast<const bf16x8_t*>(k0_ + li * KCH + ((2 * ks + hf) ^ sw_k));    \
+                _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                 \
+                    if (ks == 0) FP_MFMA_S0(sa_[qb], kf_, qf[qb][ks]);                              \
+                    else FP_MFMA_S(sa_[qb], kf_, qf[qb][ks]);                                       \
+                }                                                                                   \
+            }                                                                                       \
+        }                                                                                           \
+        FP_TILE(true, 0, true, true, true, false)                                                   \
+        int kt = 1;                                                                                 \
+        for (; kt + 2 < KT; ++kt) FP_TILE(REST_, kt, false, true, true, false)                      \
+        FP_TILE(REST_, kt, false, false, true, false) /* kt = KT-2 */                               \
+        ++kt;                                                                                       \
+        FP_TILE(REST_, kt, false, false, false, true) /* kt = KT-1 */                               \
+        {   /* O^T += V^T P^T for the very last block (KT-1, 1) */                                  \
+            const u32x4_t* vs_ = lds + 2 * K_TILE + ((KT - 1) & 1) * V_TILE;                        \
+            _Pragma("unroll") for (int t = 0; t < 2; ++t)                                           \
+                _Pragma("unroll") for (int db = 0; db < DB; ++db) {                                 \
+                    const bf16x8_t vf_ = *reinterpret_cast<const bf16x8_t*>(                        \
+                        vs_ + (db * 32 + li) * VCH + ((kh * 8 + 4 + 2 * t + hf) ^ sw_v));           \
+                    _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)                               \
+                        acc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf_, pb_[t][qb],      \
+                                                                              acc[db][qb], 0, 0, 0); \
+                }                                                                                   \
+        }                                                                                           \
+    }
+
+    FP_RUN(false)
+    {
+        // Did any score of any wave rise far enough above its reference to endanger the fp32 range?
+        // Then a row sum is huge, infinite or NaN (each fails the comparison the right way round)
+        // and every wave repeats the pass with the running maximum.
+        int* flag = reinterpret_cast<int*>(smem);
+        FP_PUBLISH()   // all waves are done with the tiles
+        if (tid == 0) *flag = 0;
+        FP_PUBLISH()
+        if (!(l_run[0] < 0x1p100f) || !(l_run[1] < 0x1p100f)) *flag = 1;
+        FP_PUBLISH()
+        const int redo = *flag;
+        FP_PUBLISH()   // the flag's LDS word is tile memory again
+        if (redo) FP_RUN(true)
+    }
+#undef FP_RUN
+#undef FP_TILE
+#undef FP_STEP
+#undef FP_G
+#undef FP_HALF
+#undef FP_E0
+#undef FP_CONSUME
+#undef FP_EXP
+#undef FP_ARG
+#undef FP_MFMA_S
+#undef FP_MFMA_S0
+#undef FP_FIX_TAIL
+#undef FP_ISSUE_ONE
+#undef FP_DMA16
+#undef FP_TILE_START
+
+    // ---- merge the key slices of a query group, normalise and store (as in the kernel above)
+    if (KSPLIT > 1) {
+        FP_PUBLISH()  // everyone is done with the operand tiles
+        float* xch = reinterpret_cast<float*>(smem) + qg * ((DB * 16 + 2) * QB * 64);
+        for (int src = 1; src < KSPLIT; ++src) {
+            if (kh == src) {
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    float* base = xch + qb * ((DB * 16 + 2) * 64) + lane;
+                    base[0] = m_run[qb];
+                    base[64] = l_run[qb];
+#pragma unroll
+                    for (int db = 0; db < DB; ++db)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) base[(2 + db * 16 + r) * 64] = acc[db][qb][r];
+                }
+            }
+            FP_PUBLISH()
+            if (kh == 0) {
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    const float* base = xch + qb * ((DB * 16 + 2) * 64) + lane;
+                    const float m_o = base[0], l_o = base[64];
+                    const float m_new = fmaxf(m_run[qb], m_o);
+                    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+                    const float a_me = __builtin_amdgcn_exp2f(m_run[qb] - m_use);
+                    const float a_o = __builtin_amdgcn_exp2f(m_o - m_use);
+                    m_run[qb] = m_new;
+                    l_run[qb] = l_run[qb] * a_me + l_o * a_o;
+#pragma unroll
+                    for (int db = 0; db < DB; ++db)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            acc[db][qb][r] = acc[db][qb][r] * a_me + base[(2 + db * 16 + r) * 64] * a_o;
+                }
+            }
+            if (src + 1 < KSPLIT) FP_PUBLISH()
+        }
+    }
+#undef FP_PUBLISH
+    if (kh == 0) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const float l_tot = l_run[qb] + other_half(l_run[qb]);
+            const float inv = 1.0f / l_tot;
+            const int qrow = q_base + qb * 32 + li;
+            if (qrow < p.k_tokens) {
+                bf16_t* dst = p.o + ((size_t)b * p.k_tokens + qrow) * p.D + head * DH + 4 * hf;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        u32x2_t pk;
+                        pk.x = pack_bf16x2(acc[db][qb][4 * g + 0] * inv, acc[db][qb][4 * g + 1] * inv);
+                        pk.y = pack_bf16x2(acc[db][qb][4 * g + 2] * inv, acc[db][qb][4 * g + 3] * inv);
+                        *reinterpret_cast<u32x2_t*>(dst + db * 32 + 8 * g) = pk;
+                    }
+            }
+        }
+    }
+#endif
+}
+
+template <int DH, int QG, int KSPLIT>
+void launch_pipe(const AttnParams& p, int B, hipStream_t stream) {
+    constexpr size_t tile_bytes = (size_t)2 * (64 * KSPLIT * (DH / 8) + DH * (8 * KSPLIT)) * 16;
+    constexpr size_t merge_bytes = KSPLIT > 1 ? (size_t)QG * (DH / 32 * 16 + 2) * 2 * 64 * 4 : 0;
+    constexpr size_t smem = tile_bytes > merge_bytes ? tile_bytes : merge_bytes;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_pipe_kernel<DH, QG, KSPLIT>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        attr_set = true;
+    }
+    const int per_wg = QG * 64;
+    attention_pipe_kernel<DH, QG, KSPLIT>
+        <<<dim3((p.k_tokens + per_wg - 1) / per_wg, p.H, B), QG * KSPLIT * 64, smem, stream>>>(p);
+}
+
 template <int DH, int QB, int QG, int KSPLIT>
 void launch_cfg(const AttnParams& p, int B, hipStream_t stream) {
     constexpr size_t tile_bytes = (size_t)2 * (64 * KSPLIT * (DH / 8) + DH * (8 * KSPLIT)) * 16;
@@ -556,12 +1039,16 @@ void launch_attention(const AttnArgs& a, hipStream_t stream) {
     const long waves = (long)((a.k_tokens + 31) / 32) * a.H * a.B;
     int cfg = waves >= 1800 ? 2 : 4;
     if (attn_cfg_override() >= 0) cfg = attn_cfg_override();
+    // the software-pipelined kernel needs head dim 128 and at least three key tiles
+    if ((cfg == 5 || cfg == 6) && (a.dh != 128 || a.L <= 2 * (cfg == 5 ? 128 : 64))) cfg = 4;
     if (a.dh == 128) {
         switch (cfg) {
             case 0: launch_cfg<128, 2, 4, 1>(p, a.B, stream); break;
             case 1: launch_cfg<128, 2, 2, 2>(p, a.B, stream); break;
             case 2: launch_cfg<128, 1, 4, 1>(p, a.B, stream); break;
             case 3: launch_cfg<128, 1, 2, 2>(p, a.B, stream); break;
+            case 5: launch_pipe<128, 2, 2>(p, a.B, stream); break;
+            case 6: launch_pipe<128, 4, 1>(p, a.B, stream); break;
             default: launch_cfg<128, 1, 4, 2>(p, a.B, stream); break;
         }
     } else {

@@ -1033,11 +1033,19 @@ void launch_attention(const AttnArgs& a, hipStream_t stream) {
     p.o = static_cast<bf16_t*>(a.o);
     p.H = a.H; p.k_tokens = a.k_tokens; p.L = a.L; p.L_cap = a.L_cap; p.D = a.H * a.dh;
     p.scale_log2e = a.scale * 1.4426950408889634f;
-    // One wave per 32 queries, two waves per SIMD: with enough queries two 4-wave
-    // workgroups share a CU; otherwise an 8-wave workgroup splits the keys of each
-    // tile between two waves per query group.
+    // Head dim 128 and more than two key tiles: the software-pipelined kernel (64 queries per wave),
+    // with 256-query workgroups when those still fill the chip, else 128-query workgroups that split
+    // each tile's keys between two waves per query group.  Otherwise one wave per 32 queries, two
+    // waves per SIMD: with enough queries two 4-wave workgroups share a CU; with fewer an 8-wave
+    // workgroup splits the keys of each tile between two waves per query group.
     const long waves = (long)((a.k_tokens + 31) / 32) * a.H * a.B;
+    const long wg256 = (long)((a.k_tokens + 255) / 256) * a.H * a.B;
+    const long wg128 = (long)((a.k_tokens + 127) / 128) * a.H * a.B;
     int cfg = waves >= 1800 ? 2 : 4;
+    if (a.dh == 128 && a.L > 256) {
+        if (wg256 >= 200) cfg = 6;
+        else if (wg128 >= 128) cfg = 5;
+    }
     if (attn_cfg_override() >= 0) cfg = attn_cfg_override();
     // the software-pipelined kernel needs head dim 128 and at least three key tiles
     if ((cfg == 5 || cfg == 6) && (a.dh != 128 || a.L <= 2 * (cfg == 5 ? 128 : 64))) cfg = 4;

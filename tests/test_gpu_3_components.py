@@ -119,7 +119,11 @@ ATT_CASES = [
     (2, 128, 1, 32, 64, 64), (2, 128, 1, 33, 65, 72), (3, 64, 2, 37, 66, 104), (2, 128, 3, 70, 115, 128),
     (16, 64, 1, 128, 552, 688), (1, 64, 1, 1, 1, 8), (2, 64, 1, 5, 200, 200), (16, 128, 1, 200, 1000, 1000),
     (16, 64, 4, 1024, 1124, 1128),   # two query blocks per wave
-    (16, 128, 1, 4096, 300, 304),    # two query blocks per wave, dh 128
+    (16, 128, 1, 4096, 300, 304),    # 256-query workgroups of the pipelined kernel, three tiles, ragged
+    # 128-query workgroups of the pipelined kernel: exactly / just over three tiles, tails of 1 and 7
+    (16, 128, 1, 1024, 384, 384), (16, 128, 1, 1000, 385, 392), (16, 128, 1, 1024, 1001, 1008),
+    (16, 128, 2, 520, 1023, 1024),
+    (16, 128, 2, 2048, 200, 200),    # 256-query workgroups, four 64-key tiles, the last one shifted
 ]
 
 
@@ -140,6 +144,26 @@ def test_attention_matches_oracle(H, dh, B, k, L, L_cap):
     for b in range(B):
         ref = O.attention(q[b].astype(np.float64), K[b].astype(np.float64), V[b].astype(np.float64), dh ** -0.5)
         assert max_rel(got[b], ref) <= TOL, (b,)
+
+
+def test_attention_scores_rising_far_above_the_first_tile():
+    """Keys late in the sequence score hundreds of octaves above the first tile's maximum: the
+    pipelined kernel's fixed softmax reference overflows and it must fall back to the running maximum."""
+    print("[attention] rising scores", flush=True)
+    H, dh, B, k, L = 16, 128, 1, 1024, 900
+    D = H * dh
+    rng = np.random.default_rng(11)
+    q = rnd(rng, B, k, H, dh)
+    K, V = rnd(rng, B, L, H, dh), rnd(rng, B, L, H, dh)
+    K[:, 600:] *= 64.0          # a power of two keeps the values bf16; scores reach several hundred
+    kc, vc = make_caches(K, V, 904)
+    o = torch.full((B, k, D), float("nan"), dtype=torch.bfloat16, device=DEV)
+    d = fb.make_dims(D, H, dh, 4 * D)
+    fb.fastvar_attention(to_dev_bf16(q.reshape(B, k, D)), kc, vc, B, k, d, L, 904, o)
+    got = from_dev_bf16(o).reshape(B, k, H, dh)
+    assert not np.isnan(got).any()
+    ref = O.attention(q[0].astype(np.float64), K[0].astype(np.float64), V[0].astype(np.float64), dh ** -0.5)
+    assert max_rel(got[0], ref) <= TOL
 
 
 def test_attention_peaked_and_uniform_rows():

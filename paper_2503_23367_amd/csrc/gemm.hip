@@ -501,7 +501,9 @@ void launch_epi(GemmParams& p, hipStream_t stream) {
     //    with one wave per SIMD; they win whenever they still give (almost) every
     //    CU a tile.  The QKV GEMM uses 256x192 (N = 3D divides evenly) with eight
     //    waves of 64x96, whose smaller accumulator leaves room for the epilogue's
-    //    extra address state; the others 256x256 with four waves of 128x128.
+    //    extra address state; the others 256x256, with eight waves of 128x64 when there is a single
+    //    round of tiles (two waves per SIMD cover each other's waits and halve the epilogue's issue
+    //    time) and four waves of 128x128 when there are several rounds.
     //  * otherwise 128x128 tiles.  At most one tile per CU: three 64-wide K stages
     //    (one workgroup per CU, LDS is free); up to two per CU: four 32-wide stages;
     //    more: two 64-wide stages, several workgroups per CU.
@@ -512,7 +514,7 @@ void launch_epi(GemmParams& p, hipStream_t stream) {
     if (EPI == EPI_QKV && tiles192 >= 192)
         cfg = 12;
     else if (EPI != EPI_QKV && tiles256 >= 192)
-        cfg = 1;
+        cfg = tiles256 <= 256 ? 11 : 1;
     else
         cfg = tiles128 <= 256 ? 7 : (tiles128 <= 512 ? 3 : 6);
     if (gemm_cfg_override(EPI) >= 0) cfg = gemm_cfg_override(EPI);

@@ -81,13 +81,15 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const bf16_t* __res
     }
 }
 
-// grid (ceil(D/64), B), block 256: mean[b,c] = (sum of the chunk partials) / N.
-// Thread (c = t%64, g = t/64) sums every 4th chunk starting at g, ascending; the
-// four partial sums of a column are then added in a fixed order.
-__global__ __launch_bounds__(256) void colsum_finalize_kernel(const double* __restrict__ partial,
-                                                              double* __restrict__ mean, int N, int D,
-                                                              int n_chunks) {
-    __shared__ double part[4][64];
+// grid (ceil(D/64), B), block 1024: mean[b,c] = (sum of the chunk partials) / N.
+// Thread (c = t%64, g = t/64) sums every 16th chunk starting at g, ascending (eight
+// independent loads at a time); the sixteen partial sums of a column are then
+// added in a fixed order.
+constexpr int kFinGroups = 16;
+__global__ __launch_bounds__(64 * kFinGroups) void colsum_finalize_kernel(const double* __restrict__ partial,
+                                                                          double* __restrict__ mean, int N, int D,
+                                                                          int n_chunks) {
+    __shared__ double part[kFinGroups][64];
     const int cl = threadIdx.x & 63, g = threadIdx.x >> 6;
     const int c = blockIdx.x * 64 + cl;
     const int b = blockIdx.y;
@@ -95,22 +97,26 @@ __global__ __launch_bounds__(256) void colsum_finalize_kernel(const double* __re
     if (c < D) {
         const double* p = partial + (size_t)b * n_chunks * D + c;
         int y = g;
-        for (; y + 12 < n_chunks; y += 16) {
-            const double a0 = p[(size_t)(y + 0) * D];
-            const double a1 = p[(size_t)(y + 4) * D];
-            const double a2 = p[(size_t)(y + 8) * D];
-            const double a3 = p[(size_t)(y + 12) * D];
-            s = (((s + a0) + a1) + a2) + a3;
+        for (; y + 7 * kFinGroups < n_chunks; y += 8 * kFinGroups) {
+            double a[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) a[j] = p[(size_t)(y + j * kFinGroups) * D];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) s += a[j];
         }
-        for (; y < n_chunks; y += 4) s += p[(size_t)y * D];
+        for (; y < n_chunks; y += kFinGroups) s += p[(size_t)y * D];
     }
     part[g][cl] = s;
     __syncthreads();
-    if (g == 0 && c < D)
-        mean[(size_t)b * D + c] = (((part[0][cl] + part[1][cl]) + part[2][cl]) + part[3][cl]) / (double)N;
+    if (g == 0 && c < D) {
+        double t = part[0][cl];
+#pragma unroll
+        for (int j = 1; j < kFinGroups; ++j) t += part[j][cl];
+        mean[(size_t)b * D + c] = t / (double)N;
+    }
 }
 
-constexpr int kScoreRowsPerBlock = 8;  // 4 waves x 2 rows
+constexpr int kScoreRowsPerBlock = 16;  // 4 waves x 2 passes x 2 rows
 
 __device__ __forceinline__ void sqdev8(double& acc, const uint4& v, const double* mu /* stride 64 */) {
     double d;
@@ -124,7 +130,7 @@ __device__ __forceinline__ void sqdev8(double& acc, const uint4& v, const double
     d = (double)bf16_hi(v.w) - mu[7 * 64]; acc = fma(d, d, acc);
 }
 
-// grid (ceil(N/8), B), block 256, dynamic LDS = round_up(D,512) doubles.
+// grid (ceil(N/16), B), block 256, dynamic LDS = round_up(D,512) doubles.
 // The mean is staged in LDS as [group of 512 cols][j = col%8][lane = (col%512)/8]
 // so that the 64 lanes of a wave read consecutive doubles.
 __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ x,
@@ -141,27 +147,30 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ x
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int groups = (D + 511) >> 9;
-    const int n0 = blockIdx.x * kScoreRowsPerBlock + wave * 2;
-    const int n1 = n0 + 1;
-    const bool ok0 = n0 < N, ok1 = n1 < N;
-    const bf16_t* row0 = x + ((size_t)b * N + (ok0 ? n0 : 0)) * D;
-    const bf16_t* row1 = x + ((size_t)b * N + (ok1 ? n1 : 0)) * D;
-    double acc0 = 0.0, acc1 = 0.0;
-    for (int g = 0; g < groups; ++g) {
-        const int col = g * 512 + lane * 8;
-        if (col < D) {
-            const uint4 v0 = *reinterpret_cast<const uint4*>(row0 + col);
-            const uint4 v1 = *reinterpret_cast<const uint4*>(row1 + col);
-            const double* mu = mu_s + g * 512 + lane;
-            sqdev8(acc0, v0, mu);
-            sqdev8(acc1, v1, mu);
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int n0 = blockIdx.x * kScoreRowsPerBlock + pass * 8 + wave * 2;
+        const int n1 = n0 + 1;
+        const bool ok0 = n0 < N, ok1 = n1 < N;
+        const bf16_t* row0 = x + ((size_t)b * N + (ok0 ? n0 : 0)) * D;
+        const bf16_t* row1 = x + ((size_t)b * N + (ok1 ? n1 : 0)) * D;
+        double acc0 = 0.0, acc1 = 0.0;
+        for (int g = 0; g < groups; ++g) {
+            const int col = g * 512 + lane * 8;
+            if (col < D) {
+                const uint4 v0 = *reinterpret_cast<const uint4*>(row0 + col);
+                const uint4 v1 = *reinterpret_cast<const uint4*>(row1 + col);
+                const double* mu = mu_s + g * 512 + lane;
+                sqdev8(acc0, v0, mu);
+                sqdev8(acc1, v1, mu);
+            }
         }
-    }
-    acc0 = wave_sum(acc0);
-    acc1 = wave_sum(acc1);
-    if (lane == 0) {
-        if (ok0) score[(size_t)b * N + n0] = (float)acc0;
-        if (ok1) score[(size_t)b * N + n1] = (float)acc1;
+        acc0 = wave_sum(acc0);
+        acc1 = wave_sum(acc1);
+        if (lane == 0) {
+            if (ok0) score[(size_t)b * N + n0] = (float)acc0;
+            if (ok1) score[(size_t)b * N + n1] = (float)acc1;
+        }
     }
 }
 
@@ -319,7 +328,7 @@ void launch_select(const void* x, int B, int N, int D, int k, int32_t* idx, int3
 
     colsum_partial_kernel<<<dim3(plan.col_tiles, plan.n_chunks, B), 256, 0, stream>>>(
         xb, partial, N, D, plan.rows_per_chunk, plan.n_chunks);
-    colsum_finalize_kernel<<<dim3((D + 63) / 64, B), 256, 0, stream>>>(partial, mean, N, D, plan.n_chunks);
+    colsum_finalize_kernel<<<dim3((D + 63) / 64, B), 64 * kFinGroups, 0, stream>>>(partial, mean, N, D, plan.n_chunks);
     const size_t mu_bytes = (size_t)plan.col_tiles * 512 * sizeof(double);
     score_kernel<<<dim3((N + kScoreRowsPerBlock - 1) / kScoreRowsPerBlock, B), 256, mu_bytes, stream>>>(
         xb, mean, score, N, D);

@@ -662,15 +662,22 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
     // one or two of them (multiply-add), takes the exp2 of those the half-group before it started
     // and consumes the ones before that (row-sum add; bf16 pack once a pair is complete): the wave
     // issues in order, so a value must not be used in the half-group that computes it.
-#define FP_ARG(S_, e_) \
-    px_[e_] = fmaf(S_[(e_) / 16][(e_) % 16], p.scale_log2e, -m_use_[(e_) / 16]);
-#define FP_EXP(e_) pe_[e_] = __builtin_amdgcn_exp2f(px_[e_]);
+    // (each value is pinned where it is computed: the optimiser would otherwise sink the packs and
+    // the row-sum adds to the end of the step, out of the MFMAs' shadow and with 32 values alive)
+#define FP_ARG(S_, e_)                                                                              \
+    px_[e_] = fmaf(S_[(e_) / 16][(e_) % 16], p.scale_log2e, -m_use_[(e_) / 16]);                    \
+    asm volatile("" : "+v"(px_[e_]));
+#define FP_EXP(e_)                                                                                  \
+    pe_[e_] = __builtin_amdgcn_exp2f(px_[e_]);                                                      \
+    asm volatile("" : "+v"(pe_[e_]));
 #define FP_CONSUME(P_, e_)                                                                          \
     {                                                                                               \
         lsum_[(e_) / 16] += pe_[e_];                                                                \
+        asm volatile("" : "+v"(lsum_[(e_) / 16]));                                                  \
         if ((e_) % 2 == 1) {                                                                        \
-            P_[((e_) % 16) >> 3][(e_) / 16][((e_) % 16 & 7) - 1] = (__bf16)pe_[(e_) - 1];           \
-            P_[((e_) % 16) >> 3][(e_) / 16][(e_) % 16 & 7] = (__bf16)pe_[e_];                       \
+            uint32_t pk_ = pack_bf16x2(pe_[(e_) - 1], pe_[e_]);                                     \
+            asm volatile("" : "+v"(pk_));                                                           \
+            pw_[((e_) / 16) * 8 + ((e_) % 16) / 2] = pk_;                                           \
         }                                                                                           \
     }
     // Half-group hh_ (0..31: two per group) starts elements [FP_E0(hh_), FP_E0(hh_+1)).  With the
@@ -787,6 +794,7 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
         constexpr int NJ_ = JHI_ > JLO_ ? JHI_ - JLO_ : 0;                                          \
         constexpr int DEPTH_ = 4;                                                                   \
         float m_use_[QB], alpha_[QB], lsum_[QB], px_[32], pe_[32], mxa_ = 0.f, mxb_ = 0.f;          \
+        uint32_t pw_[16];          /* packed probabilities: [qb][r / 2] */                         \
         _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                         \
             m_use_[qb] = m_run[qb];   /* fast mode: the reference stays; else replaced in groups 1, 3 */ \
             alpha_[qb] = 1.0f;                                                                      \
@@ -815,8 +823,11 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
         _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                         \
             if (RESC_) l_run[qb] = l_run[qb] * alpha_[qb] + lsum_[qb];                              \
             else l_run[qb] += lsum_[qb];                                                            \
-            /* the probabilities are first used in the next step: keep their arithmetic here */    \
-            asm volatile("" : "+v"(P_SM_[0][qb]), "+v"(P_SM_[1][qb]), "+v"(l_run[qb]));             \
+            _Pragma("unroll") for (int t = 0; t < 2; ++t) {                                         \
+                const u32x4_t w_ = {pw_[qb * 8 + t * 4 + 0], pw_[qb * 8 + t * 4 + 1],               \
+                                    pw_[qb * 8 + t * 4 + 2], pw_[qb * 8 + t * 4 + 3]};              \
+                P_SM_[t][qb] = __builtin_bit_cast(bf16x8_t, w_);                                    \
+            }                                                                                       \
         }                                                                                           \
         if (RESC_) {                                                                                \
             /* O is relative to the old maximum */                                                  \

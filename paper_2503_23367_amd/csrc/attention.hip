@@ -650,13 +650,15 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
     // S = K Q^T accumulates in vector registers (the softmax reads it there); the MFMA is written
     // as inline assembly because the compiler's own form of it, in a kernel this large, puts every
     // MFMA result in the accumulator file and copies it out again for the vector unit.
+    // The query operand is taken from the accumulator file (it is used by these MFMAs only, and the
+    // 64 registers it would occupy are what the vector file is short of).
     // The leading wait states stand in for the ones the compiler inserts before its own MFMAs
     // (it cannot see through the assembly: without them the results are wrong); they cost nothing,
     // the wave is waiting for the matrix pipe at that point anyway.
 #define FP_MFMA_S0(S_, a_, b_) \
-    asm("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(S_) : "v"(a_), "v"(b_))
+    asm("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(S_) : "v"(a_), "a"(b_))
 #define FP_MFMA_S(S_, a_, b_) \
-    asm("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(S_) : "v"(a_), "v"(b_))
+    asm("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(S_) : "v"(a_), "a"(b_))
 
     // The exponentials of a block are numbered e = 16*qb + r (32 per step).  A half-group starts
     // one or two of them (multiply-add), takes the exp2 of those the half-group before it started
@@ -733,7 +735,8 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
                 (kbase_) + li * KCH + ((2 * (f - NV_) + hf) ^ sw_k));                               \
         if (f >= NG_ && (N_DO_PV_))         /* the first operands of the next step */               \
             NFR_[f >= NG_ ? f - NG_ : 0] = *reinterpret_cast<const bf16x8_t*>(                      \
-                (nvbase_) + ((f >= NG_ ? f - NG_ : 0) * 32 + li) * VCH + (((nvchunk0_) + hf) ^ sw_v)); \
+                (nvbase_) + (((f >= NG_ ? f - NG_ : 0) % DB) * 32 + li) * VCH +                     \
+                (((nvchunk0_) + 2 * ((f >= NG_ ? f - NG_ : 0) / DB) + hf) ^ sw_v));                 \
         {                                                                                           \
             if (gg < NJ_) FP_ISSUE_ONE(ktk_, ktv_, JLO_ + gg)                                       \
             /* two halves, each one MFMA (query block 0, then 1) with its share of the softmax: */  \
@@ -792,7 +795,7 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
         constexpr int JLO_ = (LOAD_K_) ? 0 : K_LD;                                                  \
         constexpr int JHI_ = (LOAD_V_) ? K_LD + V_LD : K_LD;                                        \
         constexpr int NJ_ = JHI_ > JLO_ ? JHI_ - JLO_ : 0;                                          \
-        constexpr int DEPTH_ = 4;                                                                   \
+        constexpr int DEPTH_ = 6;                                                                   \
         float m_use_[QB], alpha_[QB], lsum_[QB], px_[32], pe_[32], mxa_ = 0.f, mxb_ = 0.f;          \
         uint32_t pw_[16];          /* packed probabilities: [qb][r / 2] */                         \
         _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                         \

@@ -193,6 +193,22 @@ def test_cache_grows_by_kept_tokens_only():
     assert r["y"].shape == x.shape          # token-number invariance of PTS+CTR
 
 
+def test_sampled_rows_equal_slices_of_the_full_block():
+    """The `rows` shortcut (used to check single outputs of large steps) is the full result, sliced:
+    every kept token still attends to all cached and all kept keys."""
+    rng = np.random.default_rng(21)
+    W = _rand_weights(22)
+    xk = rng.standard_normal((2, 11, DIMS.D))
+    kc = rng.standard_normal((2, 7, DIMS.H, DIMS.dh))
+    vc = rng.standard_normal((2, 7, DIMS.H, DIMS.dh))
+    full = O.block_forward_pruned(xk, W, DIMS.H, kc, vc)
+    rows = np.array([0, 3, 10])
+    part = O.block_forward_pruned(xk, W, DIMS.H, kc, vc, rows=rows)
+    assert np.allclose(part[0], full[0][:, rows], rtol=0, atol=1e-12)
+    # the cache rows produced do not depend on the sampling
+    assert np.array_equal(part[1], full[1]) and np.array_equal(part[2], full[2])
+
+
 # ------------------------------ restoration ---------------------------------
 
 def test_upsample_matches_torch_bilinear_half_pixel():

@@ -186,7 +186,7 @@ def kernel_table(wl, st, iters):
 
 
 # bench.py's kernel names -> prefix of the device kernel's name in the counter summary
-_TRAFFIC_KEYS = {"attention": "attention_kernel", "qkv gemm": "gemm_nt_kernel<256, 192",
+_TRAFFIC_KEYS = {"attention": "attention_pipe_kernel", "qkv gemm": "gemm_nt_kernel<256, 192",
                  "fc1 gemm": "gemm_nt_kernel<256, 256", "restore": "restore_kernel"}
 
 

@@ -25,8 +25,9 @@ design notes):
   * the top-k decision is taken on the score rounded to fp32, ties go to the
     lowest token index, the index set is emitted ascending;
   * `interpolate` is bilinear with half-pixel centres, edges clamped;
-  * one select/restore pair wraps the whole block (Fig. 2(b) wraps each
-    sub-layer; that finer wiring is not built here);
+  * `step` puts one select/restore pair around the whole block;
+    `step_sublayer` is the finer wiring of Fig. 2(b), one pair around the
+    attention layer and one around the FFN layer, each with its own cached map;
   * the cached map and the block output are post-residual hidden states;
   * block internals (pre-LN, eps, 1/sqrt(dh), erf-GELU, biases) come from the
     workload definition, not the paper;
@@ -204,6 +205,42 @@ def block_forward_pruned(xk: np.ndarray, W: Dict[str, np.ndarray], H: int,
     return yk, kn, vn
 
 
+def attention_sublayer_pruned(xk: np.ndarray, W: Dict[str, np.ndarray], H: int,
+                              k_cache: np.ndarray, v_cache: np.ndarray,
+                              eps: float = 1e-6, scale: Optional[float] = None):
+    """The attention layer of the block on kept tokens xk [B,k,D], with its
+    residual: h = xk + proj(attn(LN1(xk))).  Keys and values as in
+    block_forward_pruned (cached ones, then the kept tokens' own).
+
+    Returns (h [B,k,D], k_new [B,k,H,dh], v_new [B,k,H,dh]).
+    """
+    xk = np.asarray(xk, F64)
+    B, k, D = xk.shape
+    dh = D // H
+    if scale is None:
+        scale = 1.0 / math.sqrt(dh)
+    a = layer_norm(xk, W["ln1_g"], W["ln1_b"], eps)
+    qkv = linear(a, W["w_qkv"], W.get("b_qkv"))
+    q = qkv[..., :D].reshape(B, k, H, dh)
+    kn = qkv[..., D:2 * D].reshape(B, k, H, dh)
+    vn = qkv[..., 2 * D:].reshape(B, k, H, dh)
+    o = np.empty((B, k, D), dtype=F64)
+    for b in range(B):
+        keys = np.concatenate([np.asarray(k_cache[b], F64), kn[b]], axis=0)
+        vals = np.concatenate([np.asarray(v_cache[b], F64), vn[b]], axis=0)
+        o[b] = attention(q[b], keys, vals, scale).reshape(k, D)
+    return xk + linear(o, W["w_proj"], W.get("b_proj")), kn, vn
+
+
+def ffn_sublayer_pruned(xk: np.ndarray, W: Dict[str, np.ndarray], eps: float = 1e-6) -> np.ndarray:
+    """The FFN layer of the block on kept tokens xk [B,k,D], with its
+    residual: y = xk + fc2(gelu(fc1(LN2(xk))))."""
+    xk = np.asarray(xk, F64)
+    a = layer_norm(xk, W["ln2_g"], W["ln2_b"], eps)
+    u = gelu(linear(a, W["w_fc1"], W.get("b_fc1")))
+    return xk + linear(u, W["w_fc2"], W.get("b_fc2"))
+
+
 # ---------------------------------------------------------------------------
 # Cached Token Restoration  (Sec. 3.3, Eq. 6)
 # ---------------------------------------------------------------------------
@@ -261,3 +298,27 @@ def step(x, h, w, k, W, H, k_cache, v_cache, cache_map, hc, wc,
     yk, kn, vn = block_forward_pruned(xk, W, H, k_cache, v_cache, eps, scale)
     y = restore(yk, idx, cache_map, hc, wc, h, w)
     return dict(idx=idx, rank=rank, score=s32, yk=yk, k_new=kn, v_new=vn, y=y)
+
+
+def step_sublayer(x, h, w, k_attn, k_ffn, W, H, k_cache, v_cache, cache_attn, cache_ffn, hc, wc,
+                  eps: float = 1e-6, scale: Optional[float] = None, x_mid=None):
+    """Fig. 2(b): a select/restore pair around the attention layer and another
+    around the FFN layer (Sec. 3.3, implementation paragraph), each restoring
+    from the cached output of its own layer (Sec. 3.3 overview: per-layer
+    outputs of the cached step are kept).
+
+    x_mid, when given, replaces the restored map between the two halves (a
+    caller that checks a device run passes the device's own bf16-rounded map, so
+    that the second selection is taken on identical values).
+
+    Returns dict(idx_attn, hk, k_new, v_new, x_mid, idx_ffn, yk, y).
+    """
+    idx_a, _, _ = select_pivotal(x, k_attn)
+    xk = gather_tokens(np.asarray(x, F64), idx_a)
+    hk, kn, vn = attention_sublayer_pruned(xk, W, H, k_cache, v_cache, eps, scale)
+    mid = restore(hk, idx_a, cache_attn, hc, wc, h, w)
+    src = mid if x_mid is None else np.asarray(x_mid, F64)
+    idx_f, _, _ = select_pivotal(src, k_ffn)
+    yk = ffn_sublayer_pruned(gather_tokens(src, idx_f), W, eps)
+    y = restore(yk, idx_f, cache_ffn, hc, wc, h, w)
+    return dict(idx_attn=idx_a, hk=hk, k_new=kn, v_new=vn, x_mid=mid, idx_ffn=idx_f, yk=yk, y=y)

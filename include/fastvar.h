@@ -116,6 +116,9 @@ size_t fastvar_restore_workspace_bytes(int B, int N);
 /* Scratch bytes needed by fastvar_step (covers all three stages). */
 size_t fastvar_step_workspace_bytes(const fastvar_dims* dims, int B, int N, int k);
 
+/* Scratch bytes needed by fastvar_step_sublayer (covers every stage of both halves). */
+size_t fastvar_step_sublayer_workspace_bytes(const fastvar_dims* dims, int B, int N, int k_attn, int k_ffn);
+
 /* ---- device entry points ------------------------------------------------ */
 
 /*
@@ -194,6 +197,52 @@ int fastvar_step(const void* x, const int32_t* sched_h /* host */, const int32_t
                  void* k_cache, void* v_cache, int32_t* kv_len /* host in/out */, int L_cap,
                  const void* cache_map, void* y_out, int32_t* idx_out,
                  void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * The two halves of the block, each on its own kept set (Fig. 2(b) and Sec. 3.3,
+ * implementation paragraph: the selection / restoration pair wraps each
+ * Attention and each FFN layer).  Arguments as in fastvar_block_forward_pruned;
+ * both take scratch of fastvar_block_workspace_bytes(dims, B, k) bytes.
+ *   attention half:  h_kept_out[B,k,D] = xk + proj(attn(LN1(xk))),  xk = x[idx];
+ *                    appends the kept tokens' keys / values at [L0, L0+k)
+ *   FFN half:        y_kept_out[B,k,D] = xk + fc2(gelu(fc1(LN2(xk)))),  xk = x[idx]
+ * k == 0 is a no-op that returns FASTVAR_OK.
+ */
+int fastvar_attn_forward_pruned(const void* x, int N, const int32_t* idx, int B, int k,
+                                const fastvar_dims* dims /* host */,
+                                const fastvar_block_weights* weights /* host struct of device ptrs */,
+                                void* k_cache, void* v_cache, int L0, int L_cap,
+                                void* h_kept_out, void* ws, size_t ws_bytes, void* stream);
+int fastvar_ffn_forward_pruned(const void* x, int N, const int32_t* idx, int B, int k,
+                               const fastvar_dims* dims /* host */,
+                               const fastvar_block_weights* weights /* host struct of device ptrs */,
+                               void* y_kept_out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * One whole step for one block at sub-layer granularity, the wiring of
+ * Fig. 2(b): selection on x, attention half on k_attn kept tokens,
+ * restoration from cache_map_attn into x_mid; selection on x_mid, FFN half on
+ * k_ffn kept tokens, restoration from cache_map_ffn into y_out.
+ *   cache_map_attn, cache_map_ffn  [B, hc*wc, D] bf16: the outputs of this
+ *                     block's attention layer and FFN layer (residual stream
+ *                     after each) at the cached scale (Sec. 3.3 overview: the
+ *                     per-layer outputs of step K-N are saved)
+ *   x_mid             [B, h*w, D] bf16, output: the restored map between the
+ *                     two halves; must not alias x, y_out or a cache map
+ *   idx_attn_out      [B, k_attn] int32, idx_ffn_out [B, k_ffn] int32: the two
+ *                     kept sets (outputs)
+ *   kv_len            host in/out: grows by k_attn (only the attention half
+ *                     writes the cache)
+ *   ws                scratch of fastvar_step_sublayer_workspace_bytes(...)
+ * Other arguments as in fastvar_step.
+ */
+int fastvar_step_sublayer(const void* x, const int32_t* sched_h /* host */, const int32_t* sched_w /* host */,
+                          int K, int step, int cache_step, int B, int k_attn, int k_ffn,
+                          const fastvar_dims* dims /* host */, const fastvar_block_weights* weights /* host */,
+                          void* k_cache, void* v_cache, int32_t* kv_len /* host in/out */, int L_cap,
+                          const void* cache_map_attn, const void* cache_map_ffn, void* x_mid, void* y_out,
+                          int32_t* idx_attn_out, int32_t* idx_ffn_out,
+                          void* ws, size_t ws_bytes, void* stream);
 
 /* ---- component entry points ----------------------------------------------
  * The kernels of the block one at a time, with the same launch configuration

@@ -47,8 +47,9 @@ EXPORTS = ("fastvar_version", "fastvar_strerror", "fastvar_keep_count",
            "fastvar_select_workspace_bytes", "fastvar_block_workspace_bytes",
            "fastvar_restore_workspace_bytes", "fastvar_step_workspace_bytes",
            "fastvar_select_pivotal", "fastvar_block_forward_pruned", "fastvar_restore",
-           "fastvar_step", "fastvar_layernorm", "fastvar_gemm_bf16", "fastvar_qkv_gemm",
-           "fastvar_attention")
+           "fastvar_step", "fastvar_step_sublayer_workspace_bytes", "fastvar_attn_forward_pruned",
+           "fastvar_ffn_forward_pruned", "fastvar_step_sublayer", "fastvar_layernorm", "fastvar_gemm_bf16",
+           "fastvar_qkv_gemm", "fastvar_attention")
 
 
 def lib() -> C.CDLL:
@@ -86,6 +87,18 @@ def lib() -> C.CDLL:
     L.fastvar_step.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), i32, i32, i32, i32, i32,
                                C.POINTER(Dims), C.POINTER(BlockWeights), vp, vp, C.POINTER(C.c_int32), i32,
                                vp, vp, vp, vp, sz, vp]
+    L.fastvar_step_sublayer_workspace_bytes.restype = sz
+    L.fastvar_step_sublayer_workspace_bytes.argtypes = [C.POINTER(Dims), i32, i32, i32, i32]
+    L.fastvar_attn_forward_pruned.restype = i32
+    L.fastvar_attn_forward_pruned.argtypes = [vp, i32, vp, i32, i32, C.POINTER(Dims),
+                                              C.POINTER(BlockWeights), vp, vp, i32, i32, vp, vp, sz, vp]
+    L.fastvar_ffn_forward_pruned.restype = i32
+    L.fastvar_ffn_forward_pruned.argtypes = [vp, i32, vp, i32, i32, C.POINTER(Dims),
+                                             C.POINTER(BlockWeights), vp, vp, sz, vp]
+    L.fastvar_step_sublayer.restype = i32
+    L.fastvar_step_sublayer.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), i32, i32, i32, i32,
+                                        i32, i32, C.POINTER(Dims), C.POINTER(BlockWeights), vp, vp,
+                                        C.POINTER(C.c_int32), i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.fastvar_layernorm.restype = i32
     L.fastvar_layernorm.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, C.c_float, vp, vp]
     L.fastvar_gemm_bf16.restype = i32
@@ -198,6 +211,44 @@ def fastvar_step(x, sched_h, sched_w, step, cache_step, B, k, dims: Dims, weight
                             _ptr(idx_out), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
                             _stream())
     _check(rc, "fastvar_step")
+    return kv.value
+
+
+def fastvar_step_sublayer_workspace_bytes(dims: Dims, B: int, N: int, k_attn: int, k_ffn: int) -> int:
+    return lib().fastvar_step_sublayer_workspace_bytes(C.byref(dims), B, N, k_attn, k_ffn)
+
+
+def _nbytes(t) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def fastvar_attn_forward_pruned(x, N, idx, B, k, dims: Dims, weights: BlockWeights, k_cache, v_cache,
+                                L0, L_cap, h_kept_out, ws) -> None:
+    rc = lib().fastvar_attn_forward_pruned(_ptr(x), N, _ptr(idx), B, k, C.byref(dims), C.byref(weights),
+                                           _ptr(k_cache), _ptr(v_cache), L0, L_cap, _ptr(h_kept_out),
+                                           _ptr(ws), _nbytes(ws), _stream())
+    _check(rc, "fastvar_attn_forward_pruned")
+
+
+def fastvar_ffn_forward_pruned(x, N, idx, B, k, dims: Dims, weights: BlockWeights, y_kept_out, ws) -> None:
+    rc = lib().fastvar_ffn_forward_pruned(_ptr(x), N, _ptr(idx), B, k, C.byref(dims), C.byref(weights),
+                                          _ptr(y_kept_out), _ptr(ws), _nbytes(ws), _stream())
+    _check(rc, "fastvar_ffn_forward_pruned")
+
+
+def fastvar_step_sublayer(x, sched_h, sched_w, step, cache_step, B, k_attn, k_ffn, dims: Dims,
+                          weights: BlockWeights, k_cache, v_cache, kv_len: int, L_cap, cache_map_attn,
+                          cache_map_ffn, x_mid, y_out, idx_attn_out, idx_ffn_out, ws) -> int:
+    """Returns the new cache length."""
+    K = len(sched_h)
+    sh = (C.c_int32 * K)(*sched_h)
+    sw = (C.c_int32 * K)(*sched_w)
+    kv = C.c_int32(kv_len)
+    rc = lib().fastvar_step_sublayer(_ptr(x), sh, sw, K, step, cache_step, B, k_attn, k_ffn, C.byref(dims),
+                                     C.byref(weights), _ptr(k_cache), _ptr(v_cache), C.byref(kv), L_cap,
+                                     _ptr(cache_map_attn), _ptr(cache_map_ffn), _ptr(x_mid), _ptr(y_out),
+                                     _ptr(idx_attn_out), _ptr(idx_ffn_out), _ptr(ws), _nbytes(ws), _stream())
+    _check(rc, "fastvar_step_sublayer")
     return kv.value
 
 

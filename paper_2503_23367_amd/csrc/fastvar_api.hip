@@ -109,15 +109,15 @@ int check_restore(const void* y_kept, const int32_t* idx, const int32_t* rank, i
 
 int launch_status() { return hipGetLastError() == hipSuccess ? FASTVAR_OK : FASTVAR_EHIP; }
 
-void enqueue_block(const void* x, int N, const int32_t* idx, int B, int k, const fastvar_dims* d,
-                   const fastvar_block_weights* w, void* kc, void* vc, int L0, int L_cap, void* y, void* ws,
-                   hipStream_t st) {
+// Attention half of the block on the kept tokens: h1 = x[idx] + proj(attn(LN1(x[idx]))).
+// Scratch used: a, q, rows of the block plan.
+void enqueue_attn(const void* x, int N, const int32_t* idx, int B, int k, const fastvar_dims* d,
+                  const fastvar_block_weights* w, void* kc, void* vc, int L0, int L_cap, void* h1_out, void* ws,
+                  hipStream_t st) {
     const BlockPlan bp = block_plan(d, B, k);
     char* base = static_cast<char*>(ws);
     void* buf_a = base + bp.off_a;
     void* buf_q = base + bp.off_q;
-    void* buf_h1 = base + bp.off_h1;
-    void* buf_u = base + bp.off_u;
     int32_t* rows = reinterpret_cast<int32_t*>(base + bp.off_rows);
     const int M = B * k;
 
@@ -138,20 +138,59 @@ void enqueue_block(const void* x, int N, const int32_t* idx, int B, int k, const
     // h1 = x[idx] + o * Wp^T + bp
     fv::GemmArgs pj{};
     pj.A = buf_a; pj.W = w->w_proj; pj.bias = w->b_proj; pj.M = M; pj.N = d->D; pj.K = d->D;
-    pj.out = buf_h1; pj.residual = x; pj.res_rows = rows; pj.k_tokens = k;
+    pj.out = h1_out; pj.residual = x; pj.res_rows = rows; pj.k_tokens = k;
     fv::launch_gemm(fv::EPI_BIAS_RES, pj, st);
-    // a2 = LN2(h1)
-    fv::launch_layernorm(buf_h1, M, d->D, w->ln2_g, w->ln2_b, d->ln_eps, buf_q, st);
+}
+
+// MLP half: y = s + fc2(gelu(fc1(LN2(s)))), where s = src[idx] (rows gathered from a [B, N, D]
+// map) or, with idx == NULL, the contiguous [B*k, D] rows at src.  Scratch used: q, u, rows.
+void enqueue_ffn(const void* src, int N, const int32_t* idx, int B, int k, const fastvar_dims* d,
+                 const fastvar_block_weights* w, void* y, void* ws, hipStream_t st) {
+    const BlockPlan bp = block_plan(d, B, k);
+    char* base = static_cast<char*>(ws);
+    void* buf_q = base + bp.off_q;
+    void* buf_u = base + bp.off_u;
+    int32_t* rows = reinterpret_cast<int32_t*>(base + bp.off_rows);
+    const int M = B * k;
+
+    // a2 = LN2(s)
+    if (idx)
+        fv::launch_gather_layernorm(src, idx, B, N, k, d->D, w->ln2_g, w->ln2_b, d->ln_eps, rows, buf_q, st);
+    else
+        fv::launch_layernorm(src, M, d->D, w->ln2_g, w->ln2_b, d->ln_eps, buf_q, st);
     // u = gelu(a2 * W1^T + b1)
     fv::GemmArgs f1{};
     f1.A = buf_q; f1.W = w->w_fc1; f1.bias = w->b_fc1; f1.M = M; f1.N = d->F; f1.K = d->D;
     f1.out = buf_u; f1.k_tokens = k;
     fv::launch_gemm(fv::EPI_BIAS_GELU, f1, st);
-    // y = h1 + u * W2^T + b2
+    // y = s + u * W2^T + b2
     fv::GemmArgs f2{};
     f2.A = buf_u; f2.W = w->w_fc2; f2.bias = w->b_fc2; f2.M = M; f2.N = d->D; f2.K = d->F;
-    f2.out = y; f2.residual = buf_h1; f2.k_tokens = k;
+    f2.out = y; f2.residual = src; f2.res_rows = idx ? rows : nullptr; f2.k_tokens = k;
     fv::launch_gemm(fv::EPI_BIAS_RES, f2, st);
+}
+
+void enqueue_block(const void* x, int N, const int32_t* idx, int B, int k, const fastvar_dims* d,
+                   const fastvar_block_weights* w, void* kc, void* vc, int L0, int L_cap, void* y, void* ws,
+                   hipStream_t st) {
+    void* buf_h1 = static_cast<char*>(ws) + block_plan(d, B, k).off_h1;
+    enqueue_attn(x, N, idx, B, k, d, w, kc, vc, L0, L_cap, buf_h1, ws, st);
+    enqueue_ffn(buf_h1, 0, nullptr, B, k, d, w, y, ws, st);
+}
+
+int check_ffn(const void* x, int N, const int32_t* idx, int B, int k, const fastvar_dims* dims,
+              const fastvar_block_weights* wts, const void* y, const void* ws, size_t ws_bytes) {
+    int rc = check_dims(dims);
+    if (rc) return rc;
+    rc = check_weights(wts);
+    if (rc) return rc;
+    if (!x || B <= 0 || N <= 0 || k < 0 || k > N) return FASTVAR_EINVAL;
+    if (k > 0 && (!idx || !y)) return FASTVAR_EINVAL;
+    if (!aligned16(x) || (y && !aligned16(y)) || (ws && !aligned16(ws))) return FASTVAR_EALIGN;
+    const double M = (double)B * k;
+    if (M * dims->F >= 2147483648.0 || (double)dims->D * dims->F >= 2147483648.0) return FASTVAR_ECAPACITY;
+    if (k > 0 && (!ws || ws_bytes < fastvar_block_workspace_bytes(dims, B, k))) return FASTVAR_EWORKSPACE;
+    return FASTVAR_OK;
 }
 
 }  // namespace
@@ -285,6 +324,97 @@ int fastvar_step(const void* x, const int32_t* sched_h, const int32_t* sched_w, 
     fv::launch_restore(yk, rank, B, k, cache_map, hc, wc, h, w, D, y_out, st);
     rc = launch_status();
     if (rc == FASTVAR_OK) *kv_len = L0 + k;
+    return rc;
+}
+
+size_t fastvar_step_sublayer_workspace_bytes(const fastvar_dims* dims, int B, int N, int k_attn, int k_ffn) {
+    if (!dims || B <= 0 || N <= 0) return 0;
+    const int kmax = k_attn > k_ffn ? k_attn : k_ffn;
+    return fastvar_select_workspace_bytes(B, N, dims->D) + fastvar_restore_workspace_bytes(B, N) +
+           fastvar_block_workspace_bytes(dims, B, kmax);
+}
+
+int fastvar_attn_forward_pruned(const void* x, int N, const int32_t* idx, int B, int k, const fastvar_dims* dims,
+                                const fastvar_block_weights* weights, void* k_cache, void* v_cache, int L0,
+                                int L_cap, void* h_kept_out, void* ws, size_t ws_bytes, void* stream) {
+    const int rc = check_block(x, N, idx, B, k, dims, weights, k_cache, v_cache, L0, L_cap, h_kept_out, ws,
+                               ws_bytes);
+    if (rc) return rc;
+    if (k == 0) return FASTVAR_OK;
+    enqueue_attn(x, N, idx, B, k, dims, weights, k_cache, v_cache, L0, L_cap, h_kept_out, ws,
+                 static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+int fastvar_ffn_forward_pruned(const void* x, int N, const int32_t* idx, int B, int k, const fastvar_dims* dims,
+                               const fastvar_block_weights* weights, void* y_kept_out, void* ws, size_t ws_bytes,
+                               void* stream) {
+    const int rc = check_ffn(x, N, idx, B, k, dims, weights, y_kept_out, ws, ws_bytes);
+    if (rc) return rc;
+    if (k == 0) return FASTVAR_OK;
+    enqueue_ffn(x, N, idx, B, k, dims, weights, y_kept_out, ws, static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+int fastvar_step_sublayer(const void* x, const int32_t* sched_h, const int32_t* sched_w, int K, int step,
+                          int cache_step, int B, int k_attn, int k_ffn, const fastvar_dims* dims,
+                          const fastvar_block_weights* weights, void* k_cache, void* v_cache, int32_t* kv_len,
+                          int L_cap, const void* cache_map_attn, const void* cache_map_ffn, void* x_mid,
+                          void* y_out, int32_t* idx_attn_out, int32_t* idx_ffn_out, void* ws, size_t ws_bytes,
+                          void* stream) {
+    if (!sched_h || !sched_w || !kv_len || K <= 0) return FASTVAR_EINVAL;
+    if (step < 0 || step >= K || cache_step < 0 || cache_step >= step) return FASTVAR_EINVAL;
+    const int h = sched_h[step], w = sched_w[step];
+    const int hc = sched_h[cache_step], wc = sched_w[cache_step];
+    if (h <= 0 || w <= 0 || hc <= 0 || wc <= 0 || (long)h * w > FASTVAR_MAX_TOKENS) return FASTVAR_EINVAL;
+    const int N = h * w;
+    const int L0 = *kv_len;
+    int rc = check_dims(dims);
+    if (rc) return rc;
+    const int D = dims->D;
+    if (B <= 0 || k_attn < 0 || k_attn > N || k_ffn < 0 || k_ffn > N) return FASTVAR_EINVAL;
+    if (!x_mid || x_mid == x || y_out == x || y_out == x_mid) return FASTVAR_EINVAL;
+    if (!ws) return FASTVAR_EWORKSPACE;
+    if (!aligned16(ws)) return FASTVAR_EALIGN;
+    if (ws_bytes < fastvar_step_sublayer_workspace_bytes(dims, B, N, k_attn, k_ffn)) return FASTVAR_EWORKSPACE;
+
+    // scratch: [selection | rank [B,N] | block buffers for max(k_attn, k_ffn)]
+    const size_t sel_bytes = fastvar_select_workspace_bytes(B, N, D);
+    const size_t rank_bytes = fastvar_restore_workspace_bytes(B, N);
+    char* base = static_cast<char*>(ws);
+    void* ws_sel = base;
+    int32_t* rank = reinterpret_cast<int32_t*>(base + sel_bytes);
+    char* ws_blk = base + sel_bytes + rank_bytes;
+    const size_t blk_bytes = ws_bytes - sel_bytes - rank_bytes;
+    // Kept outputs of either half go to the h1 buffer of its own plan (neither half uses it).
+    void* hk = k_attn > 0 ? static_cast<void*>(ws_blk + block_plan(dims, B, k_attn).off_h1) : nullptr;
+    void* yk = k_ffn > 0 ? static_cast<void*>(ws_blk + block_plan(dims, B, k_ffn).off_h1) : nullptr;
+
+    rc = check_select(x, B, h, w, D, k_attn, idx_attn_out, ws_sel, sel_bytes);
+    if (rc) return rc;
+    rc = check_block(x, N, idx_attn_out, B, k_attn, dims, weights, k_cache, v_cache, L0, L_cap, hk, ws_blk,
+                     blk_bytes);
+    if (rc) return rc;
+    rc = check_restore(hk, idx_attn_out, rank, B, k_attn, cache_map_attn, hc, wc, h, w, D, x_mid, nullptr, 0);
+    if (rc) return rc;
+    rc = check_select(x_mid, B, h, w, D, k_ffn, idx_ffn_out, ws_sel, sel_bytes);
+    if (rc) return rc;
+    rc = check_ffn(x_mid, N, idx_ffn_out, B, k_ffn, dims, weights, yk, ws_blk, blk_bytes);
+    if (rc) return rc;
+    rc = check_restore(yk, idx_ffn_out, rank, B, k_ffn, cache_map_ffn, hc, wc, h, w, D, y_out, nullptr, 0);
+    if (rc) return rc;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const fv::SelectPlan sp = fv::select_plan(B, N, D);
+    fv::launch_select(x, B, N, D, k_attn, idx_attn_out, rank, nullptr, ws_sel, sp, st);
+    if (k_attn > 0)
+        enqueue_attn(x, N, idx_attn_out, B, k_attn, dims, weights, k_cache, v_cache, L0, L_cap, hk, ws_blk, st);
+    fv::launch_restore(hk, rank, B, k_attn, cache_map_attn, hc, wc, h, w, D, x_mid, st);
+    fv::launch_select(x_mid, B, N, D, k_ffn, idx_ffn_out, rank, nullptr, ws_sel, sp, st);
+    if (k_ffn > 0) enqueue_ffn(x_mid, N, idx_ffn_out, B, k_ffn, dims, weights, yk, ws_blk, st);
+    fv::launch_restore(yk, rank, B, k_ffn, cache_map_ffn, hc, wc, h, w, D, y_out, st);
+    rc = launch_status();
+    if (rc == FASTVAR_OK) *kv_len = L0 + k_attn;
     return rc;
 }
 

@@ -1,0 +1,215 @@
+"""GPU parity: the sub-layer wiring (Fig. 2(b): a selection / restoration pair around the
+attention layer and another around the FFN layer) vs the CPU oracle.
+
+Same bars as for the block: index sets bit-exact, floating-point tensors within 2e-2
+max-relative of the fp64 oracle, restored (pruned) slots within one bf16 rounding of the
+upsampled cache, cache rows outside the appended window untouched.  The second selection
+depends on the device's own bf16-rounded map between the two halves, so the oracle is handed
+that map for its second half (its first half is checked against it before).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fastvar_oracle as O
+from paper_2503_23367_amd import binding as fb
+from paper_2503_23367_amd import synth
+from gpu_util import (DEV, cache_rows, empty_ws, from_dev_bf16, make_caches, max_rel, to_dev_bf16,
+                      upload_weights)
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+TINY128 = synth.BlockDims(D=256, H=2, dh=128, F=512)
+TINY64 = synth.BlockDims(D=192, H=3, dh=64, F=320)
+
+
+def branch_err(got, ref, base):
+    """Error of the residual branch (result minus the residual input), after allowing for the
+    bf16 rounding of the result itself, relative to the branch magnitude."""
+    e = np.max(np.abs((got.astype(np.float64) - base) - (ref - base)))
+    return max(0.0, e - 2.0 ** -8 * 1.001 * float(np.max(np.abs(ref)))) / float(np.max(np.abs(ref - base)))
+
+
+HALF_CASES = [
+    # name, dims, B, h, w, k, L0, L_cap
+    ("tiny64_ragged", TINY64, 2, 7, 9, 37, 29, 104),
+    ("tiny128_ragged", TINY128, 3, 9, 11, 70, 45, 128),
+    ("tiny64_single_kept", TINY64, 2, 5, 5, 1, 63, 64),
+    ("d16_256px_last", synth.D16, 1, 16, 16, 128, 424, 688),
+    ("d30_s24_b2", synth.D30, 2, 24, 24, 346, 640, 992),
+]
+
+
+@pytest.mark.parametrize("name,dims,B,h,w,k,L0,L_cap", HALF_CASES, ids=[c[0] for c in HALF_CASES])
+def test_attention_half_matches_oracle(name, dims, B, h, w, k, L0, L_cap):
+    print(f"[attn half] {name} B={B} N={h*w} k={k} L0={L0}", flush=True)
+    N = h * w
+    x_np = synth.token_map(11, B, h, w, dims.D)
+    W = synth.block_weights(11, dims)
+    kp, vp = synth.kv_prior(11, B, L0, dims.H, dims.dh)
+    idx_np, _, _ = O.select_pivotal(x_np, k)
+    d = fb.make_dims(dims.D, dims.H, dims.dh, dims.F)
+    wt, wstruct = upload_weights(W)
+    x = to_dev_bf16(x_np)
+    idx = torch.from_numpy(idx_np.astype(np.int32)).to(DEV)
+    kc, vc = make_caches(kp, vp, L_cap)
+    kc0, vc0 = kc.clone(), vc.clone()
+    hk = torch.full((B, k, dims.D), float("nan"), dtype=torch.bfloat16, device=DEV)
+    ws = empty_ws(fb.fastvar_block_workspace_bytes(d, B, k))
+    ws.fill_(0xFF)
+    fb.fastvar_attn_forward_pruned(x, N, idx, B, k, d, wstruct, kc, vc, L0, L_cap, hk, ws)
+    torch.cuda.synchronize()
+    got = from_dev_bf16(hk)
+    xk = O.gather_tokens(x_np, idx_np)
+    ref, kn, vn = O.attention_sublayer_pruned(xk, W, dims.H, kp, vp)
+    kg, vg = cache_rows(kc, vc, L0, L0 + k)
+    e = (max_rel(got, ref), branch_err(got, ref, xk), max_rel(kg, kn), max_rel(vg, vn))
+    print("    max-rel: h %.2e  branch %.2e  k_new %.2e  v_new %.2e" % e, flush=True)
+    assert not np.isnan(got).any() and max(e) <= TOL, name
+    kb, kb0 = kc.view(torch.int16), kc0.view(torch.int16)
+    vb, vb0 = vc.view(torch.int16), vc0.view(torch.int16)
+    assert torch.equal(kb[:, :, :L0], kb0[:, :, :L0]) and torch.equal(kb[:, :, L0 + k:], kb0[:, :, L0 + k:])
+    assert torch.equal(vb[:, :, :, :L0], vb0[:, :, :, :L0]) and torch.equal(vb[:, :, :, L0 + k:], vb0[:, :, :, L0 + k:])
+
+
+@pytest.mark.parametrize("name,dims,B,h,w,k,L0,L_cap", HALF_CASES, ids=[c[0] for c in HALF_CASES])
+def test_ffn_half_matches_oracle(name, dims, B, h, w, k, L0, L_cap):
+    print(f"[ffn half] {name} B={B} N={h*w} k={k}", flush=True)
+    N = h * w
+    x_np = synth.token_map(12, B, h, w, dims.D)
+    W = synth.block_weights(12, dims)
+    idx_np, _, _ = O.select_pivotal(x_np, k)
+    d = fb.make_dims(dims.D, dims.H, dims.dh, dims.F)
+    wt, wstruct = upload_weights(W)
+    x = to_dev_bf16(x_np)
+    idx = torch.from_numpy(idx_np.astype(np.int32)).to(DEV)
+    yk = torch.full((B, k, dims.D), float("nan"), dtype=torch.bfloat16, device=DEV)
+    ws = empty_ws(fb.fastvar_block_workspace_bytes(d, B, k))
+    ws.fill_(0xFF)
+    fb.fastvar_ffn_forward_pruned(x, N, idx, B, k, d, wstruct, yk, ws)
+    torch.cuda.synchronize()
+    got = from_dev_bf16(yk)
+    xk = O.gather_tokens(x_np, idx_np)
+    ref = O.ffn_sublayer_pruned(xk, W)
+    e = (max_rel(got, ref), branch_err(got, ref, xk))
+    print("    max-rel: y %.2e  branch %.2e" % e, flush=True)
+    assert not np.isnan(got).any() and max(e) <= TOL, name
+
+
+def run_step_sublayer(dims, sides, step, cache_step, B, ka, kf, x_np, W, kp, vp, ca_np, cf_np, L_cap):
+    N = sides[step] ** 2
+    d = fb.make_dims(dims.D, dims.H, dims.dh, dims.F)
+    wt, wstruct = upload_weights(W)
+    x = to_dev_bf16(x_np)
+    kc, vc = make_caches(kp, vp, L_cap)
+    ca, cf = to_dev_bf16(ca_np), to_dev_bf16(cf_np)
+    mid = torch.full((B, N, dims.D), float("nan"), dtype=torch.bfloat16, device=DEV)
+    y = torch.full((B, N, dims.D), float("nan"), dtype=torch.bfloat16, device=DEV)
+    ia = torch.full((B, max(ka, 1)), -7, dtype=torch.int32, device=DEV)
+    jf = torch.full((B, max(kf, 1)), -7, dtype=torch.int32, device=DEV)
+    ws = empty_ws(fb.fastvar_step_sublayer_workspace_bytes(d, B, N, ka, kf))
+    ws.fill_(0xFF)
+    new_len = fb.fastvar_step_sublayer(x, list(sides), list(sides), step, cache_step, B, ka, kf, d, wstruct, kc, vc,
+                                       kp.shape[1], L_cap, ca, cf, mid, y, ia, jf, ws)
+    torch.cuda.synchronize()
+    return (from_dev_bf16(mid), from_dev_bf16(y), ia[:, :ka].cpu().numpy(), jf[:, :kf].cpu().numpy(), new_len,
+            kc, vc)
+
+
+def check_step_sublayer(name, dims, sides, step, cache_step, B, ka, kf, L0, L_cap, seed):
+    print(f"[sublayer step] {name} B={B} N={sides[step]**2} k_attn={ka} k_ffn={kf} L0={L0}", flush=True)
+    h = w = sides[step]
+    hc = wc = sides[cache_step]
+    N = h * w
+    x = synth.token_map(seed, B, h, w, dims.D)
+    W = synth.block_weights(seed, dims)
+    kp, vp = synth.kv_prior(seed, B, L0, dims.H, dims.dh)
+    ca = synth.cached_map(seed, B, hc, wc, dims.D)
+    cf = synth.cached_map(seed + 1000, B, hc, wc, dims.D)
+    mid, y, ia, jf, new_len, kc, vc = run_step_sublayer(dims, sides, step, cache_step, B, ka, kf, x, W, kp, vp,
+                                                        ca, cf, L_cap)
+    assert not np.isnan(mid).any() and not np.isnan(y).any(), name
+    ref = O.step_sublayer(x, h, w, ka, kf, W, dims.H, kp, vp, ca, cf, hc, wc, x_mid=mid)
+    np.testing.assert_array_equal(ia, ref["idx_attn"])
+    np.testing.assert_array_equal(jf, ref["idx_ffn"])      # taken by the oracle on the device's own map
+    assert new_len == L0 + ka
+    e_mid, e_y = max_rel(mid, ref["x_mid"]), max_rel(y, ref["y"])
+    print(f"    max-rel: x_mid {e_mid:.2e}  y {e_y:.2e}", flush=True)
+    assert e_mid <= TOL and e_y <= TOL, name
+    up_a = O.upsample_bilinear(ca, hc, wc, h, w)
+    up_f = O.upsample_bilinear(cf, hc, wc, h, w)
+    for b in range(B):
+        ka_mask = np.zeros(N, bool); ka_mask[ia[b]] = True
+        kf_mask = np.zeros(N, bool); kf_mask[jf[b]] = True
+        if ka > 0:
+            assert max_rel(mid[b, ka_mask], ref["hk"][b]) <= TOL
+        if kf > 0:
+            assert max_rel(y[b, kf_mask], ref["yk"][b]) <= TOL
+            base = mid[b, kf_mask].astype(np.float64)
+            assert branch_err(y[b, kf_mask], ref["yk"][b], base) <= TOL
+        for got, up, m in ((mid, up_a, ka_mask), (y, up_f, kf_mask)):
+            g, r = got[b, ~m].astype(np.float64), up[b, ~m]
+            assert np.all(np.abs(g - r) <= 2.0 ** -8 * 1.001 * np.abs(r) + 2e-6)
+    if ka > 0:
+        kg, vg = cache_rows(kc, vc, L0, L0 + ka)
+        assert max_rel(kg, ref["k_new"]) <= TOL and max_rel(vg, ref["v_new"]) <= TOL
+
+
+@pytest.mark.parametrize("ka,kf", [(128, 128), (0, 0), (256, 256), (100, 30), (0, 64), (64, 0), (26, 255)])
+def test_step_sublayer_d16_256px_matches_oracle(ka, kf):
+    wl = synth.WORKLOADS[synth.SMALL]
+    check_step_sublayer(wl.name, wl.dims, wl.sides, wl.step, wl.cache_step, 1, ka, kf, wl.L0_full, 688, seed=21)
+
+
+def test_step_sublayer_batched_ragged_matches_oracle():
+    check_step_sublayer("tiny128_b3", TINY128, (1, 2, 3, 5, 7, 11), 5, 3, 3, 50, 77, 88, 144, seed=22)
+    check_step_sublayer("tiny64_b2", TINY64, (1, 2, 3, 4, 6, 9), 5, 2, 2, 33, 9, 61, 96, seed=23)
+
+
+def test_step_sublayer_headline_full_size():
+    """1024 px last scale at keep 0.5 for both halves, the launch configuration of the benchmark."""
+    wl = synth.WORKLOADS[synth.HEADLINE]
+    check_step_sublayer(wl.name, wl.dims, wl.sides, wl.step, wl.cache_step, 1, wl.k, wl.k, wl.L0_full, 8480,
+                        seed=24)
+
+
+def test_step_sublayer_argument_errors():
+    print("[sublayer step] error paths", flush=True)
+    dims = TINY64
+    d = fb.make_dims(dims.D, dims.H, dims.dh, dims.F)
+    W = synth.block_weights(1, dims)
+    wt, wstruct = upload_weights(W)
+    sides = [1, 2, 4]
+    x = to_dev_bf16(synth.token_map(1, 1, 4, 4, dims.D))
+    kp, vp = synth.kv_prior(1, 1, 8, dims.H, dims.dh)
+    kc, vc = make_caches(kp, vp, 16)
+    ca = to_dev_bf16(synth.cached_map(1, 1, 2, 2, dims.D))
+    cf = to_dev_bf16(synth.cached_map(2, 1, 2, 2, dims.D))
+    mid = torch.zeros((1, 16, dims.D), dtype=torch.bfloat16, device=DEV)
+    y = torch.zeros((1, 16, dims.D), dtype=torch.bfloat16, device=DEV)
+    ia = torch.zeros((1, 4), dtype=torch.int32, device=DEV)
+    jf = torch.zeros((1, 4), dtype=torch.int32, device=DEV)
+    ws = empty_ws(fb.fastvar_step_sublayer_workspace_bytes(d, 1, 16, 4, 4))
+
+    def call(**over):
+        a = dict(x=x, sched_h=sides, sched_w=sides, step=2, cache_step=1, B=1, k_attn=4, k_ffn=4, dims=d,
+                 weights=wstruct, k_cache=kc, v_cache=vc, kv_len=8, L_cap=16, cache_map_attn=ca, cache_map_ffn=cf,
+                 x_mid=mid, y_out=y, idx_attn_out=ia, idx_ffn_out=jf, ws=ws)
+        a.update(over)
+        try:
+            fb.fastvar_step_sublayer(**a)
+        except fb.FastvarError as e:
+            return e.code
+        return 0
+
+    assert call(x_mid=x) == fb.FASTVAR_EINVAL
+    assert call(y_out=mid) == fb.FASTVAR_EINVAL
+    assert call(x_mid=None) == fb.FASTVAR_EINVAL
+    assert call(k_ffn=17) == fb.FASTVAR_EINVAL
+    assert call(cache_step=2) == fb.FASTVAR_EINVAL
+    assert call(kv_len=13) == fb.FASTVAR_ECAPACITY
+    assert call(ws=empty_ws(256)) == fb.FASTVAR_EWORKSPACE
+    torch.cuda.synchronize()
+    assert torch.all(y == 0) and torch.all(mid == 0)     # no output touched on error
+    assert call() == 0
+    torch.cuda.synchronize()

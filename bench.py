@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the pruned VAR decoding step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--wiring block|sublayer]
 
 A step is one pass of the whole hot path -- pivotal token selection, the
 transformer block on the kept tokens, cached token restoration -- through every
@@ -38,7 +38,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_state(wl, n_blocks, seed=0):
+def build_state(wl, n_blocks, seed=0, wiring="block"):
     """All device buffers of the workload.  Block 0 comes from the shared
     seeded numpy generators (so the CPU oracle can be fed the same values);
     the remaining blocks are drawn on the GPU with the same distributions."""
@@ -57,6 +57,7 @@ def build_state(wl, n_blocks, seed=0):
         x=synth.token_map(seed, B, wl.h, wl.h, dims.D),
         W=synth.block_weights(seed, dims),
         cache=synth.cached_map(seed, B, wl.hc, wl.hc, dims.D),
+        cache_attn=synth.cached_map(seed + 1000, B, wl.hc, wl.hc, dims.D),
     )
     host["kp"], host["vp"] = synth.kv_prior(seed, B, L0, dims.H, dims.dh)
 
@@ -75,6 +76,7 @@ def build_state(wl, n_blocks, seed=0):
             kc[:, :, :L0] = up(host["kp"]).permute(0, 2, 1, 3)
             vc[:, :, :, :L0] = up(host["vp"]).permute(0, 2, 3, 1)
             cache = up(host["cache"])
+            cache_attn = up(host["cache_attn"]) if wiring == "sublayer" else None
         else:
             D, F = dims.D, dims.F
             wt = dict(ln1_g=randn((D,), 0.02, 1.0), ln1_b=randn((D,), 0.02),
@@ -88,14 +90,22 @@ def build_state(wl, n_blocks, seed=0):
             kc[:, :, :L0] = randn((B, dims.H, L0, dims.dh))
             vc[:, :, :, :L0] = randn((B, dims.H, dims.dh, L0))
             cache = randn((B, wl.hc * wl.hc, dims.D))
-        blocks.append(dict(wt=wt, w=fb.make_weights(wt), kc=kc, vc=vc, cache=cache))
+            cache_attn = randn((B, wl.hc * wl.hc, dims.D)) if wiring == "sublayer" else None
+        blocks.append(dict(wt=wt, w=fb.make_weights(wt), kc=kc, vc=vc, cache=cache, cache_attn=cache_attn))
 
     d = fb.make_dims(dims.D, dims.H, dims.dh, dims.F)
-    ws = torch.empty(fb.fastvar_step_workspace_bytes(d, B, N, k), dtype=torch.uint8, device=dev)
+    ws_bytes = (fb.fastvar_step_sublayer_workspace_bytes(d, B, N, k, k) if wiring == "sublayer"
+                else fb.fastvar_step_workspace_bytes(d, B, N, k))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     xa = up(host["x"])
     xb = torch.empty_like(xa)
     idx = torch.empty((B, max(k, 1)), dtype=torch.int32, device=dev)
-    return dict(host=host, blocks=blocks, d=d, ws=ws, x_in=xa.clone(), xa=xa, xb=xb, idx=idx, L_cap=L_cap)
+    st = dict(host=host, blocks=blocks, d=d, ws=ws, x_in=xa.clone(), xa=xa, xb=xb, idx=idx, L_cap=L_cap,
+              wiring=wiring)
+    if wiring == "sublayer":
+        st["x_mid"] = torch.empty_like(xa)
+        st["idx2"] = torch.empty_like(idx)
+    return st
 
 
 def run_step(wl, st):
@@ -105,8 +115,13 @@ def run_step(wl, st):
     src, dst = st["xa"], st["xb"]
     sides = list(wl.sides)
     for blk in st["blocks"]:
-        fb.fastvar_step(src, sides, sides, wl.step, wl.cache_step, wl.B, wl.k, st["d"], blk["w"],
-                        blk["kc"], blk["vc"], wl.L0_full, st["L_cap"], blk["cache"], dst, st["idx"], st["ws"])
+        if st["wiring"] == "sublayer":
+            fb.fastvar_step_sublayer(src, sides, sides, wl.step, wl.cache_step, wl.B, wl.k, wl.k, st["d"],
+                                     blk["w"], blk["kc"], blk["vc"], wl.L0_full, st["L_cap"], blk["cache_attn"],
+                                     blk["cache"], st["x_mid"], dst, st["idx"], st["idx2"], st["ws"])
+        else:
+            fb.fastvar_step(src, sides, sides, wl.step, wl.cache_step, wl.B, wl.k, st["d"], blk["w"],
+                            blk["kc"], blk["vc"], wl.L0_full, st["L_cap"], blk["cache"], dst, st["idx"], st["ws"])
         src, dst = dst, src
     return src
 
@@ -213,7 +228,11 @@ def cpu_baseline(wl, st, n_blocks, target_seconds=12.0, max_reps=16):
     times = []
     while len(times) < max_reps and (not times or sum(times) < target_seconds):
         t0 = time.perf_counter()
-        O.step(h["x"], wl.h, wl.h, wl.k, h["W"], wl.dims.H, h["kp"], h["vp"], h["cache"], wl.hc, wl.hc)
+        if st["wiring"] == "sublayer":
+            O.step_sublayer(h["x"], wl.h, wl.h, wl.k, wl.k, h["W"], wl.dims.H, h["kp"], h["vp"], h["cache_attn"],
+                            h["cache"], wl.hc, wl.hc)
+        else:
+            O.step(h["x"], wl.h, wl.h, wl.k, h["W"], wl.dims.H, h["kp"], h["vp"], h["cache"], wl.hc, wl.hc)
         times.append(time.perf_counter() - t0)
     dt = sum(times) / len(times)
     cores = len(os.sched_getaffinity(0))
@@ -224,7 +243,7 @@ def cpu_baseline(wl, st, n_blocks, target_seconds=12.0, max_reps=16):
         blas = cores
     est_step = dt * n_blocks
     return dict(value=round(wl.B * wl.N / est_step, 3), unit="tokens/s", cores=min(cores, blas), kind="oracle",
-                sample=f"one block of {n_blocks} (select+block+restore, fp64 NumPy) run {len(times)} times, "
+                sample=f"one block of {n_blocks} ({'sub-layer wiring' if st['wiring'] == 'sublayer' else 'select+block+restore'}, fp64 NumPy) run {len(times)} times, "
                        f"{sum(times):.1f} s in all, mean {dt:.2f} s; stack time estimated as block time x {n_blocks}",
                 block_seconds=round(dt, 3), affinity_cores=cores, blas_threads=blas)
 
@@ -236,6 +255,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default=synth.HEADLINE, choices=sorted(synth.WORKLOADS))
     ap.add_argument("--blocks", type=int, default=0, help="blocks in the stack (default: the workload's)")
+    ap.add_argument("--wiring", default="block", choices=("block", "sublayer"),
+                    help="one selection/restoration pair around the block (the headline), or one around "
+                         "each of its two layers")
     ap.add_argument("--kernel-iters", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-table", action="store_true")
@@ -257,7 +279,7 @@ def main():
     n_blocks = args.blocks or wl.n_blocks
     log(f"workload {wl.name}: B={wl.B} N={wl.N} k={wl.k} L0={wl.L0_full} D={wl.dims.D} blocks={n_blocks}")
     t0 = time.perf_counter()
-    st = build_state(wl, n_blocks)
+    st = build_state(wl, n_blocks, wiring=args.wiring)
     torch.cuda.synchronize()
     log(f"inputs resident after {time.perf_counter()-t0:.1f} s; "
         f"HBM in use {torch.cuda.memory_allocated()/2**30:.2f} GiB")
@@ -299,7 +321,11 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "B": wl.B, "tokens": wl.N, "kept": wl.k, "prior_cache_tokens": wl.L0_full,
                    "D": dims.D, "heads": dims.H, "head_dim": dims.dh, "mlp": dims.F, "blocks": n_blocks,
-                   "step": "select -> block on kept tokens -> restore, every block of the stack"},
+                   "wiring": args.wiring,
+                   "step": ("select -> block on kept tokens -> restore, every block of the stack"
+                            if args.wiring == "block" else
+                            "select -> attention layer on kept tokens -> restore -> select -> FFN layer on kept "
+                            "tokens -> restore, every block of the stack")},
         "processed_tokens_per_s": round(wl.B * wl.k / (ms * 1e-3), 1),
         "us_per_block": round(ms / n_blocks * 1e3, 2),
         "mfma_frac_whole_block": round(flops_block * n_blocks / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),

@@ -108,6 +108,20 @@ def test_block_d30_batch8_sampled_rows():
     check_block("d30_s32_b8_sampled", wl.dims, wl.B, wl.h, wl.h, wl.k, wl.L0_pruned, 1400, seed=6, rows=rows)
 
 
+@pytest.mark.parametrize("name", ["inf2b_2k_s128_keep0.25", "inf2b_1024px_s64_keep1.0", "inf2b_1024px_s64_keep0.75",
+                                  "inf2b_1024px_s64_keep0.25", "inf2b_1024px_s64_keep0.1",
+                                  "inf2b_1024px_s48_keep0.5", "inf2b_2k_s96_keep0.3"])
+def test_block_model_configs_full_size_sampled_rows(name):
+    """The remaining model configurations at their full sizes (2K extension, keep-ratio sweep on the 64x64
+    scale, intermediate pruned scales), in the launch configurations the library picks for them: every kept
+    token's K/V row checked, block outputs on sampled rows."""
+    wl = synth.WORKLOADS[name]
+    L0 = wl.L0_pruned
+    rows = np.unique(np.concatenate([np.arange(0, 2), np.arange(wl.k - 3, wl.k),
+                                     np.random.default_rng(3).integers(0, wl.k, 27)]))
+    check_block(name, wl.dims, 1, wl.h, wl.h, wl.k, L0, (L0 + wl.k + 7) // 8 * 8, seed=9, rows=rows)
+
+
 def test_keep_all_equals_dense_block_on_gpu():
     """Keep ratio 1.0: the pruned path is the unpruned block (any kept order)."""
     print("[block] keep 1.0 == dense", flush=True)

@@ -322,3 +322,36 @@ def step_sublayer(x, h, w, k_attn, k_ffn, W, H, k_cache, v_cache, cache_attn, ca
     yk = ffn_sublayer_pruned(gather_tokens(src, idx_f), W, eps)
     y = restore(yk, idx_f, cache_ffn, hc, wc, h, w)
     return dict(idx_attn=idx_a, hk=hk, k_new=kn, v_new=vn, x_mid=mid, idx_ffn=idx_f, yk=yk, y=y)
+
+
+
+def scale_step(x, h, w, k, layers, H, k_caches, v_caches, cache_maps, hc, wc, structure, capture=False,
+               eps: float = 1e-6, scale: Optional[float] = None):
+    """One scale step of a stack of blocks (Fig. 2(a); Sec. 3.3, overview).
+
+    layers: list of weight dicts; k_caches / v_caches: per block [B, L0, H, dh];
+    cache_maps: per block [B, hc*wc, D] (unused in the structure stage).
+    structure=True: every block runs on all tokens, no selection or restoration
+    (the stage is kept as the standard model); with capture the block outputs are
+    returned as the new cached maps.  Otherwise each block runs select -> block on
+    the kept tokens -> restore from its own cached map; k == N runs it unpruned
+    and k == 0 leaves only the upsampled cache.  Only kept tokens enter a cache.
+
+    Returns dict(y, k_caches, v_caches (grown), captured (list or None), idx (of the
+    last block, None when nothing was selected)).
+    """
+    cur = np.asarray(x, F64)
+    N = h * w
+    new_k, new_v, captured, idx = [], [], ([] if capture else None), None
+    for l, W in enumerate(layers):
+        if structure or k == N:
+            y, kn, vn = block_forward_pruned(cur, W, H, k_caches[l], v_caches[l], eps, scale)
+        else:
+            r = step(cur, h, w, k, W, H, k_caches[l], v_caches[l], cache_maps[l], hc, wc, eps, scale)
+            y, kn, vn, idx = r["y"], r["k_new"], r["v_new"], r["idx"]
+        new_k.append(np.concatenate([np.asarray(k_caches[l], F64), kn], axis=1))
+        new_v.append(np.concatenate([np.asarray(v_caches[l], F64), vn], axis=1))
+        if capture:
+            captured.append(y)
+        cur = y
+    return dict(y=cur, k_caches=new_k, v_caches=new_v, captured=captured, idx=idx)

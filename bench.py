@@ -248,6 +248,89 @@ def cpu_baseline(wl, st, n_blocks, target_seconds=12.0, max_reps=16):
                 block_seconds=round(dt, 3), affinity_cores=cores, blas_threads=blas)
 
 
+def schedule_bench(wl, n_blocks, steps, warmup, keeps=(0.6, 0.5, 0.0, 0.0)):
+    """The whole scale schedule of the workload's model through fastvar_scale_step, twice: every step
+    unpruned, and with the last len(keeps) steps pruned to the given keep ratios after a cache capture
+    at the step before them (the paper's setting for this model: pruning ratios 40, 50, 100, 100 % on
+    the last four steps).  Token maps are seeded synthetic ones per scale (the tokenizer and the
+    residual accumulation between scales are outside the library).  Returns a dict for the JSON line."""
+    import torch
+    from paper_2503_23367_amd import binding as fb
+    dev = "cuda:0"
+    dims, B, sides = wl.dims, wl.B, list(wl.sides)
+    K = len(sides)
+    cache_step = K - len(keeps) - 1
+    hc = sides[cache_step]
+    L_cap = (sum(s * s for s in sides) + 7) // 8 * 8
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(777)
+
+    def randn(shape, std=1.0, mean=0.0):
+        return (torch.randn(shape, generator=gen, device=dev, dtype=torch.float32) * std + mean).to(torch.bfloat16)
+
+    D, F = dims.D, dims.F
+    layers = []
+    for _ in range(n_blocks):
+        wt = dict(ln1_g=randn((D,), 0.02, 1.0), ln1_b=randn((D,), 0.02),
+                  w_qkv=randn((3 * D, D), 0.02), b_qkv=randn((3 * D,), 0.02),
+                  w_proj=randn((D, D), 0.02), b_proj=randn((D,), 0.02),
+                  ln2_g=randn((D,), 0.02, 1.0), ln2_b=randn((D,), 0.02),
+                  w_fc1=randn((F, D), 0.02), b_fc1=randn((F,), 0.02),
+                  w_fc2=randn((D, F), 0.02), b_fc2=randn((D,), 0.02))
+        layers.append(dict(wt=wt, w=fb.make_weights(wt),
+                           kc=torch.zeros((B, dims.H, L_cap, dims.dh), dtype=torch.bfloat16, device=dev),
+                           vc=torch.zeros((B, dims.H, dims.dh, L_cap), dtype=torch.bfloat16, device=dev),
+                           cache=torch.zeros((B, hc * hc, D), dtype=torch.bfloat16, device=dev)))
+    arr = fb.make_layers(layers)
+    d = fb.make_dims(dims.D, dims.H, dims.dh, dims.F)
+
+    def up(a):
+        bits = synth.to_bf16_bits(a).astype(np.int16)
+        return torch.from_numpy(bits).to(dev).view(torch.bfloat16).reshape(a.shape)
+
+    xs = [up(synth.token_map(100 + i, B, s, s, D)) for i, s in enumerate(sides)]
+    Nmax = sides[-1] ** 2
+    y = torch.empty((B, Nmax, D), dtype=torch.bfloat16, device=dev)
+    tmp = torch.empty_like(y)
+    idx = torch.empty((B, Nmax), dtype=torch.int32, device=dev)
+    ws = torch.empty(fb.fastvar_step_workspace_bytes(d, B, Nmax, Nmax), dtype=torch.uint8, device=dev)
+
+    def k_of(i, pruned):
+        N = sides[i] ** 2
+        return fb.fastvar_keep_count(N, keeps[i - cache_step - 1]) if pruned and i > cache_step else N
+
+    def one_image(pruned, stamps=None):
+        kv = 0
+        for i in range(K):
+            if stamps is not None:
+                stamps[i].record()
+            kv = fb.fastvar_scale_step(xs[i], sides, sides, i, cache_step, B, k_of(i, pruned), d, arr, kv, L_cap,
+                                       y, tmp, idx, ws)
+        if stamps is not None:
+            stamps[K].record()
+        return kv
+
+    out = {}
+    for name, pruned in (("unpruned", False), ("fastvar", True)):
+        for _ in range(warmup):
+            one_image(pruned)
+        torch.cuda.synchronize()
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(K + 1)] for _ in range(steps)]
+        t0 = time.perf_counter()
+        for r in range(steps):
+            kv = one_image(pruned, ev[r])
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3 / steps
+        per_step = [sum(ev[r][i].elapsed_time(ev[r][i + 1]) for r in range(steps)) / steps for i in range(K)]
+        out[name] = dict(ms_per_image=round(wall, 3), kv_tokens=kv, ms_per_scale=[round(v, 3) for v in per_step],
+                         kept=[k_of(i, pruned) for i in range(K)])
+        log(f"{name}: {wall:.2f} ms per image; per scale " + " ".join(f"{v:.2f}" for v in per_step))
+    out["speedup"] = round(out["unpruned"]["ms_per_image"] / out["fastvar"]["ms_per_image"], 3)
+    out["last_two_scales_share_unpruned"] = round(sum(out["unpruned"]["ms_per_scale"][-2:]) /
+                                                  sum(out["unpruned"]["ms_per_scale"]), 3)
+    return dict(sides=sides, cache_step=cache_step, keep_ratios=list(keeps), blocks=n_blocks, **out)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -258,6 +341,9 @@ def main():
     ap.add_argument("--wiring", default="block", choices=("block", "sublayer"),
                     help="one selection/restoration pair around the block (the headline), or one around "
                          "each of its two layers")
+    ap.add_argument("--schedule", action="store_true",
+                    help="instead of the headline step: the model's whole scale schedule, unpruned and with the "
+                         "last four steps pruned (one JSON line of its own)")
     ap.add_argument("--kernel-iters", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-table", action="store_true")
@@ -278,6 +364,18 @@ def main():
     wl = synth.WORKLOADS[args.workload]
     n_blocks = args.blocks or wl.n_blocks
     log(f"workload {wl.name}: B={wl.B} N={wl.N} k={wl.k} L0={wl.L0_full} D={wl.dims.D} blocks={n_blocks}")
+    if args.schedule:
+        res = schedule_bench(wl, n_blocks, args.steps, args.warmup)
+        print(json.dumps({"metric": "whole scale schedule, transformer stack only: ms per image unpruned vs "
+                                    "FastVAR pruning schedule", "value": res["speedup"], "unit": "x (unpruned / pruned)",
+                          "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                          "ms_per_step": res["fastvar"]["ms_per_image"], "higher_is_better": True, "scaling": "weak",
+                          "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+                          "config": {"workload": wl.name + " (all scales)", **{k: res[k] for k in
+                                     ("sides", "cache_step", "keep_ratios", "blocks")}},
+                          "schedule": {k: res[k] for k in ("unpruned", "fastvar", "speedup",
+                                                             "last_two_scales_share_unpruned")}}), flush=True)
+        return
     t0 = time.perf_counter()
     st = build_state(wl, n_blocks, wiring=args.wiring)
     torch.cuda.synchronize()

@@ -92,6 +92,16 @@ typedef struct fastvar_block_weights {
     const void* b_fc2;  /* [D] or NULL */
 } fastvar_block_weights;
 
+/* One block of a stack, for fastvar_scale_step: its weights, its KV cache and
+ * its cached output map (Sec. 3.3, overview: the per-layer outputs of the last
+ * structure step are saved as the cache). */
+typedef struct fastvar_layer {
+    const fastvar_block_weights* weights; /* host struct of device pointers */
+    void* k_cache;                        /* [B, H, L_cap, dh] bf16 */
+    void* v_cache;                        /* [B, H, dh, L_cap] bf16 */
+    void* cache_map;                      /* [B, hc*wc, D] bf16, (hc,wc) = sched[cache_step] */
+} fastvar_layer;
+
 /* ---- host-only helpers -------------------------------------------------- */
 
 int fastvar_version(void);
@@ -153,7 +163,9 @@ int fastvar_select_pivotal(const void* x, int B, int h, int w, int D, int k,
  * fc1(LN2(h1)))) with GELU evaluated in its tanh form (within 3e-4 of the erf
  * form, below bf16 resolution); attention is unmasked softmax over
  * cache positions [0, L0+k), the last k of which this call writes.  k == 0
- * is a no-op that returns FASTVAR_OK.
+ * is a no-op that returns FASTVAR_OK.  idx may be NULL when k == N: every
+ * token is kept, in order -- the unpruned block of the structure construction
+ * stage (Sec. 3.3, overview).
  */
 int fastvar_block_forward_pruned(const void* x, int N, const int32_t* idx, int B, int k,
                                  const fastvar_dims* dims /* host */,
@@ -197,6 +209,36 @@ int fastvar_step(const void* x, const int32_t* sched_h /* host */, const int32_t
                  void* k_cache, void* v_cache, int32_t* kv_len /* host in/out */, int L_cap,
                  const void* cache_map, void* y_out, int32_t* idx_out,
                  void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * One scale step of a whole stack of blocks (Fig. 2(a); Sec. 3.3, overview):
+ * the output map of a block is the input of the next.
+ *   step <= cache_step  structure construction stage: every block runs
+ *                       unpruned (k must equal h*w; no selection, no
+ *                       restoration).  At step == cache_step each block's
+ *                       output is also written to its cache_map (which must
+ *                       then hold [B, h*w, D]): the cache capture.
+ *   step >  cache_step  texture filling stage: each block runs selection,
+ *                       block on the k kept tokens, restoration from its own
+ *                       cache_map, as fastvar_step does (k == h*w runs the
+ *                       block unpruned, k == 0 skips it: pure upsample).
+ *   layers              host array of n_layers blocks
+ *   kv_len              host in/out: every block's cache length before / after
+ *   y_out               [B, h*w, D] bf16: output map of the last block
+ *   tmp                 [B, h*w, D] bf16 scratch map (may be NULL for one
+ *                       block or at the capture step); x, y_out, tmp distinct
+ *   idx_out             [B, k] int32: kept indices of the last block (may be
+ *                       NULL when k == h*w)
+ *   ws                  scratch of fastvar_step_workspace_bytes(dims, B, h*w, k)
+ * The token maps of different scales come from the tokenizer and the residual
+ * accumulation of Eq. 2-3, which are outside this library: the caller supplies x.
+ */
+int fastvar_scale_step(const void* x, const int32_t* sched_h /* host */, const int32_t* sched_w /* host */,
+                       int K, int step, int cache_step, int B, int k,
+                       const fastvar_dims* dims /* host */, const fastvar_layer* layers /* host */, int n_layers,
+                       int32_t* kv_len /* host in/out */, int L_cap,
+                       void* y_out, void* tmp, int32_t* idx_out,
+                       void* ws, size_t ws_bytes, void* stream);
 
 /*
  * The two halves of the block, each on its own kept set (Fig. 2(b) and Sec. 3.3,

@@ -41,13 +41,18 @@ class BlockWeights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in WEIGHT_FIELDS]
 
 
+class Layer(C.Structure):
+    _fields_ = [("weights", C.POINTER(BlockWeights)), ("k_cache", C.c_void_p), ("v_cache", C.c_void_p),
+                ("cache_map", C.c_void_p)]
+
+
 _lib = None
 
 EXPORTS = ("fastvar_version", "fastvar_strerror", "fastvar_keep_count",
            "fastvar_select_workspace_bytes", "fastvar_block_workspace_bytes",
            "fastvar_restore_workspace_bytes", "fastvar_step_workspace_bytes",
            "fastvar_select_pivotal", "fastvar_block_forward_pruned", "fastvar_restore",
-           "fastvar_step", "fastvar_step_sublayer_workspace_bytes", "fastvar_attn_forward_pruned",
+           "fastvar_step", "fastvar_scale_step", "fastvar_step_sublayer_workspace_bytes", "fastvar_attn_forward_pruned",
            "fastvar_ffn_forward_pruned", "fastvar_step_sublayer", "fastvar_layernorm", "fastvar_gemm_bf16",
            "fastvar_qkv_gemm", "fastvar_attention")
 
@@ -87,6 +92,10 @@ def lib() -> C.CDLL:
     L.fastvar_step.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), i32, i32, i32, i32, i32,
                                C.POINTER(Dims), C.POINTER(BlockWeights), vp, vp, C.POINTER(C.c_int32), i32,
                                vp, vp, vp, vp, sz, vp]
+    L.fastvar_scale_step.restype = i32
+    L.fastvar_scale_step.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), i32, i32, i32, i32, i32,
+                                     C.POINTER(Dims), C.POINTER(Layer), i32, C.POINTER(C.c_int32), i32,
+                                     vp, vp, vp, vp, sz, vp]
     L.fastvar_step_sublayer_workspace_bytes.restype = sz
     L.fastvar_step_sublayer_workspace_bytes.argtypes = [C.POINTER(Dims), i32, i32, i32, i32]
     L.fastvar_attn_forward_pruned.restype = i32
@@ -211,6 +220,32 @@ def fastvar_step(x, sched_h, sched_w, step, cache_step, B, k, dims: Dims, weight
                             _ptr(idx_out), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
                             _stream())
     _check(rc, "fastvar_step")
+    return kv.value
+
+
+def make_layers(blocks):
+    """Host array of Layer structs from dicts with keys w (BlockWeights), kc, vc, cache (tensors; cache may be
+    None).  Keeps no reference to the tensors; the BlockWeights structs must outlive the array."""
+    arr = (Layer * len(blocks))()
+    for i, b in enumerate(blocks):
+        arr[i].weights = C.pointer(b["w"])
+        arr[i].k_cache = _ptr(b["kc"])
+        arr[i].v_cache = _ptr(b["vc"])
+        arr[i].cache_map = _ptr(b.get("cache"))
+    return arr
+
+
+def fastvar_scale_step(x, sched_h, sched_w, step, cache_step, B, k, dims: Dims, layers, kv_len: int, L_cap,
+                       y_out, tmp, idx_out, ws) -> int:
+    """`layers`: array from make_layers.  Returns the new cache length."""
+    K = len(sched_h)
+    sh = (C.c_int32 * K)(*sched_h)
+    sw = (C.c_int32 * K)(*sched_w)
+    kv = C.c_int32(kv_len)
+    rc = lib().fastvar_scale_step(_ptr(x), sh, sw, K, step, cache_step, B, k, C.byref(dims), layers, len(layers),
+                                  C.byref(kv), L_cap, _ptr(y_out), _ptr(tmp), _ptr(idx_out), _ptr(ws),
+                                  0 if ws is None else ws.numel() * ws.element_size(), _stream())
+    _check(rc, "fastvar_scale_step")
     return kv.value
 
 

@@ -77,7 +77,7 @@ int check_block(const void* x, int N, const int32_t* idx, int B, int k, const fa
     rc = check_weights(wts);
     if (rc) return rc;
     if (!x || !kc || !vc || B <= 0 || N <= 0 || k < 0 || k > N || L0 < 0 || L_cap <= 0) return FASTVAR_EINVAL;
-    if (k > 0 && (!idx || !y)) return FASTVAR_EINVAL;
+    if (k > 0 && (!y || (!idx && k != N))) return FASTVAR_EINVAL;   // no index list: every token kept
     if ((long)L0 + k > L_cap) return FASTVAR_ECAPACITY;
     if (L_cap % 8 != 0) return FASTVAR_EALIGN;
     if (!aligned16(x) || !aligned16(kc) || !aligned16(vc) || (y && !aligned16(y)) || (ws && !aligned16(ws)))
@@ -121,8 +121,11 @@ void enqueue_attn(const void* x, int N, const int32_t* idx, int B, int k, const 
     int32_t* rows = reinterpret_cast<int32_t*>(base + bp.off_rows);
     const int M = B * k;
 
-    // a1 = LN1(x[idx])
-    fv::launch_gather_layernorm(x, idx, B, N, k, d->D, w->ln1_g, w->ln1_b, d->ln_eps, rows, buf_a, st);
+    // a1 = LN1(x[idx]); without an index list every token is kept, in order
+    if (idx)
+        fv::launch_gather_layernorm(x, idx, B, N, k, d->D, w->ln1_g, w->ln1_b, d->ln_eps, rows, buf_a, st);
+    else
+        fv::launch_layernorm(x, M, d->D, w->ln1_g, w->ln1_b, d->ln_eps, buf_a, st);
     // q | k | v = a1 * Wqkv^T + b ; k, v appended to the caches at [L0, L0+k)
     fv::GemmArgs g{};
     g.A = buf_a; g.W = w->w_qkv; g.bias = w->b_qkv; g.M = M; g.N = 3 * d->D; g.K = d->D;
@@ -138,7 +141,7 @@ void enqueue_attn(const void* x, int N, const int32_t* idx, int B, int k, const 
     // h1 = x[idx] + o * Wp^T + bp
     fv::GemmArgs pj{};
     pj.A = buf_a; pj.W = w->w_proj; pj.bias = w->b_proj; pj.M = M; pj.N = d->D; pj.K = d->D;
-    pj.out = h1_out; pj.residual = x; pj.res_rows = rows; pj.k_tokens = k;
+    pj.out = h1_out; pj.residual = x; pj.res_rows = idx ? rows : nullptr; pj.k_tokens = k;
     fv::launch_gemm(fv::EPI_BIAS_RES, pj, st);
 }
 
@@ -322,6 +325,93 @@ int fastvar_step(const void* x, const int32_t* sched_h, const int32_t* sched_w, 
     if (k > 0)
         enqueue_block(x, N, idx_out, B, k, dims, weights, k_cache, v_cache, L0, L_cap, yk, ws_blk, st);
     fv::launch_restore(yk, rank, B, k, cache_map, hc, wc, h, w, D, y_out, st);
+    rc = launch_status();
+    if (rc == FASTVAR_OK) *kv_len = L0 + k;
+    return rc;
+}
+
+int fastvar_scale_step(const void* x, const int32_t* sched_h, const int32_t* sched_w, int K, int step,
+                       int cache_step, int B, int k, const fastvar_dims* dims, const fastvar_layer* layers,
+                       int n_layers, int32_t* kv_len, int L_cap, void* y_out, void* tmp, int32_t* idx_out,
+                       void* ws, size_t ws_bytes, void* stream) {
+    if (!sched_h || !sched_w || !kv_len || !layers || K <= 0 || n_layers <= 0) return FASTVAR_EINVAL;
+    if (step < 0 || step >= K || cache_step < 0 || cache_step >= K) return FASTVAR_EINVAL;
+    const int h = sched_h[step], w = sched_w[step];
+    if (h <= 0 || w <= 0 || (long)h * w > FASTVAR_MAX_TOKENS) return FASTVAR_EINVAL;
+    const int N = h * w;
+    const bool structure = step <= cache_step;      // structure stage: standard, unpruned
+    const bool capture = step == cache_step;
+    if (B <= 0 || k < 0 || k > N || (structure && k != N)) return FASTVAR_EINVAL;
+    int rc = check_dims(dims);
+    if (rc) return rc;
+    const int D = dims->D;
+    if (!x || !y_out || y_out == x || tmp == x || tmp == y_out) return FASTVAR_EINVAL;
+    if (!tmp && n_layers > 1 && !capture) return FASTVAR_EINVAL;
+    if (!aligned16(x) || !aligned16(y_out) || (tmp && !aligned16(tmp))) return FASTVAR_EALIGN;
+    if (!ws) return FASTVAR_EWORKSPACE;
+    if (!aligned16(ws)) return FASTVAR_EALIGN;
+    if (ws_bytes < fastvar_step_workspace_bytes(dims, B, N, k)) return FASTVAR_EWORKSPACE;
+    const int L0 = *kv_len;
+    const bool dense = k == N;
+    if (!dense && !idx_out) return FASTVAR_EINVAL;
+    const int hc = sched_h[cache_step], wc = sched_w[cache_step];
+
+    const size_t sel_bytes = fastvar_select_workspace_bytes(B, N, D);
+    const size_t rank_bytes = fastvar_restore_workspace_bytes(B, N);
+    char* base = static_cast<char*>(ws);
+    void* ws_sel = base;
+    int32_t* rank = reinterpret_cast<int32_t*>(base + sel_bytes);
+    char* ws_blk = base + sel_bytes + rank_bytes;
+    const size_t blk_bytes = ws_bytes - sel_bytes - rank_bytes;
+    void* yk = k > 0 ? static_cast<void*>(ws_blk + block_plan(dims, B, k).off_q) : nullptr;
+
+    // Every layer is checked before the first launch.  Output of layer l: its own cache map at the
+    // capture step (the next layer reads it from there), else tmp / y_out alternating so that the last
+    // layer writes y_out.
+    auto dst_of = [&](int l) -> void* {
+        if (capture) return layers[l].cache_map;
+        return ((n_layers - 1 - l) % 2 == 0) ? y_out : tmp;
+    };
+    for (int l = 0; l < n_layers; ++l) {
+        const fastvar_layer& ly = layers[l];
+        if (!ly.weights || !ly.k_cache || !ly.v_cache) return FASTVAR_EINVAL;
+        if ((capture || !structure) && !ly.cache_map) return FASTVAR_EINVAL;
+        const void* src = l == 0 ? x : dst_of(l - 1);
+        void* dst = dst_of(l);
+        if (!aligned16(dst) || dst == x) return FASTVAR_EINVAL;
+        if (dense) {
+            rc = check_block(src, N, nullptr, B, k, dims, ly.weights, ly.k_cache, ly.v_cache, L0, L_cap, dst, ws_blk,
+                             blk_bytes);
+        } else {
+            rc = check_select(src, B, h, w, D, k, idx_out, ws_sel, sel_bytes);
+            if (!rc)
+                rc = check_block(src, N, idx_out, B, k, dims, ly.weights, ly.k_cache, ly.v_cache, L0, L_cap, yk,
+                                 ws_blk, blk_bytes);
+            if (!rc) rc = check_restore(yk, idx_out, rank, B, k, ly.cache_map, hc, wc, h, w, D, dst, nullptr, 0);
+        }
+        if (rc) return rc;
+    }
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const fv::SelectPlan sp = fv::select_plan(B, N, D);
+    for (int l = 0; l < n_layers; ++l) {
+        const fastvar_layer& ly = layers[l];
+        const void* src = l == 0 ? x : dst_of(l - 1);
+        void* dst = dst_of(l);
+        if (dense) {
+            enqueue_block(src, N, nullptr, B, k, dims, ly.weights, ly.k_cache, ly.v_cache, L0, L_cap, dst, ws_blk, st);
+        } else {
+            fv::launch_select(src, B, N, D, k, idx_out, rank, nullptr, ws_sel, sp, st);
+            if (k > 0)
+                enqueue_block(src, N, idx_out, B, k, dims, ly.weights, ly.k_cache, ly.v_cache, L0, L_cap, yk, ws_blk,
+                              st);
+            fv::launch_restore(yk, rank, B, k, ly.cache_map, hc, wc, h, w, D, dst, st);
+        }
+    }
+    if (capture &&
+        hipMemcpyAsync(y_out, layers[n_layers - 1].cache_map, (size_t)B * N * D * 2, hipMemcpyDeviceToDevice, st) !=
+            hipSuccess)
+        return FASTVAR_EHIP;
     rc = launch_status();
     if (rc == FASTVAR_OK) *kv_len = L0 + k;
     return rc;

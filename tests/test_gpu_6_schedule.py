@@ -1,0 +1,209 @@
+"""GPU parity: fastvar_scale_step, the stack-level scale step (Fig. 2(a); Sec. 3.3, overview), and the
+unpruned block (no index list) it uses in the structure construction stage.
+
+A whole small schedule is run through the library for a one-block stack and compared with the
+oracle step by step: caches grow by the kept tokens only, the map captured at the cached step feeds
+the pruned steps, a skipped step leaves the upsampled cache.  For several blocks the selection of
+block l+1 depends on the device's bf16 output of block l, so the stack is checked against the
+library's own single-block entry points, which must give the same bits, and those are checked
+against the oracle elsewhere.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fastvar_oracle as O
+from paper_2503_23367_amd import binding as fb
+from paper_2503_23367_amd import synth
+from gpu_util import (DEV, cache_rows, empty_ws, from_dev_bf16, make_caches, max_rel, to_dev_bf16,
+                      upload_weights)
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+TINY128 = synth.BlockDims(D=256, H=2, dh=128, F=512)
+TINY64 = synth.BlockDims(D=192, H=3, dh=64, F=320)
+
+
+@pytest.mark.parametrize("dims,B,h,w,L0,L_cap", [(TINY64, 2, 5, 7, 13, 48), (TINY128, 1, 1, 1, 0, 8),
+                                                (TINY128, 3, 2, 2, 1, 8), (synth.D16, 1, 16, 16, 424, 680)])
+def test_unpruned_block_without_index_list(dims, B, h, w, L0, L_cap):
+    print(f"[dense block] D={dims.D} B={B} N={h*w} L0={L0}", flush=True)
+    N = h * w
+    x_np = synth.token_map(31, B, h, w, dims.D)
+    W = synth.block_weights(31, dims)
+    kp, vp = synth.kv_prior(31, B, L0, dims.H, dims.dh)
+    d = fb.make_dims(dims.D, dims.H, dims.dh, dims.F)
+    wt, wstruct = upload_weights(W)
+    x = to_dev_bf16(x_np)
+    kc, vc = make_caches(kp, vp, L_cap)
+    y = torch.full((B, N, dims.D), float("nan"), dtype=torch.bfloat16, device=DEV)
+    ws = empty_ws(fb.fastvar_block_workspace_bytes(d, B, N))
+    ws.fill_(0xFF)
+    fb.fastvar_block_forward_pruned(x, N, None, B, N, d, wstruct, kc, vc, L0, L_cap, y, ws)
+    torch.cuda.synchronize()
+    ref, kn, vn = O.block_forward_pruned(x_np, W, dims.H, kp, vp)
+    got = from_dev_bf16(y)
+    kg, vg = cache_rows(kc, vc, L0, L0 + N)
+    assert not np.isnan(got).any()
+    assert max_rel(got, ref) <= TOL and max_rel(kg, kn) <= TOL and max_rel(vg, vn) <= TOL
+    # the same rows as with the identity index list, bit for bit
+    kc2, vc2 = make_caches(kp, vp, L_cap)
+    y2 = torch.empty_like(y)
+    idx = torch.arange(N, dtype=torch.int32, device=DEV).repeat(B, 1)
+    fb.fastvar_block_forward_pruned(x, N, idx, B, N, d, wstruct, kc2, vc2, L0, L_cap, y2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
+    # an index list may only be left out when every token is kept
+    if N > 1:
+        with pytest.raises(fb.FastvarError):
+            fb.fastvar_block_forward_pruned(x, N, None, B, N - 1, d, wstruct, kc, vc, L0, L_cap, y, ws)
+
+
+def _stack(dims, n_layers, B, L_cap, hc, wc, seed):
+    layers = []
+    for l in range(n_layers):
+        W = synth.block_weights(seed + l, dims)
+        wt, wstruct = upload_weights(W)
+        kp, vp = synth.kv_prior(seed + l, B, 0, dims.H, dims.dh)
+        kc, vc = make_caches(kp, vp, L_cap)
+        cache = torch.full((B, hc * wc, dims.D), float("nan"), dtype=torch.bfloat16, device=DEV)
+        layers.append(dict(W=W, wt=wt, w=wstruct, kc=kc, vc=vc, cache=cache))
+    return layers
+
+
+def test_one_block_schedule_matches_oracle_step_by_step():
+    """Sides (1,2,3,5,8,11): structure steps 0-3 (capture at the 5x5 step), then keep 0.6, a skipped
+    step is replaced by keep 0 at the last scale."""
+    dims, B = TINY128, 2
+    sides = (1, 2, 3, 5, 8, 11)
+    cache_step = 3
+    keeps = {4: 0.6, 5: 0.0}
+    L_cap = 1 + 4 + 9 + 25 + 64 + 121 + 7
+    L_cap = (L_cap + 7) // 8 * 8
+    hc = wc = sides[cache_step]
+    layers = _stack(dims, 1, B, L_cap, hc, wc, seed=50)
+    arr = fb.make_layers(layers)
+    d = fb.make_dims(dims.D, dims.H, dims.dh, dims.F)
+    o_k = [np.zeros((B, 0, dims.H, dims.dh))]
+    o_v = [np.zeros((B, 0, dims.H, dims.dh))]
+    o_cache = None
+    kv_len = 0
+    for step, side in enumerate(sides):
+        N = side * side
+        k = N if step <= cache_step else fb.fastvar_keep_count(N, keeps[step])
+        print(f"[schedule] step {step} side {side} k={k} kv_len={kv_len}", flush=True)
+        x_np = synth.token_map(60 + step, B, side, side, dims.D)
+        x = to_dev_bf16(x_np)
+        y = torch.full((B, N, dims.D), float("nan"), dtype=torch.bfloat16, device=DEV)
+        idx = torch.full((B, max(k, 1)), -7, dtype=torch.int32, device=DEV)
+        ws = empty_ws(fb.fastvar_step_workspace_bytes(d, B, N, k))
+        ws.fill_(0xFF)
+        new_len = fb.fastvar_scale_step(x, list(sides), list(sides), step, cache_step, B, k, d, arr, kv_len, L_cap,
+                                        y, None, idx, ws)
+        torch.cuda.synchronize()
+        ref = O.scale_step(x_np, side, side, k, [layers[0]["W"]], dims.H, o_k, o_v, o_cache, hc, wc,
+                           structure=step <= cache_step, capture=step == cache_step)
+        got = from_dev_bf16(y)
+        assert new_len == kv_len + k
+        assert not np.isnan(got).any()
+        assert max_rel(got, ref["y"]) <= TOL, step
+        if step > cache_step and 0 < k < N:
+            np.testing.assert_array_equal(idx[:, :k].cpu().numpy(), ref["idx"])
+        if k > 0:
+            kg, vg = cache_rows(layers[0]["kc"], layers[0]["vc"], kv_len, kv_len + k)
+            assert max_rel(kg, ref["k_caches"][0][:, kv_len:]) <= TOL
+            assert max_rel(vg, ref["v_caches"][0][:, kv_len:]) <= TOL
+        if step == cache_step:
+            # the captured map is the output itself; the oracle goes on with the device's bf16 copy of it
+            assert torch.equal(layers[0]["cache"].view(torch.int16), y.view(torch.int16))
+            o_cache = [from_dev_bf16(layers[0]["cache"]).astype(np.float64)]
+        # the oracle's caches follow the device's bf16 rows, so that later steps see identical keys
+        kall, vall = cache_rows(layers[0]["kc"], layers[0]["vc"], 0, new_len)
+        o_k, o_v = [kall.astype(np.float64)], [vall.astype(np.float64)]
+        kv_len = new_len
+    # the last step kept nothing: the output is the upsampled captured map, within one bf16 rounding
+    up = O.upsample_bilinear(o_cache[0], hc, wc, sides[-1], sides[-1])
+    assert np.all(np.abs(got - up) <= 2.0 ** -8 * 1.001 * np.abs(up) + 2e-6)
+
+
+@pytest.mark.parametrize("n_layers", [2, 3])
+def test_stack_equals_the_single_block_entry_points(n_layers):
+    dims, B = TINY64, 2
+    sides = (2, 3, 4, 6, 9)
+    cache_step = 2
+    hc = wc = sides[cache_step]
+    L_cap = 160
+    d = fb.make_dims(dims.D, dims.H, dims.dh, dims.F)
+    A = _stack(dims, n_layers, B, L_cap, hc, wc, seed=70)      # through fastvar_scale_step
+    Bk = _stack(dims, n_layers, B, L_cap, hc, wc, seed=70)     # block by block
+    arr = fb.make_layers(A)
+    kv_a = kv_b = 0
+    for step, side in enumerate(sides):
+        N = side * side
+        k = N if step <= cache_step else fb.fastvar_keep_count(N, 0.45)
+        print(f"[stack] layers={n_layers} step {step} side {side} k={k}", flush=True)
+        x = to_dev_bf16(synth.token_map(80 + step, B, side, side, dims.D))
+        y = torch.full((B, N, dims.D), float("nan"), dtype=torch.bfloat16, device=DEV)
+        tmp = torch.full_like(y, float("nan"))
+        idx = torch.zeros((B, k), dtype=torch.int32, device=DEV)
+        ws = empty_ws(fb.fastvar_step_workspace_bytes(d, B, N, k))
+        kv_a = fb.fastvar_scale_step(x, list(sides), list(sides), step, cache_step, B, k, d, arr, kv_a, L_cap, y,
+                                     tmp, idx, ws)
+        # the same through the single-block calls
+        cur = x
+        for l, ly in enumerate(Bk):
+            out = torch.empty_like(y)
+            if step <= cache_step:
+                fb.fastvar_block_forward_pruned(cur, N, None, B, N, d, ly["w"], ly["kc"], ly["vc"], kv_b, L_cap, out,
+                                                ws)
+                if step == cache_step:
+                    ly["cache"] = out.clone()
+            else:
+                idx_b = torch.zeros((B, k), dtype=torch.int32, device=DEV)
+                fb.fastvar_step(cur, list(sides), list(sides), step, cache_step, B, k, d, ly["w"], ly["kc"], ly["vc"],
+                                kv_b, L_cap, ly["cache"], out, idx_b, ws)
+            cur = out
+        kv_b += k
+        torch.cuda.synchronize()
+        assert kv_a == kv_b
+        assert torch.equal(y.view(torch.int16), cur.view(torch.int16)), step
+        if step > cache_step:
+            assert torch.equal(idx, idx_b)
+        for la, lb in zip(A, Bk):
+            assert torch.equal(la["kc"][:, :, :kv_a].view(torch.int16), lb["kc"][:, :, :kv_a].view(torch.int16))
+            assert torch.equal(la["vc"][:, :, :, :kv_a].view(torch.int16), lb["vc"][:, :, :, :kv_a].view(torch.int16))
+            if step == cache_step:
+                assert torch.equal(la["cache"].view(torch.int16), lb["cache"].view(torch.int16))
+
+
+def test_scale_step_argument_errors():
+    print("[scale step] error paths", flush=True)
+    dims, B = TINY64, 1
+    sides = [2, 4]
+    d = fb.make_dims(dims.D, dims.H, dims.dh, dims.F)
+    layers = _stack(dims, 2, B, 32, 2, 2, seed=90)
+    arr = fb.make_layers(layers)
+    x = to_dev_bf16(synth.token_map(1, B, 4, 4, dims.D))
+    y = torch.zeros((B, 16, dims.D), dtype=torch.bfloat16, device=DEV)
+    tmp = torch.zeros_like(y)
+    idx = torch.zeros((B, 8), dtype=torch.int32, device=DEV)
+    ws = empty_ws(fb.fastvar_step_workspace_bytes(d, B, 16, 16))
+
+    def call(**over):
+        a = dict(x=x, sched_h=sides, sched_w=sides, step=1, cache_step=0, B=B, k=8, dims=d, layers=arr, kv_len=4,
+                 L_cap=32, y_out=y, tmp=tmp, idx_out=idx, ws=ws)
+        a.update(over)
+        try:
+            fb.fastvar_scale_step(**a)
+        except fb.FastvarError as e:
+            return e.code
+        return 0
+
+    assert call(tmp=None) == fb.FASTVAR_EINVAL                 # two blocks need the scratch map
+    assert call(y_out=x) == fb.FASTVAR_EINVAL
+    assert call(step=0, cache_step=0, k=3) == fb.FASTVAR_EINVAL   # structure steps are unpruned
+    assert call(idx_out=None) == fb.FASTVAR_EINVAL
+    assert call(kv_len=30) == fb.FASTVAR_ECAPACITY
+    assert call(ws=empty_ws(256)) == fb.FASTVAR_EWORKSPACE
+    torch.cuda.synchronize()
+    assert torch.all(y == 0) and torch.all(tmp == 0)

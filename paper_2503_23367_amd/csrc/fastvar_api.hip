@@ -111,9 +111,10 @@ int launch_status() { return hipGetLastError() == hipSuccess ? FASTVAR_OK : FAST
 
 // Attention half of the block on the kept tokens: h1 = x[idx] + proj(attn(LN1(x[idx]))).
 // Scratch used: a, q, rows of the block plan.
+// `scatter`: h1_out is a [B, N, D] map and row m goes to the kept token's own row of it.
 void enqueue_attn(const void* x, int N, const int32_t* idx, int B, int k, const fastvar_dims* d,
                   const fastvar_block_weights* w, void* kc, void* vc, int L0, int L_cap, void* h1_out, void* ws,
-                  hipStream_t st) {
+                  hipStream_t st, bool scatter = false) {
     const BlockPlan bp = block_plan(d, B, k);
     char* base = static_cast<char*>(ws);
     void* buf_a = base + bp.off_a;
@@ -142,13 +143,16 @@ void enqueue_attn(const void* x, int N, const int32_t* idx, int B, int k, const 
     fv::GemmArgs pj{};
     pj.A = buf_a; pj.W = w->w_proj; pj.bias = w->b_proj; pj.M = M; pj.N = d->D; pj.K = d->D;
     pj.out = h1_out; pj.residual = x; pj.res_rows = idx ? rows : nullptr; pj.k_tokens = k;
+    pj.out_rows = (scatter && idx) ? rows : nullptr;
     fv::launch_gemm(fv::EPI_BIAS_RES, pj, st);
 }
 
 // MLP half: y = s + fc2(gelu(fc1(LN2(s)))), where s = src[idx] (rows gathered from a [B, N, D]
 // map) or, with idx == NULL, the contiguous [B*k, D] rows at src.  Scratch used: q, u, rows.
+// `scatter_rows`: y is a [B, N, D] map and row m goes to row scatter_rows[m] of it (the absolute row of
+// the kept token, as left in the plan's row list by the gather).
 void enqueue_ffn(const void* src, int N, const int32_t* idx, int B, int k, const fastvar_dims* d,
-                 const fastvar_block_weights* w, void* y, void* ws, hipStream_t st) {
+                 const fastvar_block_weights* w, void* y, void* ws, hipStream_t st, bool scatter = false) {
     const BlockPlan bp = block_plan(d, B, k);
     char* base = static_cast<char*>(ws);
     void* buf_q = base + bp.off_q;
@@ -170,15 +174,18 @@ void enqueue_ffn(const void* src, int N, const int32_t* idx, int B, int k, const
     fv::GemmArgs f2{};
     f2.A = buf_u; f2.W = w->w_fc2; f2.bias = w->b_fc2; f2.M = M; f2.N = d->D; f2.K = d->F;
     f2.out = y; f2.residual = src; f2.res_rows = idx ? rows : nullptr; f2.k_tokens = k;
+    f2.out_rows = scatter ? rows : nullptr;
     fv::launch_gemm(fv::EPI_BIAS_RES, f2, st);
 }
 
+// `scatter`: y is the [B, N, D] output map and the kept tokens' outputs go straight to their own rows
+// (the row list written by the gather of the attention half is still in the plan when FC2 runs).
 void enqueue_block(const void* x, int N, const int32_t* idx, int B, int k, const fastvar_dims* d,
                    const fastvar_block_weights* w, void* kc, void* vc, int L0, int L_cap, void* y, void* ws,
-                   hipStream_t st) {
+                   hipStream_t st, bool scatter = false) {
     void* buf_h1 = static_cast<char*>(ws) + block_plan(d, B, k).off_h1;
     enqueue_attn(x, N, idx, B, k, d, w, kc, vc, L0, L_cap, buf_h1, ws, st);
-    enqueue_ffn(buf_h1, 0, nullptr, B, k, d, w, y, ws, st);
+    enqueue_ffn(buf_h1, 0, nullptr, B, k, d, w, y, ws, st, scatter && idx);
 }
 
 int check_ffn(const void* x, int N, const int32_t* idx, int B, int k, const fastvar_dims* dims,
@@ -309,8 +316,8 @@ int fastvar_step(const void* x, const int32_t* sched_h, const int32_t* sched_w, 
     int32_t* rank = reinterpret_cast<int32_t*>(base + sel_bytes);
     char* ws_blk = base + sel_bytes + rank_bytes;
     const size_t blk_bytes = ws_bytes - sel_bytes - rank_bytes;
-    // The kept outputs go to the block's query buffer: it is last read by FC1
-    // (as the LN2 output), before FC2 writes the block output.
+    // Stand-in for a kept-output buffer in the argument checks below (the block's last GEMM writes the
+    // kept rows of y_out directly).
     void* yk = k > 0 ? static_cast<void*>(ws_blk + block_plan(dims, B, k).off_q) : nullptr;
 
     rc = check_select(x, B, h, w, D, k, idx_out, ws_sel, sel_bytes);
@@ -322,9 +329,10 @@ int fastvar_step(const void* x, const int32_t* sched_h, const int32_t* sched_w, 
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     fv::launch_select(x, B, N, D, k, idx_out, rank, nullptr, ws_sel, fv::select_plan(B, N, D), st);
+    // The block's last GEMM writes the kept rows of y_out itself; restoration fills the others.
     if (k > 0)
-        enqueue_block(x, N, idx_out, B, k, dims, weights, k_cache, v_cache, L0, L_cap, yk, ws_blk, st);
-    fv::launch_restore(yk, rank, B, k, cache_map, hc, wc, h, w, D, y_out, st);
+        enqueue_block(x, N, idx_out, B, k, dims, weights, k_cache, v_cache, L0, L_cap, y_out, ws_blk, st, true);
+    fv::launch_restore(nullptr, rank, B, k, cache_map, hc, wc, h, w, D, y_out, st);
     rc = launch_status();
     if (rc == FASTVAR_OK) *kv_len = L0 + k;
     return rc;
@@ -403,9 +411,9 @@ int fastvar_scale_step(const void* x, const int32_t* sched_h, const int32_t* sch
         } else {
             fv::launch_select(src, B, N, D, k, idx_out, rank, nullptr, ws_sel, sp, st);
             if (k > 0)
-                enqueue_block(src, N, idx_out, B, k, dims, ly.weights, ly.k_cache, ly.v_cache, L0, L_cap, yk, ws_blk,
-                              st);
-            fv::launch_restore(yk, rank, B, k, ly.cache_map, hc, wc, h, w, D, dst, st);
+                enqueue_block(src, N, idx_out, B, k, dims, ly.weights, ly.k_cache, ly.v_cache, L0, L_cap, dst, ws_blk,
+                              st, true);
+            fv::launch_restore(nullptr, rank, B, k, ly.cache_map, hc, wc, h, w, D, dst, st);
         }
     }
     if (capture &&
@@ -498,11 +506,11 @@ int fastvar_step_sublayer(const void* x, const int32_t* sched_h, const int32_t* 
     const fv::SelectPlan sp = fv::select_plan(B, N, D);
     fv::launch_select(x, B, N, D, k_attn, idx_attn_out, rank, nullptr, ws_sel, sp, st);
     if (k_attn > 0)
-        enqueue_attn(x, N, idx_attn_out, B, k_attn, dims, weights, k_cache, v_cache, L0, L_cap, hk, ws_blk, st);
-    fv::launch_restore(hk, rank, B, k_attn, cache_map_attn, hc, wc, h, w, D, x_mid, st);
+        enqueue_attn(x, N, idx_attn_out, B, k_attn, dims, weights, k_cache, v_cache, L0, L_cap, x_mid, ws_blk, st, true);
+    fv::launch_restore(nullptr, rank, B, k_attn, cache_map_attn, hc, wc, h, w, D, x_mid, st);
     fv::launch_select(x_mid, B, N, D, k_ffn, idx_ffn_out, rank, nullptr, ws_sel, sp, st);
-    if (k_ffn > 0) enqueue_ffn(x_mid, N, idx_ffn_out, B, k_ffn, dims, weights, yk, ws_blk, st);
-    fv::launch_restore(yk, rank, B, k_ffn, cache_map_ffn, hc, wc, h, w, D, y_out, st);
+    if (k_ffn > 0) enqueue_ffn(x_mid, N, idx_ffn_out, B, k_ffn, dims, weights, y_out, ws_blk, st, true);
+    fv::launch_restore(nullptr, rank, B, k_ffn, cache_map_ffn, hc, wc, h, w, D, y_out, st);
     rc = launch_status();
     if (rc == FASTVAR_OK) *kv_len = L0 + k_attn;
     return rc;

@@ -43,6 +43,7 @@ struct GemmParams {
     bf16_t* out;
     const bf16_t* residual;
     const int32_t* res_rows;  // optional row gather for the residual: row of output row m is res_rows[m]
+    const int32_t* out_rows;  // optional row scatter of the output (EPI_BIAS_RES): row m goes to row out_rows[m]
     bf16_t* q_out;
     bf16_t* k_cache;
     bf16_t* v_cache;
@@ -427,7 +428,7 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
                 if (EPI == EPI_QKV)
                     dst = cd.ptr + (long)bq * cd.batch_stride + (long)tq * cd.row_stride;
                 else
-                    dst = p.out + (size_t)m * p.N + ncol;
+                    dst = p.out + (EPI == EPI_BIAS_RES && p.out_rows ? (size_t)p.out_rows[m] : (size_t)m) * p.N + ncol;
                 *reinterpret_cast<u32x4_t*>(dst) = o;
             }
             if (EPI == EPI_QKV) {
@@ -541,6 +542,7 @@ void launch_gemm(GemmEpilogue epi, const GemmArgs& a, hipStream_t stream) {
     p.out = static_cast<bf16_t*>(a.out);
     p.residual = static_cast<const bf16_t*>(a.residual);
     p.res_rows = a.res_rows;
+    p.out_rows = a.out_rows;
     p.q_out = static_cast<bf16_t*>(a.q_out);
     p.k_cache = static_cast<bf16_t*>(a.k_cache);
     p.v_cache = static_cast<bf16_t*>(a.v_cache);

@@ -53,6 +53,7 @@ struct GemmArgs {
     void* out;             // [M, N] bf16
     const void* residual;  // [M, N] bf16 (EPI_BIAS_RES), or the gather source when res_idx is set
     const int32_t* res_rows = nullptr;  // optional: the residual of output row m is row res_rows[m] of `residual`
+    const int32_t* out_rows = nullptr;  // optional (EPI_BIAS_RES): output row m is written to row out_rows[m] of `out`
     // EPI_QKV
     void* q_out;    // [M, D]
     void* k_cache;  // [B, H, L_cap, dh]

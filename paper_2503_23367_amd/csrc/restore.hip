@@ -61,6 +61,7 @@ __global__ __launch_bounds__(256) void restore_kernel(const bf16_t* __restrict__
         const int r = (k > 0) ? rank[(size_t)b * N + n] : -1;
         bf16_t* dst = y_out + ((size_t)b * N + n) * D;
         if (r >= 0) {
+            if (!y_kept) continue;   // the kept rows are already in place (written by the block's last GEMM)
             const bf16_t* src = y_kept + ((size_t)b * k + r) * D;
             for (int g = 0; g < groups; ++g) {
                 const int col = g * 512 + lane * 8;

@@ -1048,17 +1048,21 @@ void launch_attention(const AttnArgs& a, hipStream_t stream) {
     p.H = a.H; p.k_tokens = a.k_tokens; p.L = a.L; p.L_cap = a.L_cap; p.D = a.H * a.dh;
     p.scale_log2e = a.scale * 1.4426950408889634f;
     // Head dim 128 and more than two key tiles: the software-pipelined kernel (64 queries per wave),
-    // with 256-query workgroups when those still fill the chip, else 128-query workgroups that split
-    // each tile's keys between two waves per query group.  Otherwise one wave per 32 queries, two
-    // waves per SIMD: with enough queries two 4-wave workgroups share a CU; with fewer an 8-wave
-    // workgroup splits the keys of each tile between two waves per query group.
+    // with 128-query workgroups (two query groups x two key slices) or 256-query workgroups (four query
+    // groups), whichever needs less time for its rounds of workgroups; with fewer than 128 workgroups
+    // of 128 queries, 64-query workgroups of the plain kernel (one wave per 32 queries, keys split in two).
+    // Otherwise one wave per 32 queries, two waves per SIMD: with enough queries two 4-wave workgroups
+    // share a CU; with fewer an 8-wave workgroup splits the keys of each tile between two waves per
+    // query group.
     const long waves = (long)((a.k_tokens + 31) / 32) * a.H * a.B;
     const long wg256 = (long)((a.k_tokens + 255) / 256) * a.H * a.B;
     const long wg128 = (long)((a.k_tokens + 127) / 128) * a.H * a.B;
     int cfg = waves >= 1800 ? 2 : 4;
     if (a.dh == 128 && a.L > 256) {
-        if (wg256 >= 200) cfg = 6;
-        else if (wg128 >= 128) cfg = 5;
+        // rounds of workgroups on 256 CUs; a 256-query workgroup does twice the work about 7 % faster
+        const long rounds128 = (wg128 + 255) / 256, rounds256 = (wg256 + 255) / 256;
+        if (wg128 < 128) cfg = 3;   // too few queries for half the chip: 64-query workgroups, keys split in two
+        else cfg = 1.86 * (double)rounds256 < (double)rounds128 ? 6 : 5;
     }
     if (attn_cfg_override() >= 0) cfg = attn_cfg_override();
     // the software-pipelined kernel needs head dim 128 and at least three key tiles

@@ -505,19 +505,27 @@ void launch_epi(GemmParams& p, hipStream_t stream) {
     //    extra address state; the others 256x256, with eight waves of 128x64 when there is a single
     //    round of tiles (two waves per SIMD cover each other's waits and halve the epilogue's issue
     //    time) and four waves of 128x128 when there are several rounds.
-    //  * otherwise 128x128 tiles.  At most one tile per CU: three 64-wide K stages
-    //    (one workgroup per CU, LDS is free); up to two per CU: four 32-wide stages;
-    //    more: two 64-wide stages, several workgroups per CU.
+    //    Both need (almost) every CU to get a tile and the last round of tiles to be at least 80 % full.
+    //  * otherwise 128x128 tiles: three 64-wide K stages with one workgroup per CU, or two stages with
+    //    two per CU, whichever leaves fewer tile slots idle in its last round.  Shapes that give fewer
+    //    than 128 such tiles (few rows: pruned steps of the mid-size scales, high pruning ratios) use
+    //    128x64 tiles, fewer than 64 use 64x64 tiles: more workgroups streaming the weights beat the
+    //    better operand reuse of the larger tile.
     const long tiles256 = (long)((p.M + 255) / 256) * ((p.N + 255) / 256);
     const long tiles192 = (long)((p.M + 255) / 256) * ((p.N + 191) / 192);
     const long tiles128 = (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
+    // fraction of the chip's tile slots that do useful work when `tiles` tiles run `slots` at a time
+    auto fill = [](long tiles, long slots) { return (double)tiles / (double)(((tiles + slots - 1) / slots) * slots); };
+    const long big = EPI == EPI_QKV ? tiles192 : tiles256;
     int cfg;
-    if (EPI == EPI_QKV && tiles192 >= 192)
-        cfg = 12;
-    else if (EPI != EPI_QKV && tiles256 >= 192)
-        cfg = tiles256 <= 256 ? 11 : 1;
-    else
-        cfg = tiles128 <= 256 ? 7 : (tiles128 <= 512 ? 3 : 6);
+    if (big >= 192 && fill(big, 256) >= 0.8)
+        cfg = EPI == EPI_QKV ? 12 : (tiles256 <= 256 ? 11 : 1);
+    else if (tiles128 <= 64)
+        cfg = 16;
+    else if (tiles128 <= 128)
+        cfg = 17;
+    else   // one three-stage workgroup per CU, or two two-stage ones (about 8 % faster per tile when both fill)
+        cfg = 1.08 * fill(tiles128, 512) >= fill(tiles128, 256) ? 6 : 7;
     if (gemm_cfg_override(EPI) >= 0) cfg = gemm_cfg_override(EPI);
     switch (cfg) {
         case 1: launch_cfg<256, 256, 64, 2, 2, 2, 1, EPI>(p, stream); break;
@@ -527,6 +535,9 @@ void launch_epi(GemmParams& p, hipStream_t stream) {
         case 10: launch_cfg<128, 128, 64, 4, 2, 2, 2, EPI>(p, stream); break;
         case 11: launch_cfg<256, 256, 64, 2, 2, 4, 1, EPI>(p, stream); break;
         case 12: launch_cfg<256, 192, 64, 2, 4, 2, 1, EPI>(p, stream); break;
+        case 15: launch_cfg<64, 128, 64, 3, 2, 2, 1, EPI>(p, stream); break;
+        case 16: launch_cfg<64, 64, 64, 4, 2, 2, 1, EPI>(p, stream); break;
+        case 17: launch_cfg<128, 64, 64, 3, 2, 2, 1, EPI>(p, stream); break;
         default: launch_cfg<128, 128, 64, 2, 2, 2, 1, EPI>(p, stream); break;
     }
 }

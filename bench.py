@@ -112,18 +112,22 @@ def run_step(wl, st):
     """One pass of the stack at this scale: the output map of a block is the next block's input."""
     from paper_2503_23367_amd import binding as fb
     st["xa"].copy_(st["x_in"])          # same starting map every step (outside the kernels' work)
-    src, dst = st["xa"], st["xb"]
     sides = list(wl.sides)
-    for blk in st["blocks"]:
-        if st["wiring"] == "sublayer":
+    if st["wiring"] == "sublayer":
+        src, dst = st["xa"], st["xb"]
+        for blk in st["blocks"]:
             fb.fastvar_step_sublayer(src, sides, sides, wl.step, wl.cache_step, wl.B, wl.k, wl.k, st["d"],
                                      blk["w"], blk["kc"], blk["vc"], wl.L0_full, st["L_cap"], blk["cache_attn"],
                                      blk["cache"], st["x_mid"], dst, st["idx"], st["idx2"], st["ws"])
-        else:
-            fb.fastvar_step(src, sides, sides, wl.step, wl.cache_step, wl.B, wl.k, st["d"], blk["w"],
-                            blk["kc"], blk["vc"], wl.L0_full, st["L_cap"], blk["cache"], dst, st["idx"], st["ws"])
-        src, dst = dst, src
-    return src
+            src, dst = dst, src
+        return src
+    # the whole stack in one call: every block's caches start at the same prior length
+    if "layers" not in st:
+        st["layers"] = fb.make_layers(st["blocks"])
+        st["tmp"] = st["xa"].new_empty(st["xa"].shape)
+    fb.fastvar_scale_step(st["xa"], sides, sides, wl.step, wl.cache_step, wl.B, wl.k, st["d"], st["layers"],
+                          wl.L0_full, st["L_cap"], st["xb"], st["tmp"], st["idx"], st["ws"])
+    return st["xb"]
 
 
 def time_kernel(fn, iters):

@@ -409,11 +409,15 @@ int fastvar_scale_step(const void* x, const int32_t* sched_h, const int32_t* sch
         if (dense) {
             enqueue_block(src, N, nullptr, B, k, dims, ly.weights, ly.k_cache, ly.v_cache, L0, L_cap, dst, ws_blk, st);
         } else {
-            fv::launch_select(src, B, N, D, k, idx_out, rank, nullptr, ws_sel, sp, st);
+            // the restoration of the layer before left the column-sum partials of its output here
+            fv::launch_select(src, B, N, D, k, idx_out, rank, nullptr, ws_sel, sp, st, l > 0);
             if (k > 0)
                 enqueue_block(src, N, idx_out, B, k, dims, ly.weights, ly.k_cache, ly.v_cache, L0, L_cap, dst, ws_blk,
                               st, true);
-            fv::launch_restore(nullptr, rank, B, k, ly.cache_map, hc, wc, h, w, D, dst, st);
+            if (l + 1 < n_layers)
+                fv::launch_restore_colsum(nullptr, rank, B, k, ly.cache_map, hc, wc, h, w, D, dst, ws_sel, sp, st);
+            else
+                fv::launch_restore(nullptr, rank, B, k, ly.cache_map, hc, wc, h, w, D, dst, st);
         }
     }
     if (capture &&
@@ -507,8 +511,9 @@ int fastvar_step_sublayer(const void* x, const int32_t* sched_h, const int32_t* 
     fv::launch_select(x, B, N, D, k_attn, idx_attn_out, rank, nullptr, ws_sel, sp, st);
     if (k_attn > 0)
         enqueue_attn(x, N, idx_attn_out, B, k_attn, dims, weights, k_cache, v_cache, L0, L_cap, x_mid, ws_blk, st, true);
-    fv::launch_restore(nullptr, rank, B, k_attn, cache_map_attn, hc, wc, h, w, D, x_mid, st);
-    fv::launch_select(x_mid, B, N, D, k_ffn, idx_ffn_out, rank, nullptr, ws_sel, sp, st);
+    // the first restoration also leaves the column-sum partials of x_mid for the second selection
+    fv::launch_restore_colsum(nullptr, rank, B, k_attn, cache_map_attn, hc, wc, h, w, D, x_mid, ws_sel, sp, st);
+    fv::launch_select(x_mid, B, N, D, k_ffn, idx_ffn_out, rank, nullptr, ws_sel, sp, st, true);
     if (k_ffn > 0) enqueue_ffn(x_mid, N, idx_ffn_out, B, k_ffn, dims, weights, y_out, ws_blk, st, true);
     fv::launch_restore(nullptr, rank, B, k_ffn, cache_map_ffn, hc, wc, h, w, D, y_out, st);
     rc = launch_status();

@@ -20,13 +20,23 @@ struct SelectPlan {
     size_t bytes;
 };
 SelectPlan select_plan(int B, int N, int D);
+// partials_ready: the chunk partials of the column sums are already in the scratch (left there by
+// launch_restore_colsum for this very map), so the first pass over x is skipped.
 void launch_select(const void* x, int B, int N, int D, int k, int32_t* idx, int32_t* rank,
-                   float* score_out, void* ws, const SelectPlan& plan, hipStream_t stream);
+                   float* score_out, void* ws, const SelectPlan& plan, hipStream_t stream,
+                   bool partials_ready = false);
 
 // ---- restoration (Sec. 3.3, Eq. 6) ----
 void launch_rank_from_idx(const int32_t* idx, int32_t* rank, int B, int N, int k, hipStream_t stream);
 void launch_restore(const void* y_kept, const int32_t* rank, int B, int k, const void* cache_map,
                     int hc, int wc, int h, int w, int D, void* y_out, hipStream_t stream);
+// Restoration that also leaves, in the selection scratch `select_ws` laid out by `plan`, the fp64
+// column-sum partials of the map it writes: exactly what the first pass of a selection on y_out
+// would compute (same chunks, same order of additions), so that the selection of the next layer can
+// start from them.
+void launch_restore_colsum(const void* y_kept, const int32_t* rank, int B, int k, const void* cache_map,
+                           int hc, int wc, int h, int w, int D, void* y_out, void* select_ws,
+                           const SelectPlan& plan, hipStream_t stream);
 
 // ---- block pieces ----
 // xk = x[idx] (optional copy out) and a = LayerNorm(xk); one wave per row.

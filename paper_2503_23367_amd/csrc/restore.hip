@@ -101,6 +101,94 @@ __global__ __launch_bounds__(256) void restore_kernel(const bf16_t* __restrict__
     }
 }
 
+// Restoration fused with the column sums the next selection starts with.  Same geometry as the
+// selection's own first pass: grid (column tiles of 512, row chunks, B), block 256; wave w of a block
+// takes rows r0+w, r0+w+4, ... of its chunk, lane l eight columns, and adds the bf16 values it
+// writes (or, for kept rows that are already in place, reads) to fp64 sums in ascending row order;
+// the four waves are combined through LDS in the same fixed order.  The partials are therefore bit
+// for bit what that pass would compute from y_out.
+constexpr int kColsPerTile = 512;
+constexpr int kRedStride = 72;
+
+__device__ __forceinline__ void add8d(double (&acc)[8], const uint4& v) {
+    acc[0] += (double)bf16_lo(v.x);
+    acc[1] += (double)bf16_hi(v.x);
+    acc[2] += (double)bf16_lo(v.y);
+    acc[3] += (double)bf16_hi(v.y);
+    acc[4] += (double)bf16_lo(v.z);
+    acc[5] += (double)bf16_hi(v.z);
+    acc[6] += (double)bf16_lo(v.w);
+    acc[7] += (double)bf16_hi(v.w);
+}
+
+__global__ __launch_bounds__(256) void restore_colsum_kernel(const bf16_t* __restrict__ y_kept,
+                                                             const int32_t* __restrict__ rank, int k,
+                                                             const bf16_t* __restrict__ cache_map, int hc, int wc,
+                                                             int h, int w, int D, bf16_t* y_out,
+                                                             double* __restrict__ partial, int rows_per_chunk,
+                                                             int n_chunks) {
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int col = blockIdx.x * kColsPerTile + lane * 8;
+    const int b = blockIdx.z;
+    const int N = h * w;
+    const int r0 = blockIdx.y * rows_per_chunk;
+    const int r1 = min(r0 + rows_per_chunk, N);
+
+    double acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = 0.0;
+
+    if (col < D) {
+        const bf16_t* cb = cache_map + (size_t)b * hc * wc * D + col;
+        for (int n = r0 + wave; n < r1; n += 4) {
+            const int r = (k > 0) ? rank[(size_t)b * N + n] : -1;
+            bf16_t* dst = y_out + ((size_t)b * N + n) * D + col;
+            uint4 o;
+            if (r >= 0) {
+                if (y_kept) {
+                    o = *reinterpret_cast<const uint4*>(y_kept + ((size_t)b * k + r) * D + col);
+                    *reinterpret_cast<uint4*>(dst) = o;
+                } else {
+                    o = *reinterpret_cast<const uint4*>(dst);   // written by the block's last GEMM
+                }
+            } else {
+                int i0, i1, j0, j1;
+                float lr, lc;
+                axis_taps(n / w, hc, h, i0, i1, lr);
+                axis_taps(n % w, wc, w, j0, j1, lc);
+                const uint4 a = *reinterpret_cast<const uint4*>(cb + ((size_t)i0 * wc + j0) * D);
+                const uint4 bq = *reinterpret_cast<const uint4*>(cb + ((size_t)i0 * wc + j1) * D);
+                const uint4 c = *reinterpret_cast<const uint4*>(cb + ((size_t)i1 * wc + j0) * D);
+                const uint4 d = *reinterpret_cast<const uint4*>(cb + ((size_t)i1 * wc + j1) * D);
+                o.x = pack_bf16x2(lerp2(bf16_lo(a.x), bf16_lo(bq.x), bf16_lo(c.x), bf16_lo(d.x), lr, lc),
+                                  lerp2(bf16_hi(a.x), bf16_hi(bq.x), bf16_hi(c.x), bf16_hi(d.x), lr, lc));
+                o.y = pack_bf16x2(lerp2(bf16_lo(a.y), bf16_lo(bq.y), bf16_lo(c.y), bf16_lo(d.y), lr, lc),
+                                  lerp2(bf16_hi(a.y), bf16_hi(bq.y), bf16_hi(c.y), bf16_hi(d.y), lr, lc));
+                o.z = pack_bf16x2(lerp2(bf16_lo(a.z), bf16_lo(bq.z), bf16_lo(c.z), bf16_lo(d.z), lr, lc),
+                                  lerp2(bf16_hi(a.z), bf16_hi(bq.z), bf16_hi(c.z), bf16_hi(d.z), lr, lc));
+                o.w = pack_bf16x2(lerp2(bf16_lo(a.w), bf16_lo(bq.w), bf16_lo(c.w), bf16_lo(d.w), lr, lc),
+                                  lerp2(bf16_hi(a.w), bf16_hi(bq.w), bf16_hi(c.w), bf16_hi(d.w), lr, lc));
+                *reinterpret_cast<uint4*>(dst) = o;
+            }
+            add8d(acc, o);
+        }
+    }
+
+    __shared__ double red[4][8 * kRedStride];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) red[wave][j * kRedStride + lane] = acc[j];
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int cl = threadIdx.x + e * 256;  // column inside the tile
+        const int at = (cl & 7) * kRedStride + (cl >> 3);
+        const double s = ((red[0][at] + red[1][at]) + red[2][at]) + red[3][at];
+        const int c = blockIdx.x * kColsPerTile + cl;
+        if (c < D) partial[((size_t)b * n_chunks + blockIdx.y) * D + c] = s;
+    }
+}
+
 }  // namespace
 
 void launch_rank_from_idx(const int32_t* idx, int32_t* rank, int B, int N, int k, hipStream_t stream) {
@@ -114,6 +202,15 @@ void launch_restore(const void* y_kept, const int32_t* rank, int B, int k, const
     restore_kernel<<<dim3((N + rows_per_block - 1) / rows_per_block, B), 256, 0, stream>>>(
         static_cast<const bf16_t*>(y_kept), rank, k, static_cast<const bf16_t*>(cache_map), hc, wc, h, w, D,
         static_cast<bf16_t*>(y_out));
+}
+
+void launch_restore_colsum(const void* y_kept, const int32_t* rank, int B, int k, const void* cache_map, int hc,
+                           int wc, int h, int w, int D, void* y_out, void* select_ws, const SelectPlan& plan,
+                           hipStream_t stream) {
+    double* partial = reinterpret_cast<double*>(static_cast<char*>(select_ws) + plan.off_partial);
+    restore_colsum_kernel<<<dim3(plan.col_tiles, plan.n_chunks, B), 256, 0, stream>>>(
+        static_cast<const bf16_t*>(y_kept), rank, k, static_cast<const bf16_t*>(cache_map), hc, wc, h, w, D,
+        static_cast<bf16_t*>(y_out), partial, plan.rows_per_chunk, plan.n_chunks);
 }
 
 }  // namespace fv

@@ -176,6 +176,56 @@ def test_stack_equals_the_single_block_entry_points(n_layers):
                 assert torch.equal(la["cache"].view(torch.int16), lb["cache"].view(torch.int16))
 
 
+def test_stack_equals_single_block_calls_at_the_headline_size():
+    """Two blocks of the headline step through fastvar_scale_step (where the restoration of a block leaves the
+    column sums for the next block's selection) against two fastvar_step calls: same bits."""
+    wl = synth.WORKLOADS[synth.HEADLINE]
+    dims, B, N, k = wl.dims, 1, wl.N, wl.k
+    print(f"[stack] headline size, 2 blocks, N={N} k={k}", flush=True)
+    L0, L_cap = wl.L0_full, 8480
+    d = fb.make_dims(dims.D, dims.H, dims.dh, dims.F)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(5)
+
+    def rn(shape, std=1.0, mean=0.0):
+        return (torch.randn(shape, generator=gen, device=DEV) * std + mean).to(torch.bfloat16)
+
+    def make():
+        out = []
+        g2 = torch.Generator(device=DEV)
+        g2.manual_seed(9)
+        r = lambda shape, std=1.0, mean=0.0: (torch.randn(shape, generator=g2, device=DEV) * std + mean).to(torch.bfloat16)
+        D, F = dims.D, dims.F
+        for _ in range(2):
+            wt = dict(ln1_g=r((D,), 0.02, 1.0), ln1_b=r((D,), 0.02), w_qkv=r((3 * D, D), 0.02), b_qkv=r((3 * D,), 0.02),
+                      w_proj=r((D, D), 0.02), b_proj=r((D,), 0.02), ln2_g=r((D,), 0.02, 1.0), ln2_b=r((D,), 0.02),
+                      w_fc1=r((F, D), 0.02), b_fc1=r((F,), 0.02), w_fc2=r((D, F), 0.02), b_fc2=r((D,), 0.02))
+            kc = torch.zeros((B, dims.H, L_cap, dims.dh), dtype=torch.bfloat16, device=DEV)
+            vc = torch.zeros((B, dims.H, dims.dh, L_cap), dtype=torch.bfloat16, device=DEV)
+            kc[:, :, :L0] = r((B, dims.H, L0, dims.dh))
+            vc[:, :, :, :L0] = r((B, dims.H, dims.dh, L0))
+            out.append(dict(wt=wt, w=fb.make_weights(wt), kc=kc, vc=vc, cache=r((B, wl.hc * wl.hc, D))))
+        return out
+
+    x = to_dev_bf16(synth.token_map(5, B, wl.h, wl.h, dims.D))
+    sides = list(wl.sides)
+    ws = empty_ws(fb.fastvar_step_workspace_bytes(d, B, N, k))
+    A, S = make(), make()
+    ya, tmp = torch.empty_like(x), torch.empty_like(x)
+    ia = torch.zeros((B, k), dtype=torch.int32, device=DEV)
+    fb.fastvar_scale_step(x, sides, sides, wl.step, wl.cache_step, B, k, d, fb.make_layers(A), L0, L_cap, ya, tmp, ia, ws)
+    cur = x
+    for ly in S:
+        out = torch.empty_like(x)
+        ib = torch.zeros((B, k), dtype=torch.int32, device=DEV)
+        fb.fastvar_step(cur, sides, sides, wl.step, wl.cache_step, B, k, d, ly["w"], ly["kc"], ly["vc"], L0, L_cap,
+                        ly["cache"], out, ib, ws)
+        cur = out
+    torch.cuda.synchronize()
+    assert torch.equal(ia, ib)
+    assert torch.equal(ya.view(torch.int16), cur.view(torch.int16))
+
+
 def test_scale_step_argument_errors():
     print("[scale step] error paths", flush=True)
     dims, B = TINY64, 1

@@ -240,6 +240,36 @@ int fastvar_scale_step(const void* x, const int32_t* sched_h /* host */, const i
                        void* y_out, void* tmp, int32_t* idx_out,
                        void* ws, size_t ws_bytes, void* stream);
 
+/* Stages of a block inside the step entry points, for fastvar_scale_step_timed. */
+enum {
+    FASTVAR_STAGE_SELECT = 0,    /* column sums, scores, top-k */
+    FASTVAR_STAGE_LN1 = 1,       /* gather + LayerNorm 1 */
+    FASTVAR_STAGE_QKV = 2,       /* QKV GEMM + cache append */
+    FASTVAR_STAGE_ATTENTION = 3,
+    FASTVAR_STAGE_PROJ = 4,      /* output projection + residual */
+    FASTVAR_STAGE_LN2 = 5,
+    FASTVAR_STAGE_FC1 = 6,       /* FC1 + GELU */
+    FASTVAR_STAGE_FC2 = 7,       /* FC2 + residual */
+    FASTVAR_STAGE_RESTORE = 8,
+    FASTVAR_N_STAGES = 9
+};
+
+/*
+ * fastvar_scale_step with a stopwatch: a measurement aid for callers that want the time of each
+ * stage inside the running step (the benchmark's roofline figures).  Same arguments and effect;
+ * in addition an event is recorded on `stream` after every stage, the call WAITS for the stream
+ * to finish (unlike every other entry point) and writes to stage_ms[FASTVAR_N_STAGES] (host) the
+ * time of each stage in milliseconds, averaged over the n_layers blocks (at most 256).  Stages that
+ * did not run (selection and restoration in structure steps) read 0.  It creates and destroys
+ * HIP events.
+ */
+int fastvar_scale_step_timed(const void* x, const int32_t* sched_h /* host */, const int32_t* sched_w /* host */,
+                             int K, int step, int cache_step, int B, int k,
+                             const fastvar_dims* dims /* host */, const fastvar_layer* layers /* host */,
+                             int n_layers, int32_t* kv_len /* host in/out */, int L_cap,
+                             void* y_out, void* tmp, int32_t* idx_out,
+                             void* ws, size_t ws_bytes, void* stream, float* stage_ms /* host out */);
+
 /*
  * The two halves of the block, each on its own kept set (Fig. 2(b) and Sec. 3.3,
  * implementation paragraph: the selection / restoration pair wraps each

@@ -52,7 +52,8 @@ EXPORTS = ("fastvar_version", "fastvar_strerror", "fastvar_keep_count",
            "fastvar_select_workspace_bytes", "fastvar_block_workspace_bytes",
            "fastvar_restore_workspace_bytes", "fastvar_step_workspace_bytes",
            "fastvar_select_pivotal", "fastvar_block_forward_pruned", "fastvar_restore",
-           "fastvar_step", "fastvar_scale_step", "fastvar_step_sublayer_workspace_bytes", "fastvar_attn_forward_pruned",
+           "fastvar_step", "fastvar_scale_step", "fastvar_scale_step_timed",
+           "fastvar_step_sublayer_workspace_bytes", "fastvar_attn_forward_pruned",
            "fastvar_ffn_forward_pruned", "fastvar_step_sublayer", "fastvar_layernorm", "fastvar_gemm_bf16",
            "fastvar_qkv_gemm", "fastvar_attention")
 
@@ -96,6 +97,8 @@ def lib() -> C.CDLL:
     L.fastvar_scale_step.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), i32, i32, i32, i32, i32,
                                      C.POINTER(Dims), C.POINTER(Layer), i32, C.POINTER(C.c_int32), i32,
                                      vp, vp, vp, vp, sz, vp]
+    L.fastvar_scale_step_timed.restype = i32
+    L.fastvar_scale_step_timed.argtypes = L.fastvar_scale_step.argtypes + [C.POINTER(C.c_float)]
     L.fastvar_step_sublayer_workspace_bytes.restype = sz
     L.fastvar_step_sublayer_workspace_bytes.argtypes = [C.POINTER(Dims), i32, i32, i32, i32]
     L.fastvar_attn_forward_pruned.restype = i32
@@ -247,6 +250,25 @@ def fastvar_scale_step(x, sched_h, sched_w, step, cache_step, B, k, dims: Dims, 
                                   0 if ws is None else ws.numel() * ws.element_size(), _stream())
     _check(rc, "fastvar_scale_step")
     return kv.value
+
+
+STAGES = ("select", "gather+layernorm 1", "qkv gemm", "attention", "proj gemm", "layernorm 2", "fc1 gemm",
+          "fc2 gemm", "restore")
+
+
+def fastvar_scale_step_timed(x, sched_h, sched_w, step, cache_step, B, k, dims: Dims, layers, kv_len: int, L_cap,
+                             y_out, tmp, idx_out, ws):
+    """fastvar_scale_step that waits for the stream and returns (new cache length, {stage: ms per block})."""
+    K = len(sched_h)
+    sh = (C.c_int32 * K)(*sched_h)
+    sw = (C.c_int32 * K)(*sched_w)
+    kv = C.c_int32(kv_len)
+    ms = (C.c_float * len(STAGES))()
+    rc = lib().fastvar_scale_step_timed(_ptr(x), sh, sw, K, step, cache_step, B, k, C.byref(dims), layers,
+                                        len(layers), C.byref(kv), L_cap, _ptr(y_out), _ptr(tmp), _ptr(idx_out),
+                                        _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(), _stream(), ms)
+    _check(rc, "fastvar_scale_step_timed")
+    return kv.value, {n: float(ms[i]) for i, n in enumerate(STAGES)}
 
 
 def fastvar_step_sublayer_workspace_bytes(dims: Dims, B: int, N: int, k_attn: int, k_ffn: int) -> int:

@@ -109,6 +109,23 @@ int check_restore(const void* y_kept, const int32_t* idx, const int32_t* rank, i
 
 int launch_status() { return hipGetLastError() == hipSuccess ? FASTVAR_OK : FASTVAR_EHIP; }
 
+// Optional per-stage timing of the step entry points (fastvar_scale_step_timed): when a profile is
+// installed for the calling thread, an event is recorded on the launch stream after every stage.
+constexpr int kMaxMarks = 1 + FASTVAR_N_STAGES * 256;
+struct StepProfile {
+    hipEvent_t ev[kMaxMarks];
+    int stage[kMaxMarks];
+    int n = 0;
+};
+thread_local StepProfile* g_profile = nullptr;
+inline void mark(hipStream_t st, int stage) {
+    StepProfile* p = g_profile;
+    if (p && p->n < kMaxMarks) {
+        (void)hipEventRecord(p->ev[p->n], st);
+        p->stage[p->n++] = stage;
+    }
+}
+
 // Attention half of the block on the kept tokens: h1 = x[idx] + proj(attn(LN1(x[idx]))).
 // Scratch used: a, q, rows of the block plan.
 // `scatter`: h1_out is a [B, N, D] map and row m goes to the kept token's own row of it.
@@ -127,24 +144,28 @@ void enqueue_attn(const void* x, int N, const int32_t* idx, int B, int k, const 
         fv::launch_gather_layernorm(x, idx, B, N, k, d->D, w->ln1_g, w->ln1_b, d->ln_eps, rows, buf_a, st);
     else
         fv::launch_layernorm(x, M, d->D, w->ln1_g, w->ln1_b, d->ln_eps, buf_a, st);
+    mark(st, FASTVAR_STAGE_LN1);
     // q | k | v = a1 * Wqkv^T + b ; k, v appended to the caches at [L0, L0+k)
     fv::GemmArgs g{};
     g.A = buf_a; g.W = w->w_qkv; g.bias = w->b_qkv; g.M = M; g.N = 3 * d->D; g.K = d->D;
     g.q_out = buf_q; g.k_cache = kc; g.v_cache = vc;
     g.D = d->D; g.H = d->H; g.dh = d->dh; g.k_tokens = k; g.L0 = L0; g.L_cap = L_cap;
     fv::launch_gemm(fv::EPI_QKV, g, st);
+    mark(st, FASTVAR_STAGE_QKV);
     // o = softmax(q K^T * scale) V over cache positions [0, L0+k)
     fv::AttnArgs at{};
     at.q = buf_q; at.k_cache = kc; at.v_cache = vc; at.o = buf_a;
     at.B = B; at.H = d->H; at.dh = d->dh; at.k_tokens = k; at.L = L0 + k; at.L_cap = L_cap;
     at.scale = d->softmax_scale;
     fv::launch_attention(at, st);
+    mark(st, FASTVAR_STAGE_ATTENTION);
     // h1 = x[idx] + o * Wp^T + bp
     fv::GemmArgs pj{};
     pj.A = buf_a; pj.W = w->w_proj; pj.bias = w->b_proj; pj.M = M; pj.N = d->D; pj.K = d->D;
     pj.out = h1_out; pj.residual = x; pj.res_rows = idx ? rows : nullptr; pj.k_tokens = k;
     pj.out_rows = (scatter && idx) ? rows : nullptr;
     fv::launch_gemm(fv::EPI_BIAS_RES, pj, st);
+    mark(st, FASTVAR_STAGE_PROJ);
 }
 
 // MLP half: y = s + fc2(gelu(fc1(LN2(s)))), where s = src[idx] (rows gathered from a [B, N, D]
@@ -165,17 +186,20 @@ void enqueue_ffn(const void* src, int N, const int32_t* idx, int B, int k, const
         fv::launch_gather_layernorm(src, idx, B, N, k, d->D, w->ln2_g, w->ln2_b, d->ln_eps, rows, buf_q, st);
     else
         fv::launch_layernorm(src, M, d->D, w->ln2_g, w->ln2_b, d->ln_eps, buf_q, st);
+    mark(st, FASTVAR_STAGE_LN2);
     // u = gelu(a2 * W1^T + b1)
     fv::GemmArgs f1{};
     f1.A = buf_q; f1.W = w->w_fc1; f1.bias = w->b_fc1; f1.M = M; f1.N = d->F; f1.K = d->D;
     f1.out = buf_u; f1.k_tokens = k;
     fv::launch_gemm(fv::EPI_BIAS_GELU, f1, st);
+    mark(st, FASTVAR_STAGE_FC1);
     // y = s + u * W2^T + b2
     fv::GemmArgs f2{};
     f2.A = buf_u; f2.W = w->w_fc2; f2.bias = w->b_fc2; f2.M = M; f2.N = d->D; f2.K = d->F;
     f2.out = y; f2.residual = src; f2.res_rows = idx ? rows : nullptr; f2.k_tokens = k;
     f2.out_rows = scatter ? rows : nullptr;
     fv::launch_gemm(fv::EPI_BIAS_RES, f2, st);
+    mark(st, FASTVAR_STAGE_FC2);
 }
 
 // `scatter`: y is the [B, N, D] output map and the kept tokens' outputs go straight to their own rows
@@ -411,6 +435,7 @@ int fastvar_scale_step(const void* x, const int32_t* sched_h, const int32_t* sch
         } else {
             // the restoration of the layer before left the column-sum partials of its output here
             fv::launch_select(src, B, N, D, k, idx_out, rank, nullptr, ws_sel, sp, st, l > 0);
+            mark(st, FASTVAR_STAGE_SELECT);
             if (k > 0)
                 enqueue_block(src, N, idx_out, B, k, dims, ly.weights, ly.k_cache, ly.v_cache, L0, L_cap, dst, ws_blk,
                               st, true);
@@ -418,6 +443,7 @@ int fastvar_scale_step(const void* x, const int32_t* sched_h, const int32_t* sch
                 fv::launch_restore_colsum(nullptr, rank, B, k, ly.cache_map, hc, wc, h, w, D, dst, ws_sel, sp, st);
             else
                 fv::launch_restore(nullptr, rank, B, k, ly.cache_map, hc, wc, h, w, D, dst, st);
+            mark(st, FASTVAR_STAGE_RESTORE);
         }
     }
     if (capture &&
@@ -426,6 +452,39 @@ int fastvar_scale_step(const void* x, const int32_t* sched_h, const int32_t* sch
         return FASTVAR_EHIP;
     rc = launch_status();
     if (rc == FASTVAR_OK) *kv_len = L0 + k;
+    return rc;
+}
+
+int fastvar_scale_step_timed(const void* x, const int32_t* sched_h, const int32_t* sched_w, int K, int step,
+                             int cache_step, int B, int k, const fastvar_dims* dims, const fastvar_layer* layers,
+                             int n_layers, int32_t* kv_len, int L_cap, void* y_out, void* tmp, int32_t* idx_out,
+                             void* ws, size_t ws_bytes, void* stream, float* stage_ms) {
+    if (!stage_ms || n_layers <= 0 || n_layers > 256) return FASTVAR_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    StepProfile* prof = new StepProfile;
+    const int want = 1 + FASTVAR_N_STAGES * n_layers;
+    int made = 0;
+    for (; made < want; ++made)
+        if (hipEventCreate(&prof->ev[made]) != hipSuccess) break;
+    int rc = made == want ? FASTVAR_OK : FASTVAR_EHIP;
+    if (rc == FASTVAR_OK) {
+        g_profile = prof;
+        mark(st, -1);   // start of the step
+        rc = fastvar_scale_step(x, sched_h, sched_w, K, step, cache_step, B, k, dims, layers, n_layers, kv_len, L_cap,
+                                y_out, tmp, idx_out, ws, ws_bytes, stream);
+        g_profile = nullptr;
+        if (rc == FASTVAR_OK && hipStreamSynchronize(st) != hipSuccess) rc = FASTVAR_EHIP;
+    }
+    if (rc == FASTVAR_OK) {
+        for (int i = 0; i < FASTVAR_N_STAGES; ++i) stage_ms[i] = 0.f;
+        for (int i = 1; i < prof->n; ++i) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, prof->ev[i - 1], prof->ev[i]) != hipSuccess) { rc = FASTVAR_EHIP; break; }
+            stage_ms[prof->stage[i]] += ms / (float)n_layers;
+        }
+    }
+    for (int i = 0; i < made; ++i) (void)hipEventDestroy(prof->ev[i]);
+    delete prof;
     return rc;
 }
 

@@ -226,6 +226,42 @@ def test_stack_equals_single_block_calls_at_the_headline_size():
     assert torch.equal(ya.view(torch.int16), cur.view(torch.int16))
 
 
+def test_timed_scale_step_gives_the_same_result_and_stage_times():
+    print("[scale step] stopwatch variant", flush=True)
+    dims, B = TINY64, 2
+    sides = (2, 3, 5, 8)
+    cache_step, L_cap = 1, 128
+    hc = wc = sides[cache_step]
+    d = fb.make_dims(dims.D, dims.H, dims.dh, dims.F)
+    A = _stack(dims, 3, B, L_cap, hc, wc, seed=95)
+    T = _stack(dims, 3, B, L_cap, hc, wc, seed=95)
+    la, lt = fb.make_layers(A), fb.make_layers(T)
+    kv_a = kv_t = 0
+    for step, side in enumerate(sides):
+        N = side * side
+        k = N if step <= cache_step else fb.fastvar_keep_count(N, 0.5)
+        x = to_dev_bf16(synth.token_map(96 + step, B, side, side, dims.D))
+        ya, yt = (torch.full((B, N, dims.D), float("nan"), dtype=torch.bfloat16, device=DEV) for _ in range(2))
+        tmp = torch.empty_like(ya)
+        idx = torch.zeros((B, k), dtype=torch.int32, device=DEV)
+        ws = empty_ws(fb.fastvar_step_workspace_bytes(d, B, N, k))
+        kv_a = fb.fastvar_scale_step(x, list(sides), list(sides), step, cache_step, B, k, d, la, kv_a, L_cap, ya, tmp, idx, ws)
+        kv_t, ms = fb.fastvar_scale_step_timed(x, list(sides), list(sides), step, cache_step, B, k, d, lt, kv_t, L_cap,
+                                               yt, tmp, idx, ws)
+        # the timed call has waited for the stream: the result is there without a synchronize
+        assert kv_a == kv_t
+        assert torch.equal(ya.view(torch.int16), yt.view(torch.int16))
+        assert set(ms) == set(fb.STAGES)
+        pruned = step > cache_step
+        for name, v in ms.items():
+            if name in ("select", "restore") and not pruned:
+                assert v == 0.0
+            else:
+                assert 0.0 < v < 50.0, (name, v)
+    with pytest.raises(fb.FastvarError):
+        fb.fastvar_scale_step_timed(x, list(sides), list(sides), 3, cache_step, B, k, d, lt, 999, L_cap, yt, tmp, idx, ws)
+
+
 def test_scale_step_argument_errors():
     print("[scale step] error paths", flush=True)
     dims, B = TINY64, 1

@@ -126,8 +126,8 @@ def test_one_block_schedule_matches_oracle_step_by_step():
     assert np.all(np.abs(got - up) <= 2.0 ** -8 * 1.001 * np.abs(up) + 2e-6)
 
 
-@pytest.mark.parametrize("n_layers", [2, 3])
-def test_stack_equals_the_single_block_entry_points(n_layers):
+@pytest.mark.parametrize("n_layers,keeps", [(2, (0.45, 0.45)), (3, (0.45, 0.0)), (3, (1.0, 0.3))])
+def test_stack_equals_the_single_block_entry_points(n_layers, keeps):
     dims, B = TINY64, 2
     sides = (2, 3, 4, 6, 9)
     cache_step = 2
@@ -140,12 +140,12 @@ def test_stack_equals_the_single_block_entry_points(n_layers):
     kv_a = kv_b = 0
     for step, side in enumerate(sides):
         N = side * side
-        k = N if step <= cache_step else fb.fastvar_keep_count(N, 0.45)
+        k = N if step <= cache_step else fb.fastvar_keep_count(N, keeps[step - cache_step - 1])
         print(f"[stack] layers={n_layers} step {step} side {side} k={k}", flush=True)
         x = to_dev_bf16(synth.token_map(80 + step, B, side, side, dims.D))
         y = torch.full((B, N, dims.D), float("nan"), dtype=torch.bfloat16, device=DEV)
         tmp = torch.full_like(y, float("nan"))
-        idx = torch.zeros((B, k), dtype=torch.int32, device=DEV)
+        idx = torch.zeros((B, max(k, 1)), dtype=torch.int32, device=DEV)
         ws = empty_ws(fb.fastvar_step_workspace_bytes(d, B, N, k))
         kv_a = fb.fastvar_scale_step(x, list(sides), list(sides), step, cache_step, B, k, d, arr, kv_a, L_cap, y,
                                      tmp, idx, ws)
@@ -159,7 +159,7 @@ def test_stack_equals_the_single_block_entry_points(n_layers):
                 if step == cache_step:
                     ly["cache"] = out.clone()
             else:
-                idx_b = torch.zeros((B, k), dtype=torch.int32, device=DEV)
+                idx_b = torch.zeros((B, max(k, 1)), dtype=torch.int32, device=DEV)
                 fb.fastvar_step(cur, list(sides), list(sides), step, cache_step, B, k, d, ly["w"], ly["kc"], ly["vc"],
                                 kv_b, L_cap, ly["cache"], out, idx_b, ws)
             cur = out
@@ -167,7 +167,7 @@ def test_stack_equals_the_single_block_entry_points(n_layers):
         torch.cuda.synchronize()
         assert kv_a == kv_b
         assert torch.equal(y.view(torch.int16), cur.view(torch.int16)), step
-        if step > cache_step:
+        if step > cache_step and 0 < k < N:
             assert torch.equal(idx, idx_b)
         for la, lb in zip(A, Bk):
             assert torch.equal(la["kc"][:, :, :kv_a].view(torch.int16), lb["kc"][:, :, :kv_a].view(torch.int16))

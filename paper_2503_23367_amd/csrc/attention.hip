@@ -40,6 +40,9 @@ struct AttnParams {
     bf16_t* o;
     int H, k_tokens, L, L_cap, D;
     float scale_log2e;
+    // key-range split between workgroups (pipelined kernel instantiated with KVS)
+    int q_tiles, splits, keys_per_split;
+    float* part;   // [B][H][q_tile][split][(2*QB + DB*QB*16)][QG*64] fp32, register order
 };
 
 __device__ __forceinline__ int swap_bits_2_3(int v) {
@@ -528,7 +531,10 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
 // frees K tile kt and V^T tile kt-1, whose stages the second step refills.
 // The last tile is shifted back so that it ends at the (8-aligned) end of the cache: it never
 // reads past L_cap, its leading keys (already seen) and the up to 7 positions past L are masked.
-template <int DH, int QG, int KSPLIT>
+// KVS: the key range is also split between workgroups (consecutive query-tile ids of the grid's x
+// dimension are the same tile's splits); each works on keys [split*keys_per_split, ...) as if they
+// were the whole cache and leaves its unnormalised output and statistics for attention_merge_kernel.
+template <int DH, int QG, int KSPLIT, bool KVS = false>
 __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(const AttnParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
     constexpr int QB = 2;
@@ -563,16 +569,20 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
     int wg = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
     const int n_wg = gridDim.x * gridDim.y * gridDim.z;
     if ((n_wg & 7) == 0) wg = (wg & 7) * (n_wg >> 3) + (wg >> 3);  // XCD-aware order, as above
-    const int q_tile = wg % gridDim.x;
+    const int qx = wg % gridDim.x;
+    const int q_tile = KVS ? qx % p.q_tiles : qx;
+    const int split = KVS ? qx / p.q_tiles : 0;
     const int head = (wg / gridDim.x) % gridDim.y;
     const int b = wg / (gridDim.x * gridDim.y);
     const int q_base = q_tile * (QG * 32 * QB) + qg * (32 * QB);
+    const int key_first = KVS ? split * p.keys_per_split : 0;                 // a multiple of the key tile
+    const int L = KVS ? min(p.L - key_first, p.keys_per_split) : p.L;         // keys of this workgroup
 
-    const bf16_t* kc = p.kc + ((size_t)b * p.H + head) * p.L_cap * DH;
-    const bf16_t* vc = p.vc + ((size_t)b * p.H + head) * DH * (size_t)p.L_cap;
+    const bf16_t* kc = p.kc + (((size_t)b * p.H + head) * p.L_cap + key_first) * DH;
+    const bf16_t* vc = p.vc + ((size_t)b * p.H + head) * DH * (size_t)p.L_cap + key_first;
 
-    const int KT = (p.L + BN - 1) / BN;                 // >= 3, checked by the launcher
-    const int last_start = ((p.L + 7) & ~7) - BN;       // first key of the shifted last tile
+    const int KT = (L + BN - 1) / BN;                   // >= 3, checked by the launcher
+    const int last_start = ((L + 7) & ~7) - BN;         // first key of the shifted last tile
     const int last_first_new = (KT - 1) * BN;           // keys before this one were seen in tile KT-2
 #define FP_TILE_START(kt_) ((kt_) == KT - 1 ? last_start : (kt_) * BN)
 
@@ -610,7 +620,7 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
 #define FP_FIX_TAIL()                                                                               \
     {                                                                                               \
         u32x4_t* sv_ = lds + 2 * K_TILE + ((KT - 1) & 1) * V_TILE + wave * 64 + lane;               \
-        const int valid_ = p.L - (last_start + v_col0);                                             \
+        const int valid_ = L - (last_start + v_col0);                                             \
         if (valid_ < 8) {                                                                           \
             _Pragma("unroll") for (int j = 0; j < V_LD; ++j) {                                      \
                 u32x4_t v_ = sv_[j * (WAVES * 64)];                                                 \
@@ -724,7 +734,7 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
             /* previous step, free the old ones (the next step's first operands come from the new) */ \
             asm volatile("" ::: "memory");                                                          \
             __builtin_amdgcn_s_waitcnt(attn_waitcnt(0, true));                                      \
-            if ((MASK_) && ((p.L & 7) != 0)) FP_FIX_TAIL()                                          \
+            if ((MASK_) && ((L & 7) != 0)) FP_FIX_TAIL()                                          \
             FP_PUBLISH()                                                                            \
         }                                                                                           \
         if (f < NV_ && (DO_PV_))                                                                    \
@@ -751,7 +761,7 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
                 constexpr int qb = gg / 2 % 2;                                                      \
                 _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                    \
                     const int key_ = (key0_sm_) + swap_bits_2_3(8 * (r >> 2) + 4 * hf + (r & 3));   \
-                    if (key_ >= p.L || key_ < last_first_new) S_SM_[qb][r] = -INFINITY;             \
+                    if (key_ >= L || key_ < last_first_new) S_SM_[qb][r] = -INFINITY;             \
                 }                                                                                   \
             }                                                                                       \
             if ((RESC_) && (gg == 1 || gg == 3)) {                                                  \
@@ -973,6 +983,24 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
         }
     }
 #undef FP_PUBLISH
+    if (KVS) {
+        if (kh == 0) {
+            // partial result of this key range: statistics, then the accumulator, register-major
+            float* part = p.part + ((((size_t)b * p.H + head) * p.q_tiles + q_tile) * p.splits + split) *
+                                       (size_t)((2 * QB + DB * QB * 16) * (QG * 64)) + qg * 64 + lane;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                part[qb * (QG * 64)] = m_run[qb];
+                part[(QB + qb) * (QG * 64)] = l_run[qb] + other_half(l_run[qb]);
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        part[(2 * QB + (db * QB + qb) * 16 + r) * (QG * 64)] = acc[db][qb][r];
+            }
+        }
+        return;
+    }
     if (kh == 0) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
@@ -996,6 +1024,58 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
 #endif
 }
 
+// Merge of the key-range partials of attention_pipe_kernel<.., KVS = true>: grid (query tiles, H, B),
+// QG*64 threads; thread (qg, lane) reads, for every split, what wave (qg, key slice 0) lane `lane` left
+// (same register order), combines them exactly (O = sum_s 2^(m_s - m) O_s, l likewise), normalises and
+// stores bf16 with the pipelined kernel's own output mapping.
+template <int DH, int QG>
+__global__ __launch_bounds__(QG * 64) void attention_merge_kernel(const AttnParams p) {
+    constexpr int QB = 2, DB = DH / 32;
+    constexpr int SLOTS = 2 * QB + DB * QB * 16;
+    const int lane = threadIdx.x & 63, qg = threadIdx.x >> 6;
+    const int li = lane & 31, hf = lane >> 5;
+    const int q_tile = blockIdx.x, head = blockIdx.y, b = blockIdx.z;
+    const int q_base = q_tile * (QG * 32 * QB) + qg * (32 * QB);
+    const float* part = p.part + ((((size_t)b * p.H + head) * p.q_tiles + q_tile) * p.splits) *
+                                     (size_t)(SLOTS * (QG * 64)) + qg * 64 + lane;
+    const size_t sstride = (size_t)SLOTS * (QG * 64);
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        float m = -INFINITY;
+        for (int s = 0; s < p.splits; ++s) m = fmaxf(m, part[s * sstride + qb * (QG * 64)]);
+        float l = 0.f;
+        float o[DB * 16];
+#pragma unroll
+        for (int i = 0; i < DB * 16; ++i) o[i] = 0.f;
+        for (int s = 0; s < p.splits; ++s) {
+            const float* ps = part + s * sstride;
+            const float w = __builtin_amdgcn_exp2f(ps[qb * (QG * 64)] - m);
+            l += w * ps[(QB + qb) * (QG * 64)];
+            float v[DB * 16];
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) v[db * 16 + r] = ps[(2 * QB + (db * QB + qb) * 16 + r) * (QG * 64)];
+#pragma unroll
+            for (int i = 0; i < DB * 16; ++i) o[i] += w * v[i];
+        }
+        const float inv = 1.0f / l;
+        const int qrow = q_base + qb * 32 + li;
+        if (qrow < p.k_tokens) {
+            bf16_t* dst = p.o + ((size_t)b * p.k_tokens + qrow) * p.D + head * DH + 4 * hf;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    u32x2_t pk;
+                    pk.x = pack_bf16x2(o[db * 16 + 4 * g + 0] * inv, o[db * 16 + 4 * g + 1] * inv);
+                    pk.y = pack_bf16x2(o[db * 16 + 4 * g + 2] * inv, o[db * 16 + 4 * g + 3] * inv);
+                    *reinterpret_cast<u32x2_t*>(dst + db * 32 + 8 * g) = pk;
+                }
+        }
+    }
+}
+
 template <int DH, int QG, int KSPLIT>
 void launch_pipe(const AttnParams& p, int B, hipStream_t stream) {
     constexpr size_t tile_bytes = (size_t)2 * (64 * KSPLIT * (DH / 8) + DH * (8 * KSPLIT)) * 16;
@@ -1010,6 +1090,23 @@ void launch_pipe(const AttnParams& p, int B, hipStream_t stream) {
     const int per_wg = QG * 64;
     attention_pipe_kernel<DH, QG, KSPLIT>
         <<<dim3((p.k_tokens + per_wg - 1) / per_wg, p.H, B), QG * KSPLIT * 64, smem, stream>>>(p);
+}
+
+// the pipelined kernel with the key range split between `p.splits` workgroups per query tile, then the merge
+template <int DH, int QG, int KSPLIT>
+void launch_pipe_split(const AttnParams& p, int B, hipStream_t stream) {
+    constexpr size_t tile_bytes = (size_t)2 * (64 * KSPLIT * (DH / 8) + DH * (8 * KSPLIT)) * 16;
+    constexpr size_t merge_bytes = KSPLIT > 1 ? (size_t)QG * (DH / 32 * 16 + 2) * 2 * 64 * 4 : 0;
+    constexpr size_t smem = tile_bytes > merge_bytes ? tile_bytes : merge_bytes;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_pipe_kernel<DH, QG, KSPLIT, true>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        attr_set = true;
+    }
+    attention_pipe_kernel<DH, QG, KSPLIT, true>
+        <<<dim3(p.q_tiles * p.splits, p.H, B), QG * KSPLIT * 64, smem, stream>>>(p);
+    attention_merge_kernel<DH, QG><<<dim3(p.q_tiles, p.H, B), QG * 64, 0, stream>>>(p);
 }
 
 template <int DH, int QB, int QG, int KSPLIT>
@@ -1039,6 +1136,26 @@ int attn_cfg_override() {
 
 }  // namespace
 
+AttnSplitPlan attention_split_plan(int B, int H, int dh, int k_tokens, int L) {
+    AttnSplitPlan sp{1, 0, 0};
+    if (dh != 128 || L <= 256) return sp;
+    const long q_tiles = (k_tokens + 127) / 128;
+    const long wg128 = q_tiles * H * B;
+    if (wg128 >= 192) return sp;
+    int s = (int)(256 / wg128);
+    if (s > 4) s = 4;
+    for (; s > 1; --s) {
+        const int per = (((L + s - 1) / s) + 127) / 128 * 128;   // whole key tiles
+        if (per > 256 && L - (s - 1) * per > 256) {               // every range has at least three tiles
+            sp.splits = s;
+            sp.keys_per_split = per;
+            sp.bytes = (size_t)wg128 * s * (2 * 2 + 4 * 2 * 16) * 128 * sizeof(float);
+            return sp;
+        }
+    }
+    return sp;
+}
+
 void launch_attention(const AttnArgs& a, hipStream_t stream) {
     AttnParams p;
     p.q = static_cast<const bf16_t*>(a.q);
@@ -1047,6 +1164,16 @@ void launch_attention(const AttnArgs& a, hipStream_t stream) {
     p.o = static_cast<bf16_t*>(a.o);
     p.H = a.H; p.k_tokens = a.k_tokens; p.L = a.L; p.L_cap = a.L_cap; p.D = a.H * a.dh;
     p.scale_log2e = a.scale * 1.4426950408889634f;
+    p.q_tiles = (a.k_tokens + 127) / 128; p.splits = 1; p.keys_per_split = 0; p.part = nullptr;
+    if (a.split_ws && attn_cfg_override() < 0) {
+        const AttnSplitPlan sp = attention_split_plan(a.B, a.H, a.dh, a.k_tokens, a.L);
+        if (sp.splits > 1) {
+            p.splits = sp.splits; p.keys_per_split = sp.keys_per_split;
+            p.part = static_cast<float*>(a.split_ws);
+            launch_pipe_split<128, 2, 2>(p, a.B, stream);
+            return;
+        }
+    }
     // Head dim 128 and more than two key tiles: the software-pipelined kernel (64 queries per wave),
     // with 128-query workgroups (two query groups x two key slices) or 256-query workgroups (four query
     // groups), whichever needs less time for its rounds of workgroups; with fewer than 128 workgroups

@@ -16,7 +16,7 @@ inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 constexpr int kMaxWidth = 8192;  // LayerNorm keeps a row in registers; score keeps the mean in 64 KB of LDS
 
 struct BlockPlan {
-    size_t off_a, off_q, off_h1, off_u, off_rows, bytes;
+    size_t off_a, off_q, off_h1, off_u, off_rows, off_asplit, asplit_bytes, bytes;
 };
 
 BlockPlan block_plan(const fastvar_dims* d, int B, int k) {
@@ -28,6 +28,15 @@ BlockPlan block_plan(const fastvar_dims* d, int B, int k) {
     p.off_h1 = off;  off += round256(M * d->D * 2);  // residual stream after attention
     p.off_u = off;   off += round256(M * d->F * 2);  // MLP hidden
     p.off_rows = off; off += round256(M * 4);        // absolute source row of every kept token
+    // partial outputs of an attention whose key range is split between workgroups (few kept tokens);
+    // sized for the longest cache the capacity check allows is not known here: the plan is taken
+    // for the worst case over L (the scratch does not depend on L, only on B, H and k)
+    p.asplit_bytes = 0;
+    if (d->dh == 128 && k > 0) {
+        const long wg128 = (long)((k + 127) / 128) * d->H * B;
+        if (wg128 < 192) p.asplit_bytes = (size_t)wg128 * 4 * (2 * 2 + 4 * 2 * 16) * 128 * sizeof(float);
+    }
+    p.off_asplit = off; off += round256(p.asplit_bytes);
     p.bytes = off;
     return p;
 }
@@ -157,6 +166,7 @@ void enqueue_attn(const void* x, int N, const int32_t* idx, int B, int k, const 
     at.q = buf_q; at.k_cache = kc; at.v_cache = vc; at.o = buf_a;
     at.B = B; at.H = d->H; at.dh = d->dh; at.k_tokens = k; at.L = L0 + k; at.L_cap = L_cap;
     at.scale = d->softmax_scale;
+    at.split_ws = bp.asplit_bytes ? base + bp.off_asplit : nullptr;
     fv::launch_attention(at, st);
     mark(st, FASTVAR_STAGE_ATTENTION);
     // h1 = x[idx] + o * Wp^T + bp

@@ -79,7 +79,21 @@ struct AttnArgs {
     void* o;              // [B*k, D] bf16
     int B, H, dh, k_tokens, L, L_cap;
     float scale;
+    // Optional scratch (attention_split_plan) that lets shapes with too few queries to fill the chip
+    // split the key range between workgroups; without it every workgroup walks all keys.
+    void* split_ws = nullptr;
 };
 void launch_attention(const AttnArgs& a, hipStream_t stream);
+
+// Key-range split for attention shapes that give fewer than 192 workgroups of 128 queries: `splits`
+// workgroups per query tile each take `keys_per_split` keys (a multiple of the key tile) and leave
+// unnormalised partial outputs with their softmax statistics in scratch; a second kernel merges them
+// (softmax partials combine exactly).  splits == 1: no scratch, no second kernel.
+struct AttnSplitPlan {
+    int splits;
+    int keys_per_split;
+    size_t bytes;
+};
+AttnSplitPlan attention_split_plan(int B, int H, int dh, int k_tokens, int L);
 
 }  // namespace fv

@@ -116,7 +116,8 @@ __global__ __launch_bounds__(64 * kFinGroups) void colsum_finalize_kernel(const 
     }
 }
 
-constexpr int kScoreRowsPerBlock = 16;  // 4 waves x 2 passes x 2 rows
+constexpr int kScoreRowsPerBlock = 16;  // 8 waves x 2 rows: two waves per SIMD cover each other's fp64 chains and loads
+constexpr int kScoreThreads = 512;
 
 __device__ __forceinline__ void sqdev8(double& acc, const uint4& v, const double* mu /* stride 64 */) {
     double d;
@@ -130,15 +131,15 @@ __device__ __forceinline__ void sqdev8(double& acc, const uint4& v, const double
     d = (double)bf16_hi(v.w) - mu[7 * 64]; acc = fma(d, d, acc);
 }
 
-// grid (ceil(N/16), B), block 256, dynamic LDS = round_up(D,512) doubles.
+// grid (ceil(N/16), B), block 512, dynamic LDS = round_up(D,512) doubles.
 // The mean is staged in LDS as [group of 512 cols][j = col%8][lane = (col%512)/8]
 // so that the 64 lanes of a wave read consecutive doubles.
-__global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ x,
+__global__ __launch_bounds__(kScoreThreads) void score_kernel(const bf16_t* __restrict__ x,
                                                     const double* __restrict__ mean,
                                                     float* __restrict__ score, int N, int D) {
     extern __shared__ double mu_s[];
     const int b = blockIdx.y;
-    for (int c = threadIdx.x; c < D; c += 256) {
+    for (int c = threadIdx.x; c < D; c += kScoreThreads) {
         const int g = c >> 9, r = c & 511;
         mu_s[g * 512 + (r & 7) * 64 + (r >> 3)] = mean[(size_t)b * D + c];
     }
@@ -147,9 +148,8 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ x
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int groups = (D + 511) >> 9;
-#pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
-        const int n0 = blockIdx.x * kScoreRowsPerBlock + pass * 8 + wave * 2;
+    {
+        const int n0 = blockIdx.x * kScoreRowsPerBlock + wave * 2;
         const int n1 = n0 + 1;
         const bool ok0 = n0 < N, ok1 = n1 < N;
         const bf16_t* row0 = x + ((size_t)b * N + (ok0 ? n0 : 0)) * D;
@@ -331,7 +331,7 @@ void launch_select(const void* x, int B, int N, int D, int k, int32_t* idx, int3
             xb, partial, N, D, plan.rows_per_chunk, plan.n_chunks);
     colsum_finalize_kernel<<<dim3((D + 63) / 64, B), 64 * kFinGroups, 0, stream>>>(partial, mean, N, D, plan.n_chunks);
     const size_t mu_bytes = (size_t)plan.col_tiles * 512 * sizeof(double);
-    score_kernel<<<dim3((N + kScoreRowsPerBlock - 1) / kScoreRowsPerBlock, B), 256, mu_bytes, stream>>>(
+    score_kernel<<<dim3((N + kScoreRowsPerBlock - 1) / kScoreRowsPerBlock, B), kScoreThreads, mu_bytes, stream>>>(
         xb, mean, score, N, D);
     static bool attr_set = false;  // maps above 16K tokens need more than the default 64 KB of dynamic LDS
     if (!attr_set) {

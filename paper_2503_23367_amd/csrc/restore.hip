@@ -141,37 +141,63 @@ __global__ __launch_bounds__(256) void restore_colsum_kernel(const bf16_t* __res
 
     if (col < D) {
         const bf16_t* cb = cache_map + (size_t)b * hc * wc * D + col;
-        for (int n = r0 + wave; n < r1; n += 4) {
-            const int r = (k > 0) ? rank[(size_t)b * N + n] : -1;
-            bf16_t* dst = y_out + ((size_t)b * N + n) * D + col;
-            uint4 o;
-            if (r >= 0) {
-                if (y_kept) {
-                    o = *reinterpret_cast<const uint4*>(y_kept + ((size_t)b * k + r) * D + col);
-                    *reinterpret_cast<uint4*>(dst) = o;
-                } else {
-                    o = *reinterpret_cast<const uint4*>(dst);   // written by the block's last GEMM
-                }
-            } else {
-                int i0, i1, j0, j1;
-                float lr, lc;
-                axis_taps(n / w, hc, h, i0, i1, lr);
-                axis_taps(n % w, wc, w, j0, j1, lc);
-                const uint4 a = *reinterpret_cast<const uint4*>(cb + ((size_t)i0 * wc + j0) * D);
-                const uint4 bq = *reinterpret_cast<const uint4*>(cb + ((size_t)i0 * wc + j1) * D);
-                const uint4 c = *reinterpret_cast<const uint4*>(cb + ((size_t)i1 * wc + j0) * D);
-                const uint4 d = *reinterpret_cast<const uint4*>(cb + ((size_t)i1 * wc + j1) * D);
-                o.x = pack_bf16x2(lerp2(bf16_lo(a.x), bf16_lo(bq.x), bf16_lo(c.x), bf16_lo(d.x), lr, lc),
-                                  lerp2(bf16_hi(a.x), bf16_hi(bq.x), bf16_hi(c.x), bf16_hi(d.x), lr, lc));
-                o.y = pack_bf16x2(lerp2(bf16_lo(a.y), bf16_lo(bq.y), bf16_lo(c.y), bf16_lo(d.y), lr, lc),
-                                  lerp2(bf16_hi(a.y), bf16_hi(bq.y), bf16_hi(c.y), bf16_hi(d.y), lr, lc));
-                o.z = pack_bf16x2(lerp2(bf16_lo(a.z), bf16_lo(bq.z), bf16_lo(c.z), bf16_lo(d.z), lr, lc),
-                                  lerp2(bf16_hi(a.z), bf16_hi(bq.z), bf16_hi(c.z), bf16_hi(d.z), lr, lc));
-                o.w = pack_bf16x2(lerp2(bf16_lo(a.w), bf16_lo(bq.w), bf16_lo(c.w), bf16_lo(d.w), lr, lc),
-                                  lerp2(bf16_hi(a.w), bf16_hi(bq.w), bf16_hi(c.w), bf16_hi(d.w), lr, lc));
-                *reinterpret_cast<uint4*>(dst) = o;
+        // Rows are taken eight at a time (one chunk of 32 rows is eight per wave): first every row's
+        // rank, then every row's loads, then the arithmetic, so that the memory latencies of the rows
+        // overlap instead of adding up.  The sums still see the rows in ascending order.
+        constexpr int RB = 8;
+        for (int nb = r0 + wave; nb < r1; nb += 4 * RB) {
+            int rk[RB];
+#pragma unroll
+            for (int i = 0; i < RB; ++i) {
+                const int n = nb + 4 * i;
+                rk[i] = (n < r1 && k > 0) ? rank[(size_t)b * N + n] : -1;
             }
-            add8d(acc, o);
+            uint4 t0[RB], t1[RB], t2[RB], t3[RB];
+            float lr[RB], lc[RB];
+#pragma unroll
+            for (int i = 0; i < RB; ++i) {
+                const int n = nb + 4 * i;
+                if (n < r1) {
+                    if (rk[i] >= 0) {
+                        const bf16_t* src = y_kept ? y_kept + ((size_t)b * k + rk[i]) * D + col
+                                                   : y_out + ((size_t)b * N + n) * D + col;   // already in place
+                        t0[i] = *reinterpret_cast<const uint4*>(src);
+                    } else {
+                        int i0, i1, j0, j1;
+                        axis_taps(n / w, hc, h, i0, i1, lr[i]);
+                        axis_taps(n % w, wc, w, j0, j1, lc[i]);
+                        t0[i] = *reinterpret_cast<const uint4*>(cb + ((size_t)i0 * wc + j0) * D);
+                        t1[i] = *reinterpret_cast<const uint4*>(cb + ((size_t)i0 * wc + j1) * D);
+                        t2[i] = *reinterpret_cast<const uint4*>(cb + ((size_t)i1 * wc + j0) * D);
+                        t3[i] = *reinterpret_cast<const uint4*>(cb + ((size_t)i1 * wc + j1) * D);
+                    }
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < RB; ++i) {
+                const int n = nb + 4 * i;
+                if (n < r1) {
+                    bf16_t* dst = y_out + ((size_t)b * N + n) * D + col;
+                    uint4 o;
+                    if (rk[i] >= 0) {
+                        o = t0[i];
+                        if (y_kept) *reinterpret_cast<uint4*>(dst) = o;
+                    } else {
+                        const uint4 a = t0[i], bq = t1[i], c = t2[i], d = t3[i];
+                        const float fr = lr[i], fc = lc[i];
+                        o.x = pack_bf16x2(lerp2(bf16_lo(a.x), bf16_lo(bq.x), bf16_lo(c.x), bf16_lo(d.x), fr, fc),
+                                          lerp2(bf16_hi(a.x), bf16_hi(bq.x), bf16_hi(c.x), bf16_hi(d.x), fr, fc));
+                        o.y = pack_bf16x2(lerp2(bf16_lo(a.y), bf16_lo(bq.y), bf16_lo(c.y), bf16_lo(d.y), fr, fc),
+                                          lerp2(bf16_hi(a.y), bf16_hi(bq.y), bf16_hi(c.y), bf16_hi(d.y), fr, fc));
+                        o.z = pack_bf16x2(lerp2(bf16_lo(a.z), bf16_lo(bq.z), bf16_lo(c.z), bf16_lo(d.z), fr, fc),
+                                          lerp2(bf16_hi(a.z), bf16_hi(bq.z), bf16_hi(c.z), bf16_hi(d.z), fr, fc));
+                        o.w = pack_bf16x2(lerp2(bf16_lo(a.w), bf16_lo(bq.w), bf16_lo(c.w), bf16_lo(d.w), fr, fc),
+                                          lerp2(bf16_hi(a.w), bf16_hi(bq.w), bf16_hi(c.w), bf16_hi(d.w), fr, fc));
+                        *reinterpret_cast<uint4*>(dst) = o;
+                    }
+                    add8d(acc, o);
+                }
+            }
         }
     }
 

@@ -16,7 +16,8 @@ inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 constexpr int kMaxWidth = 8192;  // LayerNorm keeps a row in registers; score keeps the mean in 64 KB of LDS
 
 struct BlockPlan {
-    size_t off_a, off_q, off_h1, off_u, off_rows, off_asplit, asplit_bytes, bytes;
+    size_t off_a, off_q, off_h1, off_u, off_rows, off_asplit, asplit_bytes, off_sk, sk_bytes, bytes;
+    int sk_counters;
 };
 
 BlockPlan block_plan(const fastvar_dims* d, int B, int k) {
@@ -37,6 +38,17 @@ BlockPlan block_plan(const fastvar_dims* d, int B, int k) {
         if (wg128 < 192) p.asplit_bytes = (size_t)wg128 * 4 * (2 * 2 + 4 * 2 * 16) * 128 * sizeof(float);
     }
     p.off_asplit = off; off += round256(p.asplit_bytes);
+    // split-K scratch of the GEMMs (only shapes with few output tiles have any): one area, the
+    // largest of the four, used by one GEMM at a time
+    p.sk_bytes = 0;
+    p.sk_counters = 0;
+    const int shapes[4][2] = {{3 * d->D, d->D}, {d->D, d->D}, {d->F, d->D}, {d->D, d->F}};
+    for (const auto& nk : shapes) {
+        const fv::SplitKPlan sk = fv::gemm_splitk_plan((int)M, nk[0], nk[1]);
+        if (sk.bytes > p.sk_bytes) p.sk_bytes = sk.bytes;
+        if (sk.splits > 1 && sk.tiles > p.sk_counters) p.sk_counters = sk.tiles;
+    }
+    p.off_sk = off; off += round256(p.sk_bytes);
     p.bytes = off;
     return p;
 }
@@ -146,6 +158,7 @@ void enqueue_attn(const void* x, int N, const int32_t* idx, int B, int k, const 
     void* buf_a = base + bp.off_a;
     void* buf_q = base + bp.off_q;
     int32_t* rows = reinterpret_cast<int32_t*>(base + bp.off_rows);
+    void* sk = bp.sk_bytes ? base + bp.off_sk : nullptr;
     const int M = B * k;
 
     // a1 = LN1(x[idx]); without an index list every token is kept, in order
@@ -159,6 +172,7 @@ void enqueue_attn(const void* x, int N, const int32_t* idx, int B, int k, const 
     g.A = buf_a; g.W = w->w_qkv; g.bias = w->b_qkv; g.M = M; g.N = 3 * d->D; g.K = d->D;
     g.q_out = buf_q; g.k_cache = kc; g.v_cache = vc;
     g.D = d->D; g.H = d->H; g.dh = d->dh; g.k_tokens = k; g.L0 = L0; g.L_cap = L_cap;
+    g.splitk_ws = sk;
     fv::launch_gemm(fv::EPI_QKV, g, st);
     mark(st, FASTVAR_STAGE_QKV);
     // o = softmax(q K^T * scale) V over cache positions [0, L0+k)
@@ -174,6 +188,7 @@ void enqueue_attn(const void* x, int N, const int32_t* idx, int B, int k, const 
     pj.A = buf_a; pj.W = w->w_proj; pj.bias = w->b_proj; pj.M = M; pj.N = d->D; pj.K = d->D;
     pj.out = h1_out; pj.residual = x; pj.res_rows = idx ? rows : nullptr; pj.k_tokens = k;
     pj.out_rows = (scatter && idx) ? rows : nullptr;
+    pj.splitk_ws = sk;
     fv::launch_gemm(fv::EPI_BIAS_RES, pj, st);
     mark(st, FASTVAR_STAGE_PROJ);
 }
@@ -189,6 +204,7 @@ void enqueue_ffn(const void* src, int N, const int32_t* idx, int B, int k, const
     void* buf_q = base + bp.off_q;
     void* buf_u = base + bp.off_u;
     int32_t* rows = reinterpret_cast<int32_t*>(base + bp.off_rows);
+    void* sk = bp.sk_bytes ? base + bp.off_sk : nullptr;
     const int M = B * k;
 
     // a2 = LN2(s)
@@ -201,6 +217,7 @@ void enqueue_ffn(const void* src, int N, const int32_t* idx, int B, int k, const
     fv::GemmArgs f1{};
     f1.A = buf_q; f1.W = w->w_fc1; f1.bias = w->b_fc1; f1.M = M; f1.N = d->F; f1.K = d->D;
     f1.out = buf_u; f1.k_tokens = k;
+    f1.splitk_ws = sk;
     fv::launch_gemm(fv::EPI_BIAS_GELU, f1, st);
     mark(st, FASTVAR_STAGE_FC1);
     // y = s + u * W2^T + b2
@@ -208,12 +225,22 @@ void enqueue_ffn(const void* src, int N, const int32_t* idx, int B, int k, const
     f2.A = buf_u; f2.W = w->w_fc2; f2.bias = w->b_fc2; f2.M = M; f2.N = d->D; f2.K = d->F;
     f2.out = y; f2.residual = src; f2.res_rows = idx ? rows : nullptr; f2.k_tokens = k;
     f2.out_rows = scatter ? rows : nullptr;
+    f2.splitk_ws = sk;
     fv::launch_gemm(fv::EPI_BIAS_RES, f2, st);
     mark(st, FASTVAR_STAGE_FC2);
 }
 
 // `scatter`: y is the [B, N, D] output map and the kept tokens' outputs go straight to their own rows
 // (the row list written by the gather of the attention half is still in the plan when FC2 runs).
+// The arrival counters of the split-K scratch must be zero before the first GEMM that uses them; every
+// such GEMM leaves them zero again, so once per entry-point call is enough.
+void zero_splitk_counters(void* ws, const fastvar_dims* d, int B, int k, hipStream_t st) {
+    if (k <= 0) return;
+    const BlockPlan bp = block_plan(d, B, k);
+    if (bp.sk_bytes)
+        fv::launch_zero_i32(reinterpret_cast<int32_t*>(static_cast<char*>(ws) + bp.off_sk), bp.sk_counters, st);
+}
+
 void enqueue_block(const void* x, int N, const int32_t* idx, int B, int k, const fastvar_dims* d,
                    const fastvar_block_weights* w, void* kc, void* vc, int L0, int L_cap, void* y, void* ws,
                    hipStream_t st, bool scatter = false) {
@@ -302,6 +329,7 @@ int fastvar_block_forward_pruned(const void* x, int N, const int32_t* idx, int B
                                ws_bytes);
     if (rc) return rc;
     if (k == 0) return FASTVAR_OK;
+    zero_splitk_counters(ws, dims, B, k, static_cast<hipStream_t>(stream));
     enqueue_block(x, N, idx, B, k, dims, weights, k_cache, v_cache, L0, L_cap, y_kept_out, ws,
                   static_cast<hipStream_t>(stream));
     return launch_status();
@@ -362,6 +390,7 @@ int fastvar_step(const void* x, const int32_t* sched_h, const int32_t* sched_w, 
     if (rc) return rc;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
+    zero_splitk_counters(ws_blk, dims, B, k, st);
     fv::launch_select(x, B, N, D, k, idx_out, rank, nullptr, ws_sel, fv::select_plan(B, N, D), st);
     // The block's last GEMM writes the kept rows of y_out itself; restoration fills the others.
     if (k > 0)
@@ -436,6 +465,7 @@ int fastvar_scale_step(const void* x, const int32_t* sched_h, const int32_t* sch
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const fv::SelectPlan sp = fv::select_plan(B, N, D);
+    zero_splitk_counters(ws_blk, dims, B, k, st);
     for (int l = 0; l < n_layers; ++l) {
         const fastvar_layer& ly = layers[l];
         const void* src = l == 0 ? x : dst_of(l - 1);
@@ -512,6 +542,7 @@ int fastvar_attn_forward_pruned(const void* x, int N, const int32_t* idx, int B,
                                ws_bytes);
     if (rc) return rc;
     if (k == 0) return FASTVAR_OK;
+    zero_splitk_counters(ws, dims, B, k, static_cast<hipStream_t>(stream));
     enqueue_attn(x, N, idx, B, k, dims, weights, k_cache, v_cache, L0, L_cap, h_kept_out, ws,
                  static_cast<hipStream_t>(stream));
     return launch_status();
@@ -523,6 +554,7 @@ int fastvar_ffn_forward_pruned(const void* x, int N, const int32_t* idx, int B, 
     const int rc = check_ffn(x, N, idx, B, k, dims, weights, y_kept_out, ws, ws_bytes);
     if (rc) return rc;
     if (k == 0) return FASTVAR_OK;
+    zero_splitk_counters(ws, dims, B, k, static_cast<hipStream_t>(stream));
     enqueue_ffn(x, N, idx, B, k, dims, weights, y_kept_out, ws, static_cast<hipStream_t>(stream));
     return launch_status();
 }
@@ -577,12 +609,14 @@ int fastvar_step_sublayer(const void* x, const int32_t* sched_h, const int32_t* 
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const fv::SelectPlan sp = fv::select_plan(B, N, D);
+    zero_splitk_counters(ws_blk, dims, B, k_attn, st);
     fv::launch_select(x, B, N, D, k_attn, idx_attn_out, rank, nullptr, ws_sel, sp, st);
     if (k_attn > 0)
         enqueue_attn(x, N, idx_attn_out, B, k_attn, dims, weights, k_cache, v_cache, L0, L_cap, x_mid, ws_blk, st, true);
     // the first restoration also leaves the column-sum partials of x_mid for the second selection
     fv::launch_restore_colsum(nullptr, rank, B, k_attn, cache_map_attn, hc, wc, h, w, D, x_mid, ws_sel, sp, st);
     fv::launch_select(x_mid, B, N, D, k_ffn, idx_ffn_out, rank, nullptr, ws_sel, sp, st, true);
+    zero_splitk_counters(ws_blk, dims, B, k_ffn, st);   // the two halves lay the scratch out for their own k
     if (k_ffn > 0) enqueue_ffn(x_mid, N, idx_ffn_out, B, k_ffn, dims, weights, y_out, ws_blk, st, true);
     fv::launch_restore(nullptr, rank, B, k_ffn, cache_map_ffn, hc, wc, h, w, D, y_out, st);
     rc = launch_status();

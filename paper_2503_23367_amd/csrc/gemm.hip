@@ -49,6 +49,9 @@ struct GemmParams {
     bf16_t* v_cache;
     int D, H, dh, k_tokens, L0, L_cap;
     int tiles_m, tiles_n;
+    int splits;        // split-K slices (grid.y); 1 unless the kernel is instantiated with SK
+    float* sk_part;    // [tile][slice][BM*BN] fp32 partial tiles, accumulator-register order
+    int* sk_cnt;       // [tile] arrival counters, zero between launches
 };
 
 // Where one output column lands: element address = ptr + b*batch_stride + t*row_stride
@@ -109,7 +112,10 @@ __device__ __forceinline__ int swz(int row) {
 // summed through LDS at the end.  Eight waves (two per SIMD) cover each other's
 // barrier, load and LDS waits where the tile gives one wave per SIMD too little
 // independent work.
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, int KG, int EPI>
+// SK: the K range is also split between workgroups (blockIdx.y); every workgroup leaves its partial
+// tile in scratch memory, and the one that arrives last at the tile's counter adds the slices up, in
+// slice order (so the sum does not depend on who was last), and runs the epilogue.  Nobody waits.
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, int KG, int EPI, bool SK = false>
 __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const GemmParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
     constexpr int NWQ = WGM * WGN;             // waves per k-group
@@ -154,6 +160,12 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
     const int tm = first_m + in_grp % gsize;
     const int tn = in_grp / gsize;
     const int m0 = tm * BM, n0 = tn * BN;
+    static_assert(!SK || KG == 1, "split-K across workgroups is written for one k-group");
+    const int n_splits = SK ? p.splits : 1;
+    const int split = SK ? (int)blockIdx.y : 0;
+    const int KT = p.K / BK / n_splits;          // K tiles of this workgroup
+    const bf16_t* const Ab = p.A + (size_t)split * KT * BK;
+    const bf16_t* const Wb = p.W + (size_t)split * KT * BK;
 
     // Direct-to-LDS loads: one instruction moves 64 x 16 bytes into a contiguous
     // 1 KB of LDS (lane l lands at base + 16 l), i.e. RPI whole tile rows.  The
@@ -187,10 +199,10 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
 #define FV_ISSUE_Q(kt_, stage_, q_)                                                             \
     {                                                                                           \
         if ((q_) < A_LD)                                                                        \
-            FV_DMA16(p.A + (size_t)(kt_) * BK, a_off[(q_) < A_LD ? (q_) : 0],                   \
+            FV_DMA16(Ab + (size_t)(kt_) * BK, a_off[(q_) < A_LD ? (q_) : 0],                   \
                      lds + (stage_) * STAGE + wave * 64 + (q_) * (NW * 64));                    \
         else                                                                                    \
-            FV_DMA16(p.W + (size_t)(kt_) * BK, w_off[(q_) >= A_LD ? (q_) - A_LD : 0],           \
+            FV_DMA16(Wb + (size_t)(kt_) * BK, w_off[(q_) >= A_LD ? (q_) - A_LD : 0],           \
                      lds + (stage_) * STAGE + A_TILE + wave * 64 + ((q_) - A_LD) * (NW * 64));  \
     }
 #define FV_ISSUE_TILE(kt_, stage_)                                                              \
@@ -239,8 +251,6 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
         for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
-
-    const int KT = p.K / BK;
 
     // ---- prologue: STAGES-1 tiles in flight, wait for the first
 #pragma unroll
@@ -370,6 +380,66 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
         }
         if (kg != 0) return;  // no barrier follows
     }
+    if (SK) {
+        // Leave this slice's partial tile (register-major, lane contiguous), then count arrivals;
+        // 32-row blocks that lie entirely past M (most of the tile at the small scales) are skipped.
+        // The partial tiles and the counter are written and read with device-scope atomic accesses
+        // (relaxed): those are coherent across the chip's L2s by themselves, so no cache write-back
+        // or invalidate is needed (a device-scope fence in each of 256 workgroups costs 7 us per
+        // GEMM here).  Order: every thread waits until its own stores have been acknowledged, the
+        // barrier collects the workgroup, and only then one thread counts the workgroup in.
+        float* part = p.sk_part + ((size_t)blockIdx.x * n_splits) * (BM * BN) + wq * 64 + lane;
+        float* mine = part + (size_t)split * (BM * BN);
+        static_for<0, MI>([&](auto mi_c) {
+            constexpr int mi = decltype(mi_c)::value;
+            if (m0 + wm * WTM + mi * 32 < p.M) {
+                static_for<0, NI * 16>([&](auto j_c) {
+                    constexpr int j = decltype(j_c)::value;
+                    __hip_atomic_store(mine + (mi * NI * 16 + j) * (NWQ * 64), acc[mi][j / 16][j % 16],
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                });
+            }
+        });
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));   // own stores acknowledged
+        int* flag = reinterpret_cast<int*>(smem);
+        __syncthreads();
+        if (tid == 0)
+            *flag = __hip_atomic_fetch_add(p.sk_cnt + blockIdx.x, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        const int arrived = *flag;
+        __syncthreads();                 // the flag's LDS word is staging memory below
+        if (arrived != n_splits - 1) return;
+        // sum the slices in slice order; several slices' loads in flight at a time (128 registers' worth)
+        static_for<0, MI>([&](auto mi_c) {
+            constexpr int mi = decltype(mi_c)::value;
+            if (m0 + wm * WTM + mi * 32 < p.M) {
+                float sum[NI * 16];
+                _Pragma("unroll") for (int j = 0; j < NI * 16; ++j) sum[j] = 0.f;
+                constexpr int SG = 8 / NI > 0 ? 8 / NI : 1;
+                for (int s0 = 0; s0 < n_splits; s0 += SG) {
+                    float v[SG][NI * 16];
+                    _Pragma("unroll") for (int g = 0; g < SG; ++g) {
+                        const int sl = min(s0 + g, n_splits - 1);
+                        const float* src = part + (size_t)sl * (BM * BN) + (mi * NI * 16) * (NWQ * 64);
+                        _Pragma("unroll") for (int j = 0; j < NI * 16; ++j)
+                            v[g][j] = __hip_atomic_load(src + j * (NWQ * 64), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                    _Pragma("unroll") for (int g = 0; g < SG; ++g) {
+                        if (s0 + g < n_splits) {
+                            _Pragma("unroll") for (int j = 0; j < NI * 16; ++j) sum[j] += v[g][j];
+                        }
+                    }
+                }
+                static_for<0, NI * 16>([&](auto j_c) {
+                    constexpr int j = decltype(j_c)::value;
+                    acc[mi][j / 16][j % 16] = sum[j];
+                });
+            }
+        });
+        if (tid == 0)   // ready for the next launch
+            __hip_atomic_store(p.sk_cnt + blockIdx.x, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     float* stg = reinterpret_cast<float*>(smem) + XCH + wq * (32 * SROW);
 
     float bias[NI];
@@ -464,7 +534,7 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
 #endif
 }
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, int KG, int EPI>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, int KG, int EPI, bool SK = false>
 void launch_cfg(GemmParams& p, hipStream_t stream) {
     constexpr size_t smem = (size_t)STAGES * (BM + BN) * BK * sizeof(bf16_t);
     p.tiles_m = (p.M + BM - 1) / BM;
@@ -472,12 +542,18 @@ void launch_cfg(GemmParams& p, hipStream_t stream) {
     static bool attr_set = false;  // raising the dynamic-LDS limit is per function, once per process
     if (!attr_set) {
         (void)hipFuncSetAttribute(
-            reinterpret_cast<const void*>(&gemm_nt_kernel<BM, BN, BK, STAGES, WGM, WGN, KG, EPI>),
+            reinterpret_cast<const void*>(&gemm_nt_kernel<BM, BN, BK, STAGES, WGM, WGN, KG, EPI, SK>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         attr_set = true;
     }
-    gemm_nt_kernel<BM, BN, BK, STAGES, WGM, WGN, KG, EPI>
-        <<<dim3(p.tiles_m * p.tiles_n), 64 * WGM * WGN * KG, smem, stream>>>(p);
+    if (!SK) p.splits = 1;
+    gemm_nt_kernel<BM, BN, BK, STAGES, WGM, WGN, KG, EPI, SK>
+        <<<dim3(p.tiles_m * p.tiles_n, SK ? p.splits : 1), 64 * WGM * WGN * KG, smem, stream>>>(p);
+}
+
+__global__ void zero_i32_kernel(int32_t* p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
 }
 
 // Developer knob: FASTVAR_GEMM_CFG (all epilogues) or FASTVAR_GEMM_CFG<e> (epilogue e = 0, 1, 2)
@@ -527,6 +603,16 @@ void launch_epi(GemmParams& p, hipStream_t stream) {
     else   // one three-stage workgroup per CU, or two two-stage ones (about 8 % faster per tile when both fill)
         cfg = 1.08 * fill(tiles128, 512) >= fill(tiles128, 256) ? 6 : 7;
     if (gemm_cfg_override(EPI) >= 0) cfg = gemm_cfg_override(EPI);
+    if (p.sk_part && gemm_cfg_override(EPI) < 0) {
+        // few output tiles: split K between workgroups (the caller sized the scratch with the same plan)
+        const SplitKPlan sk = gemm_splitk_plan(p.M, p.N, p.K);
+        if (sk.splits > 1) {
+            p.splits = sk.splits;
+            if (sk.small_tiles) launch_cfg<64, 64, 64, 8, 2, 2, 1, EPI, true>(p, stream);
+            else launch_cfg<128, 128, 64, 3, 2, 2, 1, EPI, true>(p, stream);
+            return;
+        }
+    }
     switch (cfg) {
         case 1: launch_cfg<256, 256, 64, 2, 2, 2, 1, EPI>(p, stream); break;
         case 3: launch_cfg<128, 128, 32, 4, 2, 2, 1, EPI>(p, stream); break;
@@ -544,6 +630,26 @@ void launch_epi(GemmParams& p, hipStream_t stream) {
 
 }  // namespace
 
+SplitKPlan gemm_splitk_plan(int M, int N, int K) {
+    SplitKPlan sk;
+    sk.small_tiles = M <= 64;
+    const int t = sk.small_tiles ? 64 : 128;
+    sk.tiles = ((M + t - 1) / t) * ((N + t - 1) / t);
+    sk.splits = 1;
+    const int KT = K / 64;
+    const int min_kt = sk.small_tiles ? 2 : 4;   // K tiles a slice must keep
+    if (sk.tiles <= (sk.small_tiles ? 128 : 96))
+        while (sk.tiles * sk.splits * 2 <= 256 && KT % (sk.splits * 2) == 0 && KT / (sk.splits * 2) >= min_kt)
+            sk.splits *= 2;
+    sk.counter_bytes = sk.splits > 1 ? (((size_t)sk.tiles * 4 + 255) & ~(size_t)255) : 0;
+    sk.bytes = sk.splits > 1 ? sk.counter_bytes + (size_t)sk.tiles * sk.splits * t * t * 4 : 0;
+    return sk;
+}
+
+void launch_zero_i32(int32_t* p, int n, hipStream_t stream) {
+    if (n > 0) zero_i32_kernel<<<(n + 255) / 256, 256, 0, stream>>>(p, n);
+}
+
 void launch_gemm(GemmEpilogue epi, const GemmArgs& a, hipStream_t stream) {
     GemmParams p;
     p.A = static_cast<const bf16_t*>(a.A);
@@ -559,6 +665,16 @@ void launch_gemm(GemmEpilogue epi, const GemmArgs& a, hipStream_t stream) {
     p.v_cache = static_cast<bf16_t*>(a.v_cache);
     p.D = a.D; p.H = a.H; p.dh = a.dh; p.k_tokens = a.k_tokens; p.L0 = a.L0; p.L_cap = a.L_cap;
     p.tiles_m = p.tiles_n = 0;
+    p.splits = 1;
+    p.sk_part = nullptr;
+    p.sk_cnt = nullptr;
+    if (a.splitk_ws) {
+        const SplitKPlan sk = gemm_splitk_plan(a.M, a.N, a.K);
+        if (sk.splits > 1) {
+            p.sk_cnt = static_cast<int*>(a.splitk_ws);
+            p.sk_part = reinterpret_cast<float*>(static_cast<char*>(a.splitk_ws) + sk.counter_bytes);
+        }
+    }
     switch (epi) {
         case EPI_QKV: launch_epi<EPI_QKV>(p, stream); break;
         case EPI_BIAS_RES: launch_epi<EPI_BIAS_RES>(p, stream); break;

@@ -69,8 +69,28 @@ struct GemmArgs {
     void* k_cache;  // [B, H, L_cap, dh]
     void* v_cache;  // [B, H, dh, L_cap]
     int D, H, dh, k_tokens, L0, L_cap;
+    // Optional scratch for the split-K path of shapes with few output tiles (gemm_splitk_plan):
+    // [counters | partial tiles]; the counters must be zero on entry and are zero again on exit.
+    void* splitk_ws = nullptr;
 };
 void launch_gemm(GemmEpilogue epi, const GemmArgs& a, hipStream_t stream);
+
+// Split-K plan for a GEMM shape with few output tiles (few rows: the small scales of a schedule, where
+// a block is nothing but streaming its weights once): the K range is cut into `splits` slices that run
+// as separate workgroups, so that every CU streams a share of the weights; the workgroup that finishes
+// a tile last sums the slices in slice order and runs the epilogue.  Up to 64 rows use 64x64 tiles with
+// an eight-stage ring (a workgroup's whole K slice, or half of it, is in flight at once), more rows
+// 128x128 tiles.  splits == 1: no scratch needed.
+struct SplitKPlan {
+    int splits;
+    int tiles;
+    bool small_tiles;      // 64x64 tiles
+    size_t counter_bytes;  // one int per tile, rounded up
+    size_t bytes;          // counters + partial tiles
+};
+SplitKPlan gemm_splitk_plan(int M, int N, int K);
+// zero the n counters at the head of a split-K scratch area
+void launch_zero_i32(int32_t* p, int n, hipStream_t stream);
 
 struct AttnArgs {
     const void* q;        // [B*k, D] bf16 (feature = head*dh + d)

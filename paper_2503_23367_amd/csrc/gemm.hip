@@ -638,9 +638,11 @@ SplitKPlan gemm_splitk_plan(int M, int N, int K) {
     sk.splits = 1;
     const int KT = K / 64;
     const int min_kt = sk.small_tiles ? 2 : 4;   // K tiles a slice must keep
-    if (sk.tiles <= (sk.small_tiles ? 128 : 96))
-        while (sk.tiles * sk.splits * 2 <= 256 && KT % (sk.splits * 2) == 0 && KT / (sk.splits * 2) >= min_kt)
-            sk.splits *= 2;
+    // a short K range is over before the slices' summing would pay for itself
+    if (K >= 2048 && sk.tiles <= (sk.small_tiles ? 128 : 96))
+        while (sk.splits < (sk.small_tiles ? 8 : 4) && sk.tiles * sk.splits * 2 <= 256 &&
+               KT % (sk.splits * 2) == 0 && KT / (sk.splits * 2) >= min_kt)
+            sk.splits *= 2;   // (more slices than that cost more to sum than they save)
     sk.counter_bytes = sk.splits > 1 ? (((size_t)sk.tiles * 4 + 255) & ~(size_t)255) : 0;
     sk.bytes = sk.splits > 1 ? sk.counter_bytes + (size_t)sk.tiles * sk.splits * t * t * 4 : 0;
     return sk;

@@ -43,6 +43,7 @@ struct AttnParams {
     // key-range split between workgroups (pipelined kernel instantiated with KVS)
     int q_tiles, splits, keys_per_split;
     float* part;   // [B][H][q_tile][split][(2*QB + DB*QB*16)][QG*64] fp32, register order
+    int* split_cnt;   // [B][H][q_tile] arrival counters, zero between launches
 };
 
 __device__ __forceinline__ int swap_bits_2_3(int v) {
@@ -984,19 +985,94 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
     }
 #undef FP_PUBLISH
     if (KVS) {
+        // Every key range leaves its partial result (statistics, then the accumulator, register-major)
+        // and counts itself in at the query tile's counter; the workgroup that arrives last combines
+        // all ranges exactly, in range order (its own from registers), normalises and stores.  The
+        // partials and the counter are accessed with device-scope relaxed atomics, coherent across
+        // the chip's L2s by themselves; every thread waits for its own stores to be acknowledged
+        // before the barrier that precedes the count.  Nobody waits for anybody.
+        constexpr int SLOTS = 2 * QB + DB * QB * 16;
+        const size_t tile_id = ((size_t)b * p.H + head) * p.q_tiles + q_tile;
+        float* part0 = p.part + tile_id * p.splits * (size_t)(SLOTS * (QG * 64)) + qg * 64 + lane;
+        const size_t sstride = (size_t)SLOTS * (QG * 64);
+        float l_tot[QB];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) l_tot[qb] = l_run[qb] + other_half(l_run[qb]);
         if (kh == 0) {
-            // partial result of this key range: statistics, then the accumulator, register-major
-            float* part = p.part + ((((size_t)b * p.H + head) * p.q_tiles + q_tile) * p.splits + split) *
-                                       (size_t)((2 * QB + DB * QB * 16) * (QG * 64)) + qg * 64 + lane;
+            float* part = part0 + split * sstride;
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
-                part[qb * (QG * 64)] = m_run[qb];
-                part[(QB + qb) * (QG * 64)] = l_run[qb] + other_half(l_run[qb]);
+                __hip_atomic_store(part + qb * (QG * 64), m_run[qb], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(part + (QB + qb) * (QG * 64), l_tot[qb], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
-                        part[(2 * QB + (db * QB + qb) * 16 + r) * (QG * 64)] = acc[db][qb][r];
+                        __hip_atomic_store(part + (2 * QB + (db * QB + qb) * 16 + r) * (QG * 64), acc[db][qb][r],
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(attn_waitcnt(0, true));   // own stores acknowledged
+        int* flag = reinterpret_cast<int*>(smem);
+        __syncthreads();
+        if (tid == 0)
+            *flag = __hip_atomic_fetch_add(p.split_cnt + tile_id, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        const int arrived = *flag;
+        if (arrived != p.splits - 1) return;
+        if (tid == 0) __hip_atomic_store(p.split_cnt + tile_id, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (kh != 0) return;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            // statistics of every range (at most four), own from registers
+            float ms[4], ws[4];
+            float m = m_run[qb];
+            for (int s2 = 0; s2 < p.splits; ++s2) {
+                ms[s2 & 3] = s2 == split ? m_run[qb]
+                                         : __hip_atomic_load(part0 + s2 * sstride + qb * (QG * 64), __ATOMIC_RELAXED,
+                                                             __HIP_MEMORY_SCOPE_AGENT);
+                m = fmaxf(m, ms[s2 & 3]);
+            }
+            float l = 0.f;
+            for (int s2 = 0; s2 < p.splits; ++s2) {
+                ws[s2 & 3] = __builtin_amdgcn_exp2f(ms[s2 & 3] - m);
+                const float ls = s2 == split ? l_tot[qb]
+                                             : __hip_atomic_load(part0 + s2 * sstride + (QB + qb) * (QG * 64),
+                                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                l += ws[s2 & 3] * ls;
+            }
+            const float inv = 1.0f / l;
+            const int qrow = q_base + qb * 32 + li;
+            bf16_t* dst = p.o + ((size_t)b * p.k_tokens + min(qrow, p.k_tokens - 1)) * p.D + head * DH + 4 * hf;
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                float o[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[r] = 0.f;
+                for (int s2 = 0; s2 < p.splits; ++s2) {
+                    float v[16];
+                    if (s2 == split) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) v[r] = acc[db][qb][r];
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            v[r] = __hip_atomic_load(part0 + s2 * sstride + (2 * QB + (db * QB + qb) * 16 + r) * (QG * 64),
+                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) o[r] += ws[s2 & 3] * v[r];
+                }
+                if (qrow < p.k_tokens) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        u32x2_t pk;
+                        pk.x = pack_bf16x2(o[4 * g + 0] * inv, o[4 * g + 1] * inv);
+                        pk.y = pack_bf16x2(o[4 * g + 2] * inv, o[4 * g + 3] * inv);
+                        *reinterpret_cast<u32x2_t*>(dst + db * 32 + 8 * g) = pk;
+                    }
+                }
             }
         }
         return;
@@ -1024,58 +1100,6 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
 #endif
 }
 
-// Merge of the key-range partials of attention_pipe_kernel<.., KVS = true>: grid (query tiles, H, B),
-// QG*64 threads; thread (qg, lane) reads, for every split, what wave (qg, key slice 0) lane `lane` left
-// (same register order), combines them exactly (O = sum_s 2^(m_s - m) O_s, l likewise), normalises and
-// stores bf16 with the pipelined kernel's own output mapping.
-template <int DH, int QG>
-__global__ __launch_bounds__(QG * 64) void attention_merge_kernel(const AttnParams p) {
-    constexpr int QB = 2, DB = DH / 32;
-    constexpr int SLOTS = 2 * QB + DB * QB * 16;
-    const int lane = threadIdx.x & 63, qg = threadIdx.x >> 6;
-    const int li = lane & 31, hf = lane >> 5;
-    const int q_tile = blockIdx.x, head = blockIdx.y, b = blockIdx.z;
-    const int q_base = q_tile * (QG * 32 * QB) + qg * (32 * QB);
-    const float* part = p.part + ((((size_t)b * p.H + head) * p.q_tiles + q_tile) * p.splits) *
-                                     (size_t)(SLOTS * (QG * 64)) + qg * 64 + lane;
-    const size_t sstride = (size_t)SLOTS * (QG * 64);
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        float m = -INFINITY;
-        for (int s = 0; s < p.splits; ++s) m = fmaxf(m, part[s * sstride + qb * (QG * 64)]);
-        float l = 0.f;
-        float o[DB * 16];
-#pragma unroll
-        for (int i = 0; i < DB * 16; ++i) o[i] = 0.f;
-        for (int s = 0; s < p.splits; ++s) {
-            const float* ps = part + s * sstride;
-            const float w = __builtin_amdgcn_exp2f(ps[qb * (QG * 64)] - m);
-            l += w * ps[(QB + qb) * (QG * 64)];
-            float v[DB * 16];
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) v[db * 16 + r] = ps[(2 * QB + (db * QB + qb) * 16 + r) * (QG * 64)];
-#pragma unroll
-            for (int i = 0; i < DB * 16; ++i) o[i] += w * v[i];
-        }
-        const float inv = 1.0f / l;
-        const int qrow = q_base + qb * 32 + li;
-        if (qrow < p.k_tokens) {
-            bf16_t* dst = p.o + ((size_t)b * p.k_tokens + qrow) * p.D + head * DH + 4 * hf;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    u32x2_t pk;
-                    pk.x = pack_bf16x2(o[db * 16 + 4 * g + 0] * inv, o[db * 16 + 4 * g + 1] * inv);
-                    pk.y = pack_bf16x2(o[db * 16 + 4 * g + 2] * inv, o[db * 16 + 4 * g + 3] * inv);
-                    *reinterpret_cast<u32x2_t*>(dst + db * 32 + 8 * g) = pk;
-                }
-        }
-    }
-}
-
 template <int DH, int QG, int KSPLIT>
 void launch_pipe(const AttnParams& p, int B, hipStream_t stream) {
     constexpr size_t tile_bytes = (size_t)2 * (64 * KSPLIT * (DH / 8) + DH * (8 * KSPLIT)) * 16;
@@ -1092,7 +1116,7 @@ void launch_pipe(const AttnParams& p, int B, hipStream_t stream) {
         <<<dim3((p.k_tokens + per_wg - 1) / per_wg, p.H, B), QG * KSPLIT * 64, smem, stream>>>(p);
 }
 
-// the pipelined kernel with the key range split between `p.splits` workgroups per query tile, then the merge
+// the pipelined kernel with the key range split between `p.splits` workgroups per query tile
 template <int DH, int QG, int KSPLIT>
 void launch_pipe_split(const AttnParams& p, int B, hipStream_t stream) {
     constexpr size_t tile_bytes = (size_t)2 * (64 * KSPLIT * (DH / 8) + DH * (8 * KSPLIT)) * 16;
@@ -1106,7 +1130,6 @@ void launch_pipe_split(const AttnParams& p, int B, hipStream_t stream) {
     }
     attention_pipe_kernel<DH, QG, KSPLIT, true>
         <<<dim3(p.q_tiles * p.splits, p.H, B), QG * KSPLIT * 64, smem, stream>>>(p);
-    attention_merge_kernel<DH, QG><<<dim3(p.q_tiles, p.H, B), QG * 64, 0, stream>>>(p);
 }
 
 template <int DH, int QB, int QG, int KSPLIT>
@@ -1125,6 +1148,16 @@ void launch_cfg(const AttnParams& p, int B, hipStream_t stream) {
         <<<dim3((p.k_tokens + per_wg - 1) / per_wg, p.H, B), QG * KSPLIT * 64, smem, stream>>>(p);
 }
 
+// Developer knob: FASTVAR_ATTN_WIDE=0 turns the 256-query / two-range variant off.
+bool attn_wide_enabled() {
+    static int v = -1;
+    if (v < 0) {
+        const char* e = getenv("FASTVAR_ATTN_WIDE");
+        v = e ? atoi(e) : 1;
+    }
+    return v != 0;
+}
+
 int attn_cfg_override() {
     static int v = -2;
     if (v == -2) {
@@ -1137,20 +1170,40 @@ int attn_cfg_override() {
 }  // namespace
 
 AttnSplitPlan attention_split_plan(int B, int H, int dh, int k_tokens, int L) {
-    AttnSplitPlan sp{1, 0, 0};
+    AttnSplitPlan sp{1, 0, false, 0, 0, 0};
     if (dh != 128 || L <= 256) return sp;
-    const long q_tiles = (k_tokens + 127) / 128;
-    const long wg128 = q_tiles * H * B;
-    if (wg128 >= 192) return sp;
-    int s = (int)(256 / wg128);
-    if (s > 4) s = 4;
-    for (; s > 1; --s) {
-        const int per = (((L + s - 1) / s) + 127) / 128 * 128;   // whole key tiles
-        if (per > 256 && L - (s - 1) * per > 256) {               // every range has at least three tiles
-            sp.splits = s;
-            sp.keys_per_split = per;
-            sp.bytes = (size_t)wg128 * s * (2 * 2 + 4 * 2 * 16) * 128 * sizeof(float);
-            return sp;
+    const long wg128 = (long)((k_tokens + 127) / 128) * H * B;
+    const long wg256 = (long)((k_tokens + 255) / 256) * H * B;
+    const size_t per_query_row = (size_t)(2 * 2 + 4 * 2 * 16) * 64 * sizeof(float);   // per wave of 64 queries
+    auto ranges_ok = [&](int s, int bn, int& per) {
+        per = (((L + s - 1) / s) + bn - 1) / bn * bn;          // whole key tiles
+        return per > 2 * bn && L - (s - 1) * per > 2 * bn;     // every range has at least three tiles
+    };
+    if (wg128 < 192) {
+        // too few queries to fill the chip: 128-query workgroups on 2-4 key ranges
+        int s = (int)(256 / wg128);
+        if (s > 4) s = 4;
+        for (; s > 1; --s) {
+            int per;
+            if (ranges_ok(s, 128, per)) {
+                sp.splits = s; sp.keys_per_split = per;
+                sp.counters = (int)wg128;
+                sp.counter_bytes = ((size_t)wg128 * 4 + 255) & ~(size_t)255;
+                sp.bytes = sp.counter_bytes + (size_t)wg128 * s * 2 * per_query_row;
+                return sp;
+            }
+        }
+        return sp;
+    }
+    if (wg256 * 2 <= 256 && wg256 * 2 >= 224 && attn_wide_enabled()) {
+        // exactly one round of 256-query workgroups on two key ranges: the wider workgroup moves half the
+        // K / V bytes per MFMA, which outweighs writing and merging the partial outputs
+        int per;
+        if (ranges_ok(2, 64, per)) {
+            sp.splits = 2; sp.keys_per_split = per; sp.wide = true;
+            sp.counters = (int)wg256;
+            sp.counter_bytes = ((size_t)wg256 * 4 + 255) & ~(size_t)255;
+            sp.bytes = sp.counter_bytes + (size_t)wg256 * 2 * 4 * per_query_row;
         }
     }
     return sp;
@@ -1164,13 +1217,19 @@ void launch_attention(const AttnArgs& a, hipStream_t stream) {
     p.o = static_cast<bf16_t*>(a.o);
     p.H = a.H; p.k_tokens = a.k_tokens; p.L = a.L; p.L_cap = a.L_cap; p.D = a.H * a.dh;
     p.scale_log2e = a.scale * 1.4426950408889634f;
-    p.q_tiles = (a.k_tokens + 127) / 128; p.splits = 1; p.keys_per_split = 0; p.part = nullptr;
+    p.q_tiles = (a.k_tokens + 127) / 128; p.splits = 1; p.keys_per_split = 0; p.part = nullptr; p.split_cnt = nullptr;
     if (a.split_ws && attn_cfg_override() < 0) {
         const AttnSplitPlan sp = attention_split_plan(a.B, a.H, a.dh, a.k_tokens, a.L);
         if (sp.splits > 1) {
             p.splits = sp.splits; p.keys_per_split = sp.keys_per_split;
-            p.part = static_cast<float*>(a.split_ws);
-            launch_pipe_split<128, 2, 2>(p, a.B, stream);
+            p.split_cnt = static_cast<int*>(a.split_ws);
+            p.part = reinterpret_cast<float*>(static_cast<char*>(a.split_ws) + sp.counter_bytes);
+            if (sp.wide) {
+                p.q_tiles = (a.k_tokens + 255) / 256;
+                launch_pipe_split<128, 4, 1>(p, a.B, stream);
+            } else {
+                launch_pipe_split<128, 2, 2>(p, a.B, stream);
+            }
             return;
         }
     }

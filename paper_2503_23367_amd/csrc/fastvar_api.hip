@@ -17,7 +17,7 @@ constexpr int kMaxWidth = 8192;  // LayerNorm keeps a row in registers; score ke
 
 struct BlockPlan {
     size_t off_a, off_q, off_h1, off_u, off_rows, off_asplit, asplit_bytes, off_sk, sk_bytes, bytes;
-    int sk_counters;
+    int sk_counters, asplit_counters;
 };
 
 BlockPlan block_plan(const fastvar_dims* d, int B, int k) {
@@ -33,9 +33,15 @@ BlockPlan block_plan(const fastvar_dims* d, int B, int k) {
     // sized for the longest cache the capacity check allows is not known here: the plan is taken
     // for the worst case over L (the scratch does not depend on L, only on B, H and k)
     p.asplit_bytes = 0;
+    p.asplit_counters = 0;
     if (d->dh == 128 && k > 0) {
         const long wg128 = (long)((k + 127) / 128) * d->H * B;
-        if (wg128 < 192) p.asplit_bytes = (size_t)wg128 * 4 * (2 * 2 + 4 * 2 * 16) * 128 * sizeof(float);
+        const long wg256 = (long)((k + 255) / 256) * d->H * B;
+        const size_t per_wg128 = (size_t)(2 * 2 + 4 * 2 * 16) * 128 * sizeof(float);
+        const size_t cnt_bytes = round256((size_t)wg128 * 4);                        // arrival counters first
+        if (wg128 < 192) p.asplit_bytes = cnt_bytes + (size_t)wg128 * 4 * per_wg128;              // up to four key ranges
+        else if (wg256 * 2 <= 256) p.asplit_bytes = cnt_bytes + (size_t)wg256 * 2 * 2 * per_wg128;   // two, 256-query tiles
+        p.asplit_counters = p.asplit_bytes ? (int)wg128 : 0;
     }
     p.off_asplit = off; off += round256(p.asplit_bytes);
     // split-K scratch of the GEMMs (only shapes with few output tiles have any): one area, the
@@ -232,13 +238,16 @@ void enqueue_ffn(const void* src, int N, const int32_t* idx, int B, int k, const
 
 // `scatter`: y is the [B, N, D] output map and the kept tokens' outputs go straight to their own rows
 // (the row list written by the gather of the attention half is still in the plan when FC2 runs).
-// The arrival counters of the split-K scratch must be zero before the first GEMM that uses them; every
-// such GEMM leaves them zero again, so once per entry-point call is enough.
+// The arrival counters of the split-K scratch (GEMM) and of the key-range split (attention) must be zero
+// before the first kernel that uses them; every such kernel leaves them zero again, so once per
+// entry-point call is enough.
 void zero_splitk_counters(void* ws, const fastvar_dims* d, int B, int k, hipStream_t st) {
     if (k <= 0) return;
     const BlockPlan bp = block_plan(d, B, k);
     if (bp.sk_bytes)
         fv::launch_zero_i32(reinterpret_cast<int32_t*>(static_cast<char*>(ws) + bp.off_sk), bp.sk_counters, st);
+    if (bp.asplit_bytes)
+        fv::launch_zero_i32(reinterpret_cast<int32_t*>(static_cast<char*>(ws) + bp.off_asplit), bp.asplit_counters, st);
 }
 
 void enqueue_block(const void* x, int N, const int32_t* idx, int B, int k, const fastvar_dims* d,

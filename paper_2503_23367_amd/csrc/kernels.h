@@ -107,12 +107,16 @@ void launch_attention(const AttnArgs& a, hipStream_t stream);
 
 // Key-range split for attention shapes that give fewer than 192 workgroups of 128 queries: `splits`
 // workgroups per query tile each take `keys_per_split` keys (a multiple of the key tile) and leave
-// unnormalised partial outputs with their softmax statistics in scratch; a second kernel merges them
-// (softmax partials combine exactly).  splits == 1: no scratch, no second kernel.
+// unnormalised partial outputs with their softmax statistics in scratch; the workgroup that finishes a
+// query tile last merges them (softmax partials combine exactly; it adds them in range order, so the
+// result does not depend on who was last).  splits == 1: no scratch.
 struct AttnSplitPlan {
     int splits;
     int keys_per_split;
-    size_t bytes;
+    bool wide;      // 256-query workgroups (else 128-query ones)
+    int counters;          // arrival counters at the head of the scratch (zero on entry, zero again on exit)
+    size_t counter_bytes;
+    size_t bytes;          // counters + partial results
 };
 AttnSplitPlan attention_split_plan(int B, int H, int dh, int k_tokens, int L);
 

@@ -14,8 +14,9 @@ path and imports nothing from it.
 Pins (tests/test_oracle_*.py): brute-force loops and exhaustive sorts on tiny
 maps, closed forms (variance identity, shift invariance, constant maps,
 half-pixel bilinear weights), keep-ratio 1.0 == dense block, library routines
-of torch-CPU for LayerNorm / attention / GELU / bilinear interpolation, and a
-hand-worked fixture under tests/golden/.  The paper prints no worked numeric
+of torch-CPU for LayerNorm / attention / GELU / bilinear interpolation, a
+hand-worked fixture under tests/golden/, and for the schedule the paper's own
+settings (Sec. 4.1) written out by hand.  The paper prints no worked numeric
 example of a whole step, so `step` as a composition is pinned only through its
 parts: whole-step values are "parity unpinned" against the paper itself.
 
@@ -24,7 +25,10 @@ design notes):
   * score is the squared L2 distance (Alg. 1) -- same ordering as Eq. 5's norm;
   * the top-k decision is taken on the score rounded to fp32, ties go to the
     lowest token index, the index set is emitted ascending;
-  * `interpolate` is bilinear with half-pixel centres, edges clamped;
+  * `interpolate` is bilinear with half-pixel centres, edges clamped, in Eq. 6 and
+    in Eq. 2 alike; Eq. 2 is taken as the definition of the intermediate prediction
+    and Eq. 3 as its unfolding, exact only where resampling composes (bilinear
+    resampling in two hops is not one hop, so the two differ in general);
   * `step` puts one select/restore pair around the whole block;
     `step_sublayer` is the finer wiring of Fig. 2(b), one pair around the
     attention layer and one around the FFN layer, each with its own cached map;
@@ -355,3 +359,60 @@ def scale_step(x, h, w, k, layers, H, k_caches, v_caches, cache_maps, hc, wc, st
             captured.append(y)
         cur = y
     return dict(y=cur, k_caches=new_k, v_caches=new_v, captured=captured, idx=idx)
+
+
+# ---------------------------------------------------------------------------
+# Around the scale step: pruning schedule (Sec. 3.3 overview, Sec. 4.1) and the
+# intermediate prediction (Sec. 3.1, Eq. 2, Eq. 3)
+# ---------------------------------------------------------------------------
+
+def schedule_plan(sizes, prune_ratios):
+    """Which steps are pruned, how many tokens each keeps, and which step is cached.
+
+    sizes: [(h_1, w_1) .. (h_K, w_K)]; prune_ratios: the N ratios of the last N steps,
+    in step order (Sec. 4.1: e.g. 40, 50, 100, 100 % with N = 4, or 50, 75 % with N = 2).
+    The first K-N steps are the structure stage and keep everything; the per-block
+    outputs of the last of them (step K-N, index K-N-1 counted from 0) are what the
+    texture steps restore from.  A ratio of 100 % keeps nothing: the step is skipped.
+    Returns (keep counts [K], structure flags [K], cached step index or -1 when N == 0
+    or N == K).
+    """
+    K, n = len(sizes), len(prune_ratios)
+    assert 0 <= n <= K
+    keep, structure = [], []
+    for i, (h, w) in enumerate(sizes):
+        if i < K - n:
+            keep.append(h * w)
+            structure.append(True)
+        else:
+            keep.append(keep_count(h * w, 1.0 - float(prune_ratios[i - (K - n)])))
+            structure.append(False)
+    cached = K - n - 1 if 0 < n < K else -1
+    return keep, structure, cached
+
+
+def residual_accumulate(r_prev: Optional[np.ndarray], hp: int, wp: int,
+                        f_k: Optional[np.ndarray], h: int, w: int) -> np.ndarray:
+    """Eq. 2: r_k = interpolate(r_{k-1}, (h, w)) + f_k, maps as [B, h*w, C], fp64.
+
+    r_prev None: the first step, r_1 = f_1.  f_k None: a skipped step (ratio 100 %),
+    whose output is the interpolation of the previous intermediate prediction alone.
+    `interpolate` is the same bilinear resampling as in Eq. 6 (the paper names no mode).
+    """
+    if r_prev is None:
+        assert f_k is not None
+        return np.asarray(f_k, F64).copy()
+    up = upsample_bilinear(r_prev, hp, wp, h, w)
+    return up if f_k is None else up + np.asarray(f_k, F64)
+
+
+def cumulative_prediction(fs, sizes, k: int) -> np.ndarray:
+    """Eq. 3: r_k = sum_{i<=k} interpolate(f_i, (h_k, w_k)) (k counted from 1)."""
+    h, w = sizes[k - 1]
+    out = None
+    for i in range(k):
+        hi, wi = sizes[i]
+        t = upsample_bilinear(fs[i], hi, wi, h, w)
+        out = t if out is None else out + t
+    return out
+

@@ -120,6 +120,27 @@ size_t fastvar_select_workspace_bytes(int B, int N, int D);
 /* Scratch bytes needed by fastvar_block_forward_pruned for B*k kept tokens. */
 size_t fastvar_block_workspace_bytes(const fastvar_dims* dims, int B, int k);
 
+/*
+ * The pruning schedule as keep counts (Sec. 3.3, overview: the first K-N steps
+ * are the structure construction stage and stay unpruned, the per-block
+ * outputs of step K-N are cached, the last N steps are pruned; Sec. 4.1: the
+ * N progressive pruning ratios, e.g. 40, 50, 100, 100 % or 50, 75 %).  Host
+ * function, all pointers host.
+ *   sched_h, sched_w  [K] the scale schedule
+ *   prune_ratio       [n_pruned] fraction of tokens dropped at each of the last
+ *                     n_pruned steps, in step order, each in [0, 1]; 1 drops
+ *                     every token (the step is skipped: k = 0)
+ *   keep_out          [K] tokens kept per step: h*w for the first K-n_pruned
+ *                     steps, fastvar_keep_count(h*w, 1 - ratio) after
+ *   cache_step_out    index (from 0) of the cached step, K-n_pruned-1: the
+ *                     cache_step argument of the step entry points; -1 when
+ *                     n_pruned == 0 (nothing is restored, nothing to cache)
+ * FASTVAR_EINVAL: null pointer, K <= 0, a non-positive or too large scale, a
+ * ratio outside [0, 1], n_pruned < 0 or n_pruned >= K (no step left to cache).
+ */
+int fastvar_schedule_plan(const int32_t* sched_h, const int32_t* sched_w, int K, const double* prune_ratio,
+                          int n_pruned, int32_t* keep_out, int32_t* cache_step_out);
+
 /* Scratch bytes needed by fastvar_restore when `rank` is NULL (else 0). */
 size_t fastvar_restore_workspace_bytes(int B, int N);
 
@@ -193,6 +214,24 @@ int fastvar_restore(const void* y_kept, const int32_t* idx, const int32_t* rank,
                     void* y_out, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Intermediate prediction of the next-scale recursion (Sec. 3.1, Eq. 2):
+ * r_out = interpolate(r_prev, (h, w)) + f_k.
+ *   r_prev   [B, hp*wp, C] fp32  prediction after the previous step; NULL at
+ *                                the first step (then r_out = f_k)
+ *   f_k      [B, h*w, C] bf16    the model's output at this step (the residual);
+ *                                NULL for a skipped step (pruning ratio 100 %,
+ *                                Sec. 4.1: the previous prediction is only
+ *                                interpolated to the new size)
+ *   r_out    [B, h*w, C] fp32    must not alias r_prev
+ * `interpolate` is the bilinear resampling of Eq. 6 (half-pixel centres, edges
+ * clamped); the sum is kept in fp32 so that thirteen steps of it do not round
+ * thirteen times to bf16.  C % 4 == 0; all pointers device, 16-byte aligned.
+ * r_prev and f_k both NULL is FASTVAR_EINVAL.
+ */
+int fastvar_residual_accumulate(const float* r_prev, int hp, int wp, const void* f_k, int h, int w, int B, int C,
+                                float* r_out, void* stream);
+
+/*
  * One whole step for one block: selection, block on kept tokens, restoration
  * (Fig. 2(b) at block granularity).
  *   sched_h, sched_w  host int arrays of length K: the scale schedule
@@ -230,8 +269,9 @@ int fastvar_step(const void* x, const int32_t* sched_h /* host */, const int32_t
  *   idx_out             [B, k] int32: kept indices of the last block (may be
  *                       NULL when k == h*w)
  *   ws                  scratch of fastvar_step_workspace_bytes(dims, B, h*w, k)
- * The token maps of different scales come from the tokenizer and the residual
- * accumulation of Eq. 2-3, which are outside this library: the caller supplies x.
+ * The token map of a scale is derived from the intermediate prediction
+ * (fastvar_residual_accumulate) by the model's tokenizer and embedding, which are
+ * outside this library: the caller supplies x.
  */
 int fastvar_scale_step(const void* x, const int32_t* sched_h /* host */, const int32_t* sched_w /* host */,
                        int K, int step, int cache_step, int B, int k,

@@ -48,7 +48,8 @@ class Layer(C.Structure):
 
 _lib = None
 
-EXPORTS = ("fastvar_version", "fastvar_strerror", "fastvar_keep_count",
+EXPORTS = ("fastvar_version", "fastvar_strerror", "fastvar_keep_count", "fastvar_schedule_plan",
+           "fastvar_residual_accumulate",
            "fastvar_select_workspace_bytes", "fastvar_block_workspace_bytes",
            "fastvar_restore_workspace_bytes", "fastvar_step_workspace_bytes",
            "fastvar_select_pivotal", "fastvar_block_forward_pruned", "fastvar_restore",
@@ -87,6 +88,11 @@ def lib() -> C.CDLL:
     L.fastvar_block_forward_pruned.restype = i32
     L.fastvar_block_forward_pruned.argtypes = [vp, i32, vp, i32, i32, C.POINTER(Dims),
                                                C.POINTER(BlockWeights), vp, vp, i32, i32, vp, vp, sz, vp]
+    L.fastvar_schedule_plan.restype = i32
+    L.fastvar_schedule_plan.argtypes = [C.POINTER(C.c_int32), C.POINTER(C.c_int32), i32, C.POINTER(C.c_double), i32,
+                                        C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+    L.fastvar_residual_accumulate.restype = i32
+    L.fastvar_residual_accumulate.argtypes = [vp, i32, i32, vp, i32, i32, i32, i32, vp, vp]
     L.fastvar_restore.restype = i32
     L.fastvar_restore.argtypes = [vp, vp, vp, i32, i32, vp, i32, i32, i32, i32, i32, vp, vp, sz, vp]
     L.fastvar_step.restype = i32
@@ -178,6 +184,24 @@ def fastvar_select_workspace_bytes(B: int, N: int, D: int) -> int:
 
 def fastvar_block_workspace_bytes(dims: Dims, B: int, k: int) -> int:
     return lib().fastvar_block_workspace_bytes(C.byref(dims), B, k)
+
+
+def fastvar_schedule_plan(sched_h, sched_w, prune_ratio):
+    """Host call: returns (keep counts per step, cached step index or -1)."""
+    K, n = len(sched_h), len(prune_ratio)
+    hs = (C.c_int32 * K)(*sched_h)
+    ws_ = (C.c_int32 * K)(*sched_w)
+    pr = (C.c_double * max(n, 1))(*prune_ratio)
+    keep = (C.c_int32 * K)()
+    cached = C.c_int32(-2)
+    rc = lib().fastvar_schedule_plan(hs, ws_, K, pr if n else None, n, keep, C.byref(cached))
+    _check(rc, "fastvar_schedule_plan")
+    return list(keep), cached.value
+
+
+def fastvar_residual_accumulate(r_prev, hp, wp, f_k, h, w, B, Cc, r_out) -> None:
+    rc = lib().fastvar_residual_accumulate(_ptr(r_prev), hp, wp, _ptr(f_k), h, w, B, Cc, _ptr(r_out), _stream())
+    _check(rc, "fastvar_residual_accumulate")
 
 
 def fastvar_restore_workspace_bytes(B: int, N: int) -> int:

@@ -299,6 +299,24 @@ int fastvar_keep_count(int N, double keep_ratio) {
     return (int)v;
 }
 
+int fastvar_schedule_plan(const int32_t* sched_h, const int32_t* sched_w, int K, const double* prune_ratio,
+                          int n_pruned, int32_t* keep_out, int32_t* cache_step_out) {
+    if (!sched_h || !sched_w || !keep_out || !cache_step_out || K <= 0) return FASTVAR_EINVAL;
+    if (n_pruned < 0 || n_pruned >= K || (n_pruned > 0 && !prune_ratio)) return FASTVAR_EINVAL;
+    for (int i = 0; i < K; ++i)
+        if (sched_h[i] <= 0 || sched_w[i] <= 0 || (long)sched_h[i] * sched_w[i] > FASTVAR_MAX_TOKENS)
+            return FASTVAR_EINVAL;
+    for (int j = 0; j < n_pruned; ++j)
+        if (!(prune_ratio[j] >= 0.0 && prune_ratio[j] <= 1.0)) return FASTVAR_EINVAL;
+    const int first_pruned = K - n_pruned;
+    for (int i = 0; i < K; ++i) {
+        const int N = sched_h[i] * sched_w[i];
+        keep_out[i] = i < first_pruned ? N : fastvar_keep_count(N, 1.0 - prune_ratio[i - first_pruned]);
+    }
+    *cache_step_out = n_pruned > 0 ? first_pruned - 1 : -1;
+    return FASTVAR_OK;
+}
+
 size_t fastvar_select_workspace_bytes(int B, int N, int D) {
     if (B <= 0 || N <= 0 || D <= 0) return 0;
     return fv::select_plan(B, N, D).bytes;
@@ -357,6 +375,18 @@ int fastvar_restore(const void* y_kept, const int32_t* idx, const int32_t* rank,
         rank = rebuilt;
     }
     fv::launch_restore(y_kept, rank, B, k, cache_map, hc, wc, h, w, D, y_out, st);
+    return launch_status();
+}
+
+int fastvar_residual_accumulate(const float* r_prev, int hp, int wp, const void* f_k, int h, int w, int B, int C,
+                                float* r_out, void* stream) {
+    if (!r_out || (!r_prev && !f_k) || B <= 0 || h <= 0 || w <= 0 || C <= 0) return FASTVAR_EINVAL;
+    if (r_prev && (hp <= 0 || wp <= 0)) return FASTVAR_EINVAL;
+    if ((long)h * w > FASTVAR_MAX_TOKENS || (r_prev && (long)hp * wp > FASTVAR_MAX_TOKENS)) return FASTVAR_ECAPACITY;
+    if (C % 4 != 0 || !aligned16(r_out) || (r_prev && !aligned16(r_prev)) || (f_k && !aligned16(f_k)))
+        return FASTVAR_EALIGN;
+    if (r_out == r_prev) return FASTVAR_EINVAL;
+    fv::launch_residual_accumulate(r_prev, hp, wp, f_k, h, w, B, C, r_out, static_cast<hipStream_t>(stream));
     return launch_status();
 }
 

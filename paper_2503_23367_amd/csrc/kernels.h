@@ -38,6 +38,11 @@ void launch_restore_colsum(const void* y_kept, const int32_t* rank, int B, int k
                            int hc, int wc, int h, int w, int D, void* y_out, void* select_ws,
                            const SelectPlan& plan, hipStream_t stream);
 
+// Eq. 2 on fp32 maps [B, h*w, C] (C % 4 == 0): r_out = resample(r_prev [B, hp*wp, C]) + f_k (bf16).
+// r_prev or f_k may be null (not both).
+void launch_residual_accumulate(const float* r_prev, int hp, int wp, const void* f_k, int h, int w, int B, int C,
+                                float* r_out, hipStream_t stream);
+
 // ---- block pieces ----
 // xk = x[idx] (optional copy out) and a = LayerNorm(xk); one wave per row.
 // rows_out (optional, int32 [B*k]) receives the absolute source row b*N + idx[m] of

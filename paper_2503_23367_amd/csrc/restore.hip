@@ -215,6 +215,47 @@ __global__ __launch_bounds__(256) void restore_colsum_kernel(const bf16_t* __res
     }
 }
 
+// Intermediate prediction (Sec. 3.1, Eq. 2): r_k = interpolate(r_{k-1}, (h, w)) + f_k on fp32 maps of C
+// channels.  One thread per four channels of one position; either term may be absent (first step: no
+// previous map; skipped step: no residual).  HBM bound: reads 4 taps (neighbouring threads share them
+// through the cache) and 8 bytes of residual, writes 16 bytes.
+__global__ __launch_bounds__(256) void residual_accumulate_kernel(const float* __restrict__ r_prev, int hp, int wp,
+                                                                  const bf16_t* __restrict__ f_k, int h, int w, int C,
+                                                                  float* __restrict__ r_out, long total) {
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int c4 = C >> 2;
+    const int c = (int)(i % c4) << 2;
+    const long t = i / c4;
+    const int N = h * w;
+    const int n = (int)(t % N);
+    const long b = t / N;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (r_prev) {
+        int i0, i1, j0, j1;
+        float lr, lc;
+        axis_taps(n / w, hp, h, i0, i1, lr);
+        axis_taps(n % w, wp, w, j0, j1, lc);
+        const float* pb = r_prev + (size_t)b * hp * wp * C + c;
+        const float4 c00 = *reinterpret_cast<const float4*>(pb + ((size_t)i0 * wp + j0) * C);
+        const float4 c01 = *reinterpret_cast<const float4*>(pb + ((size_t)i0 * wp + j1) * C);
+        const float4 c10 = *reinterpret_cast<const float4*>(pb + ((size_t)i1 * wp + j0) * C);
+        const float4 c11 = *reinterpret_cast<const float4*>(pb + ((size_t)i1 * wp + j1) * C);
+        acc.x = lerp2(c00.x, c01.x, c10.x, c11.x, lr, lc);
+        acc.y = lerp2(c00.y, c01.y, c10.y, c11.y, lr, lc);
+        acc.z = lerp2(c00.z, c01.z, c10.z, c11.z, lr, lc);
+        acc.w = lerp2(c00.w, c01.w, c10.w, c11.w, lr, lc);
+    }
+    if (f_k) {
+        const uint2 v = *reinterpret_cast<const uint2*>(f_k + (size_t)t * C + c);
+        acc.x += bf16_lo(v.x);
+        acc.y += bf16_hi(v.x);
+        acc.z += bf16_lo(v.y);
+        acc.w += bf16_hi(v.y);
+    }
+    *reinterpret_cast<float4*>(r_out + (size_t)t * C + c) = acc;
+}
+
 }  // namespace
 
 void launch_rank_from_idx(const int32_t* idx, int32_t* rank, int B, int N, int k, hipStream_t stream) {
@@ -237,6 +278,15 @@ void launch_restore_colsum(const void* y_kept, const int32_t* rank, int B, int k
     restore_colsum_kernel<<<dim3(plan.col_tiles, plan.n_chunks, B), 256, 0, stream>>>(
         static_cast<const bf16_t*>(y_kept), rank, k, static_cast<const bf16_t*>(cache_map), hc, wc, h, w, D,
         static_cast<bf16_t*>(y_out), partial, plan.rows_per_chunk, plan.n_chunks);
+}
+
+void launch_residual_accumulate(const float* r_prev, int hp, int wp, const void* f_k, int h, int w, int B, int C,
+                                float* r_out, hipStream_t stream) {
+    const long total = (long)B * h * w * (C / 4);
+    if (total == 0) return;
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    residual_accumulate_kernel<<<blocks, 256, 0, stream>>>(r_prev, hp, wp, static_cast<const bf16_t*>(f_k), h, w, C,
+                                                           r_out, total);
 }
 
 }  // namespace fv

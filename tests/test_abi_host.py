@@ -46,6 +46,26 @@ def test_keep_count_agrees_with_oracle_reading():
     assert fb.fastvar_keep_count(-1, 0.5) == fb.FASTVAR_EINVAL
 
 
+def test_schedule_plan_agrees_with_oracle_and_rejects_bad_schedules():
+    sides = (1, 2, 4, 6, 8, 12, 16, 20, 24, 32, 40, 48, 64)
+    cases = [(sides, sides, (0.4, 0.5, 1.0, 1.0)), (sides, sides, (0.5, 0.75)), (sides, sides, ()),
+             ((1, 2, 4, 8, 16), (1, 3, 6, 12, 24), (0.5, 0.75)), ((5, 5), (5, 5), (0.5,)),
+             ((3, 7, 9, 11), (2, 5, 9, 13), (0.0, 0.33, 0.999))]
+    for hs, ws, pr in cases:
+        keep, cached = fb.fastvar_schedule_plan(hs, ws, pr)
+        want_keep, _, want_cached = O.schedule_plan(list(zip(hs, ws)), pr)
+        assert keep == want_keep and cached == want_cached, (hs, ws, pr)
+    # the paper's thirteen-step setting: the cached step is the 24x24 one, the last two steps are skipped
+    keep, cached = fb.fastvar_schedule_plan(sides, sides, (0.4, 0.5, 1.0, 1.0))
+    assert cached == 8 and keep[9:] == [614, 800, 0, 0]
+    for hs, ws, pr in [((2, 4), (2, 4), (0.5, 0.5)),          # every step pruned: nothing left to cache
+                       ((2, 0), (2, 4), (0.5,)), ((2, 4), (2, 4), (1.5,)), ((2, 4), (2, 4), (-0.1,)),
+                       ((2, 400), (2, 400), (0.5,))]:          # 160000 tokens: beyond the maximum
+        with pytest.raises(fb.FastvarError) as e:
+            fb.fastvar_schedule_plan(hs, ws, pr)
+        assert e.value.code == fb.FASTVAR_EINVAL
+
+
 def test_workspace_sizes_are_monotone_and_cover_stages():
     d = fb.make_dims(2048, 16, 128, 8192)
     s = fb.fastvar_select_workspace_bytes(1, 4096, 2048)

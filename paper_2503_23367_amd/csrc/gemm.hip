@@ -517,15 +517,26 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
             for (int ni = 0; ni < NI; ++ni) {
                 const int nb = n0 + wn * WTN + ni * 32;  // wave-uniform; sections are multiples of 64 wide
                 if (nb >= 2 * p.D && nb < p.N && m < p.M) {
+                    // Head and channel of the block's first column: one (wave-uniform) division per
+                    // block.  When the head dimension is a multiple of 32 the whole block lies in that
+                    // head and a column is just an offset; else each column is divided on its own.
+                    const int f0 = nb - 2 * p.D;
+                    const int hh0 = f0 / p.dh;
+                    const int d0 = f0 - hh0 * p.dh;
+                    const bool one_head = (p.dh & 31) == 0;
+                    bf16_t* const v0 = p.v_cache + (((size_t)b * p.H + hh0) * p.dh + d0) * p.L_cap + p.L0 + t;
 #pragma unroll
                     for (int j = 0; j < 16; ++j) {
                         const int col = frag_half + 2 * j;
-                        const int f = nb + col - 2 * p.D;
-                        const int hh = f / p.dh;
-                        const int d = f - hh * p.dh;
                         const float v = stg[frag_row * SROW + ni * 32 + col];
-                        p.v_cache[(((size_t)b * p.H + hh) * p.dh + d) * p.L_cap + p.L0 + t] =
-                            (bf16_t)f32_to_bf16_bits(v);
+                        bf16_t* dst = v0 + (size_t)col * p.L_cap;
+                        if (!one_head) {
+                            const int f = f0 + col;
+                            const int hh = f / p.dh;
+                            const int d = f - hh * p.dh;
+                            dst = p.v_cache + (((size_t)b * p.H + hh) * p.dh + d) * p.L_cap + p.L0 + t;
+                        }
+                        *dst = (bf16_t)f32_to_bf16_bits(v);
                     }
                 }
             }

@@ -534,7 +534,8 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
 // reads past L_cap, its leading keys (already seen) and the up to 7 positions past L are masked.
 // KVS: the key range is also split between workgroups (consecutive query-tile ids of the grid's x
 // dimension are the same tile's splits); each works on keys [split*keys_per_split, ...) as if they
-// were the whole cache and leaves its unnormalised output and statistics for attention_merge_kernel.
+// were the whole cache and leaves its unnormalised output and statistics for the workgroup that
+// arrives last at the tile, which merges the ranges.
 template <int DH, int QG, int KSPLIT, bool KVS = false>
 __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(const AttnParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
@@ -693,22 +694,24 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
             pw_[((e_) / 16) * 8 + ((e_) % 16) / 2] = pk_;                                           \
         }                                                                                           \
     }
-    // Half-group hh_ (0..31: two per group) starts elements [FP_E0(hh_), FP_E0(hh_+1)).  With the
-    // running maximum the first eight half-groups are busy with the maxima and the 32 elements are
-    // spread 2,1,1,2,... over the other 24; in fast mode every half-group starts exactly one.
-#define FP_E0(RESC_, hh_) \
-    ((hh_) < 0 ? 0 : (RESC_) ? ((hh_) < 8 ? 0 : ((hh_) - 8) + (((hh_) - 8) + 2) / 3) : ((hh_) > 32 ? 32 : (hh_)))
+    // Half-group hh_ (two per group, 2 * NG_ per step) starts elements [FP_E0(hh_), FP_E0(hh_+1)) of the
+    // 32.  With the running maximum the first eight half-groups are busy with the maxima and the
+    // elements are spread over the others (16 groups: 2,1,1,2,...; 8 groups: four each); in fast mode
+    // every half-group starts the same number (one or two).
+#define FP_E0(RESC_, hh_)                                                                           \
+    ((hh_) < 0 ? 0                                                                                  \
+     : (RESC_) ? ((hh_) < 8 ? 0                                                                     \
+                  : NG_ == 16 ? ((hh_) - 8) + (((hh_) - 8) + 2) / 3                                 \
+                              : (((hh_) - 8) * 4 > 32 ? 32 : ((hh_) - 8) * 4))                      \
+               : ((hh_) * (16 / NG_) > 32 ? 32 : (hh_) * (16 / NG_)))
 #define FP_HALF(RESC_, S_, P_, hh_)                                                                 \
     {                                                                                               \
         constexpr int x0_ = FP_E0(RESC_, hh_), x1_ = FP_E0(RESC_, (hh_) + 1);                       \
         constexpr int e0_ = FP_E0(RESC_, (hh_) - 1), e1_ = x0_;                                     \
         constexpr int c0_ = FP_E0(RESC_, (hh_) - 2), c1_ = e0_;                                     \
-        if (x1_ - x0_ >= 1) { FP_ARG(S_, (x1_ - x0_ >= 1 ? x0_ : 0)) }                              \
-        if (x1_ - x0_ == 2) { FP_ARG(S_, (x1_ - x0_ == 2 ? x0_ + 1 : 0)) }                          \
-        if (e1_ - e0_ >= 1) { FP_EXP((e1_ - e0_ >= 1 ? e0_ : 0)) }                                  \
-        if (e1_ - e0_ == 2) { FP_EXP((e1_ - e0_ == 2 ? e0_ + 1 : 0)) }                              \
-        if (c1_ - c0_ >= 1) FP_CONSUME(P_, (c1_ - c0_ >= 1 ? c0_ : 1))                              \
-        if (c1_ - c0_ == 2) FP_CONSUME(P_, (c1_ - c0_ == 2 ? c0_ + 1 : 1))                          \
+        static_for<x0_, x1_>([&](auto e_c) { constexpr int e = decltype(e_c)::value; FP_ARG(S_, e) }); \
+        static_for<e0_, e1_>([&](auto e_c) { constexpr int e = decltype(e_c)::value; FP_EXP(e) });  \
+        static_for<c0_, c1_>([&](auto e_c) { constexpr int e = decltype(e_c)::value; FP_CONSUME(P_, e) }); \
     }
     // One step.  S_SM_/P_SM_: block whose softmax is taken (scores in, probabilities out; first key
     // key0_sm_, MASK_ for blocks of the last tile).  DO_QK_: S_QK_ = K Q^T for the 32 key rows at
@@ -727,7 +730,7 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
     // group g_ of a step (a literal, so that every index below is a compile-time constant)
 #define FP_G(g_, RESC_, S_SM_, P_SM_, key0_sm_, MASK_, DO_QK_, S_QK_, kbase_, DO_PV_, P_PV_, vbase_, vchunk0_, \
              LOAD_K_, ktk_, LOAD_V_, ktv_, FR_, NFR_, N_DO_PV_, nvbase_, nvchunk0_, BAR_)           \
-    {                                                                                               \
+    if constexpr ((g_) < NG_) {                                                                     \
         constexpr int gg = (g_);                                                                    \
         constexpr int f = gg + DEPTH_;      /* operand fragment read in this group */               \
         if ((BAR_) && gg == NG_ - DEPTH_) {                                                         \
@@ -802,11 +805,11 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
     {                                                                                               \
         constexpr int NV_ = 2 * DB;                                                                 \
         constexpr int NG_ = 2 * DB + KS;           /* groups = fragments */                         \
-        static_assert(NG_ == 16, "the group list below is written for 16 groups");                  \
+        static_assert(NG_ == 16 || NG_ == 8, "the group list below is written for 16 or 8 groups"); \
         constexpr int JLO_ = (LOAD_K_) ? 0 : K_LD;                                                  \
         constexpr int JHI_ = (LOAD_V_) ? K_LD + V_LD : K_LD;                                        \
         constexpr int NJ_ = JHI_ > JLO_ ? JHI_ - JLO_ : 0;                                          \
-        constexpr int DEPTH_ = 6;                                                                   \
+        constexpr int DEPTH_ = NV_ < 6 ? NV_ : 6;  /* the fragments read ahead into the next step are V^T ones */ \
         float m_use_[QB], alpha_[QB], lsum_[QB], px_[32], pe_[32], mxa_ = 0.f, mxb_ = 0.f;          \
         uint32_t pw_[16];          /* packed probabilities: [qb][r / 2] */                         \
         _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                         \
@@ -831,9 +834,8 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
         FP_G(14, RESC_, S_SM_, P_SM_, key0_sm_, MASK_, DO_QK_, S_QK_, kbase_, DO_PV_, P_PV_, vbase_, vchunk0_, LOAD_K_, ktk_, LOAD_V_, ktv_, FR_, NFR_, N_DO_PV_, nvbase_, nvchunk0_, BAR_) \
         FP_G(15, RESC_, S_SM_, P_SM_, key0_sm_, MASK_, DO_QK_, S_QK_, kbase_, DO_PV_, P_PV_, vbase_, vchunk0_, LOAD_K_, ktk_, LOAD_V_, ktv_, FR_, NFR_, N_DO_PV_, nvbase_, nvchunk0_, BAR_) \
         /* what the last half-groups left in flight */                                              \
-        FP_EXP(31)                                                                                  \
-        FP_CONSUME(P_SM_, 30)                                                                       \
-        FP_CONSUME(P_SM_, 31)                                                                       \
+        static_for<FP_E0(RESC_, 2 * NG_ - 1), 32>([&](auto e_c) { constexpr int e = decltype(e_c)::value; FP_EXP(e) }); \
+        static_for<FP_E0(RESC_, 2 * NG_ - 2), 32>([&](auto e_c) { constexpr int e = decltype(e_c)::value; FP_CONSUME(P_SM_, e) }); \
         _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                         \
             if (RESC_) l_run[qb] = l_run[qb] * alpha_[qb] + lsum_[qb];                              \
             else l_run[qb] += lsum_[qb];                                                            \
@@ -1250,9 +1252,16 @@ void launch_attention(const AttnArgs& a, hipStream_t stream) {
         if (wg128 < 128) cfg = 3;   // too few queries for half the chip: 64-query workgroups, keys split in two
         else cfg = 1.86 * (double)rounds256 < (double)rounds128 ? 6 : 5;
     }
+    if (a.dh == 64 && a.L >= 1024 && wg256 >= 128 && (a.k_tokens + 255) / 256 * 2 == (a.k_tokens + 127) / 128) {
+        // Head dim 64 is bound by the softmax, not the matrix pipe, and the pipelined kernel gains less:
+        // its 256-query workgroups win (by 5-20 % on 8 x 30 heads, 1024-3072 keys) where they pad the
+        // queries no further than 128-query workgroups would and the key loop is long enough to pay
+        // for the longer prologue; the plain kernel wins elsewhere.
+        cfg = 6;
+    }
     if (attn_cfg_override() >= 0) cfg = attn_cfg_override();
-    // the software-pipelined kernel needs head dim 128 and at least three key tiles
-    if ((cfg == 5 || cfg == 6) && (a.dh != 128 || a.L <= 2 * (cfg == 5 ? 128 : 64))) cfg = 4;
+    // the software-pipelined kernel needs at least three key tiles
+    if ((cfg == 5 || cfg == 6) && a.L <= 2 * (cfg == 5 ? 128 : 64)) cfg = 4;
     if (a.dh == 128) {
         switch (cfg) {
             case 0: launch_cfg<128, 2, 4, 1>(p, a.B, stream); break;
@@ -1269,6 +1278,8 @@ void launch_attention(const AttnArgs& a, hipStream_t stream) {
             case 1: launch_cfg<64, 2, 2, 2>(p, a.B, stream); break;
             case 2: launch_cfg<64, 1, 4, 1>(p, a.B, stream); break;
             case 3: launch_cfg<64, 1, 2, 2>(p, a.B, stream); break;
+            case 5: launch_pipe<64, 2, 2>(p, a.B, stream); break;
+            case 6: launch_pipe<64, 4, 1>(p, a.B, stream); break;
             default: launch_cfg<64, 1, 4, 2>(p, a.B, stream); break;
         }
     }

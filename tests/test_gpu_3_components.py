@@ -124,6 +124,13 @@ ATT_CASES = [
     (16, 128, 1, 1024, 384, 384), (16, 128, 1, 1000, 385, 392), (16, 128, 1, 1024, 1001, 1008),
     (16, 128, 2, 520, 1023, 1024),
     (16, 128, 2, 2048, 200, 200),    # 256-query workgroups, four 64-key tiles, the last one shifted
+    # head dim 64 with 256-query workgroups of the pipelined kernel (eight groups per step instead of
+    # sixteen; chosen from 1024 keys on, where 256-query tiles pad no further than 128-query ones):
+    # whole tiles, tails of 1 and 7 keys, ragged query counts
+    (16, 64, 8, 256, 1024, 1024), (16, 64, 4, 410, 1025, 1032), (16, 64, 2, 1000, 1031, 1032),
+    (30, 64, 8, 410, 1626, 1632),    # the 512 px model's 32x32 step at full size
+    # head dim 64, same shapes just outside that rule: the plain kernel
+    (16, 64, 2, 520, 1023, 1024), (16, 64, 4, 346, 1025, 1032), (16, 64, 1, 4096, 300, 304),
 ]
 
 
@@ -146,20 +153,22 @@ def test_attention_matches_oracle(H, dh, B, k, L, L_cap):
         assert max_rel(got[b], ref) <= TOL, (b,)
 
 
-def test_attention_scores_rising_far_above_the_first_tile():
+@pytest.mark.parametrize("dh,k,L", [(128, 1024, 900), (64, 2048, 1100)])
+def test_attention_scores_rising_far_above_the_first_tile(dh, k, L):
     """Keys late in the sequence score hundreds of octaves above the first tile's maximum: the
     pipelined kernel's fixed softmax reference overflows and it must fall back to the running maximum."""
-    print("[attention] rising scores", flush=True)
-    H, dh, B, k, L = 16, 128, 1, 1024, 900
+    print(f"[attention] rising scores dh={dh} k={k} L={L}", flush=True)
+    H, B = 16, 1
     D = H * dh
     rng = np.random.default_rng(11)
     q = rnd(rng, B, k, H, dh)
     K, V = rnd(rng, B, L, H, dh), rnd(rng, B, L, H, dh)
     K[:, 600:] *= 64.0          # a power of two keeps the values bf16; scores reach several hundred
-    kc, vc = make_caches(K, V, 904)
+    L_cap = (L + 7) // 8 * 8
+    kc, vc = make_caches(K, V, L_cap)
     o = torch.full((B, k, D), float("nan"), dtype=torch.bfloat16, device=DEV)
     d = fb.make_dims(D, H, dh, 4 * D)
-    fb.fastvar_attention(to_dev_bf16(q.reshape(B, k, D)), kc, vc, B, k, d, L, 904, o)
+    fb.fastvar_attention(to_dev_bf16(q.reshape(B, k, D)), kc, vc, B, k, d, L, L_cap, o)
     got = from_dev_bf16(o).reshape(B, k, H, dh)
     assert not np.isnan(got).any()
     ref = O.attention(q[0].astype(np.float64), K[0].astype(np.float64), V[0].astype(np.float64), dh ** -0.5)

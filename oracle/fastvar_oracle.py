@@ -153,6 +153,8 @@ def attention(q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: float) -> np.n
     """
     M, H, dh = q.shape
     out = np.empty((M, H, dh), dtype=F64)
+    if M == 0:          # no queries (a skipped step): nothing to compute, also with no keys
+        return out
     for h in range(H):
         s = (q[:, h, :] @ K[:, h, :].T) * scale          # [M, L]
         s = s - s.max(axis=-1, keepdims=True)

@@ -652,11 +652,15 @@ SplitKPlan gemm_splitk_plan(int M, int N, int K) {
     const int KT = K / 64;
     const int min_kt = sk.small_tiles ? 2 : 4;   // K tiles a slice must keep
     // a short K range is over before the slices' summing would pay for itself
+    static_assert(kSplitKMaxTiles >= 128 && (kSplitKMaxTiles * 4) % 256 == 0, "covers both tile-count limits below");
     if (K >= 2048 && sk.tiles <= (sk.small_tiles ? 128 : 96))
         while (sk.splits < (sk.small_tiles ? 8 : 4) && sk.tiles * sk.splits * 2 <= 256 &&
                KT % (sk.splits * 2) == 0 && KT / (sk.splits * 2) >= min_kt)
             sk.splits *= 2;   // (more slices than that cost more to sum than they save)
-    sk.counter_bytes = sk.splits > 1 ? (((size_t)sk.tiles * 4 + 255) & ~(size_t)255) : 0;
+    // The counter area has one size for every shape (the most tiles the condition above admits): the
+    // GEMMs of a block share one scratch area, and a partial tile of one must never land on a counter
+    // of another.
+    sk.counter_bytes = sk.splits > 1 ? (size_t)kSplitKMaxTiles * 4 : 0;
     sk.bytes = sk.splits > 1 ? sk.counter_bytes + (size_t)sk.tiles * sk.splits * t * t * 4 : 0;
     return sk;
 }

@@ -86,11 +86,12 @@ void launch_gemm(GemmEpilogue epi, const GemmArgs& a, hipStream_t stream);
 // a tile last sums the slices in slice order and runs the epilogue.  Up to 64 rows use 64x64 tiles with
 // an eight-stage ring (a workgroup's whole K slice, or half of it, is in flight at once), more rows
 // 128x128 tiles.  splits == 1: no scratch needed.
+constexpr int kSplitKMaxTiles = 128;   // most output tiles a split-K launch has
 struct SplitKPlan {
     int splits;
     int tiles;
     bool small_tiles;      // 64x64 tiles
-    size_t counter_bytes;  // one int per tile, rounded up
+    size_t counter_bytes;  // kSplitKMaxTiles ints whatever the shape: GEMMs that share a scratch area share the counters
     size_t bytes;          // counters + partial tiles
 };
 SplitKPlan gemm_splitk_plan(int M, int N, int K);

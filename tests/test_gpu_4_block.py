@@ -86,6 +86,16 @@ CASES = [
     ("tiny128_keep_all_tile_edges", TINY128, 1, 16, 16, 256, 128, 384),
     ("d30_s24_b2", synth.D30, 2, 24, 24, 346, 640, 992),
     ("inf2b_s40_keep0.6", synth.INF2B, 1, 40, 40, 960, 2521, 3488),
+    # few rows at the large model's widths: every GEMM splits K between workgroups, with 64x64 tiles up
+    # to 64 rows and 128x128 tiles above; the four GEMMs of a block have different tile counts and share
+    # one scratch area (counters and partial tiles)
+    ("inf2b_side1", synth.INF2B, 1, 1, 1, 1, 0, 8),
+    ("inf2b_side6_keep_all", synth.INF2B, 1, 6, 6, 36, 21, 64),
+    ("inf2b_side8_keep_all", synth.INF2B, 1, 8, 8, 64, 57, 128),
+    ("inf2b_side12_keep_all", synth.INF2B, 1, 12, 12, 144, 121, 272),
+    ("inf2b_side24_keep_all", synth.INF2B, 1, 24, 24, 576, 921, 1504),
+    ("inf2b_b2_k50", synth.INF2B, 2, 10, 10, 50, 300, 352),
+    ("wide_mlp5632_225_rows", synth.BlockDims(D=2048, H=16, dh=128, F=5632), 1, 15, 15, 225, 103, 336),
 ]
 
 

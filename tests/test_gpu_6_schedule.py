@@ -226,6 +226,57 @@ def test_stack_equals_single_block_calls_at_the_headline_size():
     assert torch.equal(ya.view(torch.int16), cur.view(torch.int16))
 
 
+@pytest.mark.parametrize("side", [2, 8, 12, 24])
+def test_structure_steps_of_the_large_model_across_layers(side):
+    """Structure steps of the 2B-class model: few rows, so every GEMM splits K between workgroups, and the
+    four GEMMs of a block (different tile counts) and the blocks of the stack reuse one scratch area whose
+    arrival counters are cleared once per call.  Three blocks through fastvar_scale_step must give the bits
+    of three single-block calls; the first block is also checked against the oracle."""
+    dims = synth.INF2B
+    B, N, n_layers = 1, side * side, 3
+    print(f"[structure step] large model, {n_layers} blocks, N={N}", flush=True)
+    L0 = 37
+    L_cap = (L0 + N + 7) // 8 * 8
+    d = fb.make_dims(dims.D, dims.H, dims.dh, dims.F)
+    x_np = synth.token_map(41, B, side, side, dims.D)
+    Ws = [synth.block_weights(41 + l, dims, block=l) for l in range(n_layers)]
+    kp, vp = synth.kv_prior(41, B, L0, dims.H, dims.dh)
+    up = [upload_weights(W) for W in Ws]
+    x = to_dev_bf16(x_np)
+
+    def layers():
+        out = []
+        for (wt, wstruct) in up:
+            kc, vc = make_caches(kp, vp, L_cap)
+            out.append(dict(wt=wt, w=wstruct, kc=kc, vc=vc, cache=None))
+        return out
+
+    ws = empty_ws(fb.fastvar_step_workspace_bytes(d, B, N, N))
+    ws.fill_(0xFF)
+    A, S = layers(), layers()
+    sides = [side, 2 * side]
+    ya = torch.full((B, N, dims.D), float("nan"), dtype=torch.bfloat16, device=DEV)
+    tmp = torch.empty_like(ya)
+    new_len = fb.fastvar_scale_step(x, sides, sides, 0, 1, B, N, d, fb.make_layers(A), L0, L_cap, ya, tmp, None, ws)
+    assert new_len == L0 + N
+    cur, first = x, None
+    for ly in S:
+        out = torch.full((B, N, dims.D), float("nan"), dtype=torch.bfloat16, device=DEV)
+        fb.fastvar_block_forward_pruned(cur, N, None, B, N, d, ly["w"], ly["kc"], ly["vc"], L0, L_cap, out, ws)
+        first = out if first is None else first
+        cur = out
+    torch.cuda.synchronize()
+    assert not torch.isnan(ya.float()).any()
+    assert torch.equal(ya.view(torch.int16), cur.view(torch.int16))
+    for la, lb in zip(A, S):
+        assert torch.equal(la["kc"].view(torch.int16), lb["kc"].view(torch.int16))
+        assert torch.equal(la["vc"].view(torch.int16), lb["vc"].view(torch.int16))
+    ref, kn, vn = O.block_forward_pruned(x_np, Ws[0], dims.H, kp, vp)
+    assert max_rel(from_dev_bf16(first), ref) <= TOL
+    kg, vg = cache_rows(S[0]["kc"], S[0]["vc"], L0, L0 + N)
+    assert max_rel(kg, kn) <= TOL and max_rel(vg, vn) <= TOL
+
+
 def test_timed_scale_step_gives_the_same_result_and_stage_times():
     print("[scale step] stopwatch variant", flush=True)
     dims, B = TINY64, 2

@@ -78,3 +78,11 @@ def test_captured_maps_feed_the_next_texture_step():
         rest = np.setdiff1d(np.arange(25), b["idx"][s])
         np.testing.assert_array_equal(b["y"][s, rest], up[s, rest])
         assert np.abs(b["y"][s, b["idx"][s]] - up[s, b["idx"][s]]).max() > 1e-3
+
+
+def test_skipped_step_with_an_empty_cache_is_the_upsampled_map():
+    # degenerate corner: no kept tokens and no cached keys at all (Sec. 4.1: a 100 % ratio skips the step)
+    Ws, x, kc, vc, cm, (h, w, hc, wc, L0) = _setup(5, n_layers=1, L0=0)
+    r = O.step(x, h, w, 0, Ws[0], DIMS.H, kc[0], vc[0], cm[0], hc, wc)
+    np.testing.assert_array_equal(r["y"], O.upsample_bilinear(cm[0], hc, wc, h, w))
+    assert r["k_new"].shape[1] == 0 and r["idx"].shape[1] == 0

@@ -1,0 +1,147 @@
+"""GPU parity on seeded random shapes: the block and the whole step against the oracle, whole schedules through
+the stack entry point against the single-block entry points.
+
+The fixed cases of the other files sit on the shapes of the paper's models; the launch heuristics (tile shapes,
+K split between workgroups, key ranges split between workgroups, 64x64 / 128x128 / 256-row tiles, head dim 64
+or 128) switch on row counts, widths and cache lengths in between, so a seeded sweep walks through
+combinations nobody wrote down.  Same bars as elsewhere: 2e-2 max-relative against the oracle, index sets equal
+outside the near-tie band, bit equality between entry points that run the same kernels.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fastvar_oracle as O
+from paper_2503_23367_amd import binding as fb
+from paper_2503_23367_amd import synth
+from gpu_util import DEV, empty_ws, max_rel, to_dev_bf16
+from test_gpu_4_block import check_block, run_step
+from test_gpu_6_schedule import _stack
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+def _block_case(rng, wide):
+    if wide:     # widths of the large models, where the GEMMs split K and the attention splits key ranges
+        dh = int(rng.choice([64, 128, 128]))
+        H = int(rng.choice([8, 16, 24, 30])) if dh == 64 else int(rng.choice([8, 12, 16]))
+    else:
+        dh = int(rng.choice([64, 128]))
+        H = int(rng.choice([1, 2, 3, 4, 8]))
+    D = H * dh
+    F = 64 * int(rng.integers(max(1, D // 64 if wide else 1), 4 * D // 64 + 1))
+    B = int(rng.choice([1, 1, 2, 3]))
+    h, w = int(rng.integers(1, 41)), int(rng.integers(1, 41))
+    N = h * w
+    k = int(rng.choice([1, N, max(1, N // 2), int(rng.integers(1, N + 1))]))
+    if B * k > 2200:
+        k = max(1, 2200 // B)
+    L0 = int(rng.choice([0, int(rng.integers(0, 600)), int(rng.integers(600, 7000 if wide else 2500))]))
+    L_cap = ((L0 + k + 7) // 8) * 8 + 8 * int(rng.integers(0, 3))
+    return synth.BlockDims(D=D, H=H, dh=dh, F=F), B, h, w, k, L0, L_cap
+
+
+@pytest.mark.parametrize("seed,wide", [(s, s % 2 == 0) for s in range(20)])
+def test_block_random_shape(seed, wide):
+    rng = np.random.default_rng(1000 + seed)
+    dims, B, h, w, k, L0, L_cap = _block_case(rng, wide)
+    rows = None
+    if B * k * (L0 + k) * dims.D > 6e10 or B * k * dims.D * dims.F > 3e10:   # keep the oracle to seconds
+        rows = np.unique(np.concatenate([[0, k - 1], rng.integers(0, k, size=40)]))
+    check_block(f"random{seed}", dims, B, h, w, k, L0, L_cap, seed=2000 + seed, rows=rows)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_step_random_shape(seed):
+    rng = np.random.default_rng(3000 + seed)
+    dh = int(rng.choice([64, 128]))
+    H = int(rng.choice([1, 2, 4, 8, 16]))
+    D = H * dh
+    F = 64 * int(rng.integers(1, 4 * D // 64 + 1))
+    B = int(rng.choice([1, 1, 2, 3]))
+    s = int(rng.integers(2, 36))
+    sc = int(rng.integers(1, s))
+    N = s * s
+    k = int(rng.choice([0, N, max(1, N // 2), int(rng.integers(0, N + 1))]))
+    L0 = int(rng.choice([0, int(rng.integers(0, 300)), int(rng.integers(300, 2500))]))
+    L_cap = ((L0 + k + 7) // 8) * 8 + 8
+    dims = synth.BlockDims(D=D, H=H, dh=dh, F=F)
+    print(f"[random step {seed}] D={D} H={H} dh={dh} F={F} B={B} side={s} cache side={sc} k={k} L0={L0}", flush=True)
+    x = synth.token_map(500 + seed, B, s, s, D)
+    W = synth.block_weights(500 + seed, dims)
+    kp, vp = synth.kv_prior(500 + seed, B, L0, H, dh)
+    cache = synth.cached_map(500 + seed, B, sc, sc, D)
+    y, idx, new_len, kc, vc = run_step(dims, (sc, s), 1, 0, B, k, x, W, kp, vp, cache, L_cap)
+    ref = O.step(x, s, s, k, W, H, kp, vp, cache, sc, sc)
+    assert new_len == L0 + k
+    assert not np.isnan(y).any()
+    if k > 0 and not np.array_equal(idx, ref["idx"]):
+        # sets may differ only inside the near-tie band of the threshold score; then the maps differ too
+        for b in range(B):
+            diff = set(idx[b].tolist()) ^ set(ref["idx"][b].tolist())
+            thr = np.sort(ref["score"][b])[::-1][k - 1]
+            assert all(abs(ref["score"][b][j] - thr) <= 1e-6 * abs(thr) for j in diff)
+        return
+    assert max_rel(y, ref["y"]) <= TOL
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_schedule_random_shape_stack_equals_single_block_calls(seed):
+    rng = np.random.default_rng(4000 + seed)
+    wide = seed % 3 == 0
+    dh = int(rng.choice([64, 128]))
+    H = (16 if dh == 128 else 32) if wide else int(rng.choice([1, 2, 4, 8]))
+    D = H * dh
+    F = 64 * int(rng.integers(max(1, D // 64), 3 * D // 64 + 1))
+    B = int(rng.choice([1, 1, 2]))
+    n_layers = int(rng.choice([2, 3]))
+    sides = sorted(set(int(v) for v in rng.integers(1, 20 if wide else 30, size=int(rng.integers(3, 6)))))
+    if len(sides) < 3:
+        sides = [1, 3, 7, 12]
+    K = len(sides)
+    cache_step = int(rng.integers(0, K - 1))
+    keeps = [float(rng.choice([0.0, 0.25, 0.5, 0.6, 1.0, float(rng.random())])) for _ in range(K)]
+    dims = synth.BlockDims(D=D, H=H, dh=dh, F=F)
+    hc = wc = sides[cache_step]
+    L_cap = (sum(s * s for s in sides) + 7) // 8 * 8 + 8
+    print(f"[random schedule {seed}] D={D} H={H} dh={dh} F={F} B={B} layers={n_layers} sides={sides} "
+          f"cache_step={cache_step} keeps={[round(v, 2) for v in keeps]}", flush=True)
+    d = fb.make_dims(D, H, dh, F)
+    A = _stack(dims, n_layers, B, L_cap, hc, wc, seed=300 + seed)
+    Bk = _stack(dims, n_layers, B, L_cap, hc, wc, seed=300 + seed)
+    arr = fb.make_layers(A)
+    kv_a = kv_b = 0
+    for step, side in enumerate(sides):
+        N = side * side
+        k = N if step <= cache_step else fb.fastvar_keep_count(N, keeps[step])
+        x = to_dev_bf16(synth.token_map(400 + seed * 10 + step, B, side, side, D))
+        y = torch.full((B, N, D), float("nan"), dtype=torch.bfloat16, device=DEV)
+        tmp = torch.full_like(y, float("nan"))
+        idx = torch.zeros((B, max(k, 1)), dtype=torch.int32, device=DEV)
+        ws = empty_ws(fb.fastvar_step_workspace_bytes(d, B, N, k))
+        ws.fill_(0xFF)
+        kv_a = fb.fastvar_scale_step(x, list(sides), list(sides), step, cache_step, B, k, d, arr, kv_a, L_cap, y, tmp,
+                                     idx, ws)
+        cur = x
+        for ly in Bk:
+            out = torch.empty_like(y)
+            if step <= cache_step:
+                fb.fastvar_block_forward_pruned(cur, N, None, B, N, d, ly["w"], ly["kc"], ly["vc"], kv_b, L_cap, out, ws)
+                if step == cache_step:
+                    ly["cache"] = out.clone()
+            else:
+                idx_b = torch.zeros((B, max(k, 1)), dtype=torch.int32, device=DEV)
+                fb.fastvar_step(cur, list(sides), list(sides), step, cache_step, B, k, d, ly["w"], ly["kc"], ly["vc"],
+                                kv_b, L_cap, ly["cache"], out, idx_b, ws)
+            cur = out
+        kv_b += k
+        torch.cuda.synchronize()
+        assert kv_a == kv_b
+        assert not torch.isnan(y.float()).any(), step
+        assert torch.equal(y.view(torch.int16), cur.view(torch.int16)), step
+        if step > cache_step and 0 < k < N:
+            assert torch.equal(idx, idx_b)
+        for la, lb in zip(A, Bk):
+            assert torch.equal(la["kc"][:, :, :kv_a].view(torch.int16), lb["kc"][:, :, :kv_a].view(torch.int16))
+            assert torch.equal(la["vc"][:, :, :, :kv_a].view(torch.int16), lb["vc"][:, :, :, :kv_a].view(torch.int16))

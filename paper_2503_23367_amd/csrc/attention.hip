@@ -1171,41 +1171,42 @@ int attn_cfg_override() {
 
 }  // namespace
 
-AttnSplitPlan attention_split_plan(int B, int H, int dh, int k_tokens, int L) {
+AttnSplitPlan attention_split_plan(int B, int H, int dh, int k_tokens, int L, size_t max_bytes) {
     AttnSplitPlan sp{1, 0, false, 0, 0, 0};
-    if (dh != 128 || L <= 256) return sp;
+    if (dh != 128 || L <= 256 || k_tokens <= 0) return sp;
     const long wg128 = (long)((k_tokens + 127) / 128) * H * B;
     const long wg256 = (long)((k_tokens + 255) / 256) * H * B;
     const size_t per_query_row = (size_t)(2 * 2 + 4 * 2 * 16) * 64 * sizeof(float);   // per wave of 64 queries
+    // The counters take the same room whichever variant is chosen (one per 128-query tile, the larger count).
+    const size_t counter_bytes = ((size_t)wg128 * 4 + 255) & ~(size_t)255;
     auto ranges_ok = [&](int s, int bn, int& per) {
         per = (((L + s - 1) / s) + bn - 1) / bn * bn;          // whole key tiles
         return per > 2 * bn && L - (s - 1) * per > 2 * bn;     // every range has at least three tiles
     };
-    if (wg128 < 192) {
-        // too few queries to fill the chip: 128-query workgroups on 2-4 key ranges
-        int s = (int)(256 / wg128);
-        if (s > 4) s = 4;
-        for (; s > 1; --s) {
+    // Time model, in units of one 128-query workgroup walking all L keys: workgroups run in rounds of 256
+    // (one per CU); a 256-query workgroup takes 1.86 units (twice the work, about 7 % faster); a workgroup
+    // on one of s key ranges takes 1/s of that plus its prologue, its partial output and the merge: 4 % for
+    // two ranges, 18 % per extra range beyond (measured at 1152-3072 kept tokens, 5-13 K keys; with three
+    // rounds of workgroups the split lost in every case tried, so at most two are considered).  Unsplit,
+    // the launcher below takes the cheaper of the two workgroup sizes.
+    auto rounds = [](long wgs) { return (double)((wgs + 255) / 256); };
+    const double kWide = 1.86;
+    double best = rounds(wg128) < kWide * rounds(wg256) ? rounds(wg128) : kWide * rounds(wg256);
+    best *= 0.97;    // a split has to win by more than the model's noise
+    for (int wide = 0; wide <= (attn_wide_enabled() ? 1 : 0); ++wide) {
+        const long wg = wide ? wg256 : wg128;
+        for (int s = 2; s <= 4; ++s) {
             int per;
-            if (ranges_ok(s, 128, per)) {
-                sp.splits = s; sp.keys_per_split = per;
-                sp.counters = (int)wg128;
-                sp.counter_bytes = ((size_t)wg128 * 4 + 255) & ~(size_t)255;
-                sp.bytes = sp.counter_bytes + (size_t)wg128 * s * 2 * per_query_row;
-                return sp;
+            if (wg * s > 512 || !ranges_ok(s, wide ? 64 : 128, per)) continue;
+            const size_t bytes = counter_bytes + (size_t)wg * s * (wide ? 4 : 2) * per_query_row;
+            if (max_bytes && bytes > max_bytes) continue;
+            const double overhead = s == 2 ? 0.04 : 0.18 * (s - 1);
+            const double cost = (wide ? kWide : 1.0) * rounds(wg * s) / s * (1.0 + overhead);
+            if (cost < best) {
+                best = cost;
+                sp.splits = s; sp.keys_per_split = per; sp.wide = wide != 0;
+                sp.counters = (int)wg; sp.counter_bytes = counter_bytes; sp.bytes = bytes;
             }
-        }
-        return sp;
-    }
-    if (wg256 * 2 <= 256 && wg256 * 2 >= 224 && attn_wide_enabled()) {
-        // exactly one round of 256-query workgroups on two key ranges: the wider workgroup moves half the
-        // K / V bytes per MFMA, which outweighs writing and merging the partial outputs
-        int per;
-        if (ranges_ok(2, 64, per)) {
-            sp.splits = 2; sp.keys_per_split = per; sp.wide = true;
-            sp.counters = (int)wg256;
-            sp.counter_bytes = ((size_t)wg256 * 4 + 255) & ~(size_t)255;
-            sp.bytes = sp.counter_bytes + (size_t)wg256 * 2 * 4 * per_query_row;
         }
     }
     return sp;
@@ -1221,7 +1222,7 @@ void launch_attention(const AttnArgs& a, hipStream_t stream) {
     p.scale_log2e = a.scale * 1.4426950408889634f;
     p.q_tiles = (a.k_tokens + 127) / 128; p.splits = 1; p.keys_per_split = 0; p.part = nullptr; p.split_cnt = nullptr;
     if (a.split_ws && attn_cfg_override() < 0) {
-        const AttnSplitPlan sp = attention_split_plan(a.B, a.H, a.dh, a.k_tokens, a.L);
+        const AttnSplitPlan sp = attention_split_plan(a.B, a.H, a.dh, a.k_tokens, a.L, a.split_ws_bytes);
         if (sp.splits > 1) {
             p.splits = sp.splits; p.keys_per_split = sp.keys_per_split;
             p.split_cnt = static_cast<int*>(a.split_ws);

@@ -29,19 +29,17 @@ BlockPlan block_plan(const fastvar_dims* d, int B, int k) {
     p.off_h1 = off;  off += round256(M * d->D * 2);  // residual stream after attention
     p.off_u = off;   off += round256(M * d->F * 2);  // MLP hidden
     p.off_rows = off; off += round256(M * 4);        // absolute source row of every kept token
-    // partial outputs of an attention whose key range is split between workgroups (few kept tokens);
-    // sized for the longest cache the capacity check allows is not known here: the plan is taken
-    // for the worst case over L (the scratch does not depend on L, only on B, H and k)
+    // partial outputs of an attention whose key range is split between workgroups: sized for the plan
+    // of an unbounded cache length (every variant admissible); with the real length the launcher only
+    // considers variants that fit into this
     p.asplit_bytes = 0;
     p.asplit_counters = 0;
-    if (d->dh == 128 && k > 0) {
-        const long wg128 = (long)((k + 127) / 128) * d->H * B;
-        const long wg256 = (long)((k + 255) / 256) * d->H * B;
-        const size_t per_wg128 = (size_t)(2 * 2 + 4 * 2 * 16) * 128 * sizeof(float);
-        const size_t cnt_bytes = round256((size_t)wg128 * 4);                        // arrival counters first
-        if (wg128 < 192) p.asplit_bytes = cnt_bytes + (size_t)wg128 * 4 * per_wg128;              // up to four key ranges
-        else if (wg256 * 2 <= 256) p.asplit_bytes = cnt_bytes + (size_t)wg256 * 2 * 2 * per_wg128;   // two, 256-query tiles
-        p.asplit_counters = p.asplit_bytes ? (int)wg128 : 0;
+    if (k > 0) {
+        const fv::AttnSplitPlan sp = fv::attention_split_plan(B, d->H, d->dh, k, 1 << 28);
+        if (sp.splits > 1) {
+            p.asplit_bytes = sp.bytes;
+            p.asplit_counters = (int)(sp.counter_bytes / 4);
+        }
     }
     p.off_asplit = off; off += round256(p.asplit_bytes);
     // split-K scratch of the GEMMs (only shapes with few output tiles have any): one area, the
@@ -187,6 +185,7 @@ void enqueue_attn(const void* x, int N, const int32_t* idx, int B, int k, const 
     at.B = B; at.H = d->H; at.dh = d->dh; at.k_tokens = k; at.L = L0 + k; at.L_cap = L_cap;
     at.scale = d->softmax_scale;
     at.split_ws = bp.asplit_bytes ? base + bp.off_asplit : nullptr;
+    at.split_ws_bytes = bp.asplit_bytes;
     fv::launch_attention(at, st);
     mark(st, FASTVAR_STAGE_ATTENTION);
     // h1 = x[idx] + o * Wp^T + bp

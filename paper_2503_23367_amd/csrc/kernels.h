@@ -108,14 +108,18 @@ struct AttnArgs {
     // Optional scratch (attention_split_plan) that lets shapes with too few queries to fill the chip
     // split the key range between workgroups; without it every workgroup walks all keys.
     void* split_ws = nullptr;
+    size_t split_ws_bytes = 0;   // its size: variants that need more are not considered
 };
 void launch_attention(const AttnArgs& a, hipStream_t stream);
 
-// Key-range split for attention shapes that give fewer than 192 workgroups of 128 queries: `splits`
-// workgroups per query tile each take `keys_per_split` keys (a multiple of the key tile) and leave
-// unnormalised partial outputs with their softmax statistics in scratch; the workgroup that finishes a
-// query tile last merges them (softmax partials combine exactly; it adds them in range order, so the
-// result does not depend on who was last).  splits == 1: no scratch.
+// Key-range split for attention shapes whose workgroups do not fill whole rounds of 256 CUs (too few
+// queries, or a last round that is mostly empty): `splits` workgroups per query tile each take
+// `keys_per_split` keys (a multiple of the key tile) and leave unnormalised partial outputs with their
+// softmax statistics in scratch; the workgroup that finishes a query tile last merges them (softmax
+// partials combine exactly; it adds them in range order, so the result does not depend on who was last).
+// The plan is the cheapest of 128- or 256-query workgroups on 2-4 key ranges under a simple round-count
+// model, if that beats the unsplit launch.  splits == 1: no scratch.  max_bytes != 0: only variants whose
+// scratch fits.
 struct AttnSplitPlan {
     int splits;
     int keys_per_split;
@@ -124,6 +128,6 @@ struct AttnSplitPlan {
     size_t counter_bytes;
     size_t bytes;          // counters + partial results
 };
-AttnSplitPlan attention_split_plan(int B, int H, int dh, int k_tokens, int L);
+AttnSplitPlan attention_split_plan(int B, int H, int dh, int k_tokens, int L, size_t max_bytes = 0);
 
 }  // namespace fv

@@ -120,7 +120,8 @@ def test_block_d30_batch8_sampled_rows():
 
 @pytest.mark.parametrize("name", ["inf2b_2k_s128_keep0.25", "inf2b_1024px_s64_keep1.0", "inf2b_1024px_s64_keep0.75",
                                   "inf2b_1024px_s64_keep0.25", "inf2b_1024px_s64_keep0.1",
-                                  "inf2b_1024px_s48_keep0.5", "inf2b_2k_s96_keep0.3"])
+                                  "inf2b_1024px_s48_keep0.5", "inf2b_2k_s96_keep0.3", "inf2b_2k_s80_keep0.4",
+                                  "inf2b_1024px_s64_keep0.4"])
 def test_block_model_configs_full_size_sampled_rows(name):
     """The remaining model configurations at their full sizes (2K extension, keep-ratio sweep on the 64x64
     scale, intermediate pruned scales), in the launch configurations the library picks for them: every kept

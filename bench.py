@@ -328,11 +328,15 @@ def schedule_bench(wl, n_blocks, steps, warmup, keeps=(0.6, 0.5, 0.0, 0.0)):
     y = torch.empty((B, Nmax, D), dtype=torch.bfloat16, device=dev)
     tmp = torch.empty_like(y)
     idx = torch.empty((B, Nmax), dtype=torch.int32, device=dev)
-    ws = torch.empty(fb.fastvar_step_workspace_bytes(d, B, Nmax, Nmax), dtype=torch.uint8, device=dev)
 
     def k_of(i, pruned):
         N = sides[i] ** 2
         return fb.fastvar_keep_count(N, keeps[i - cache_step - 1]) if pruned and i > cache_step else N
+
+    # one scratch buffer for every step of both runs: the sizes are not monotone in the kept count
+    ws_bytes = max(fb.fastvar_step_workspace_bytes(d, B, sides[i] ** 2, k_of(i, pruned))
+                   for i in range(K) for pruned in (False, True))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
 
     def one_image(pruned, stamps=None):
         kv = 0

@@ -117,7 +117,10 @@ int fastvar_keep_count(int N, double keep_ratio);
 /* Scratch bytes needed by fastvar_select_pivotal for a [B, N, D] map. */
 size_t fastvar_select_workspace_bytes(int B, int N, int D);
 
-/* Scratch bytes needed by fastvar_block_forward_pruned for B*k kept tokens. */
+/* Scratch bytes needed by fastvar_block_forward_pruned for B*k kept tokens.  Not monotone in k: launches
+ * with few workgroups get extra room for partial results that larger ones do not need, so a caller that
+ * reuses one buffer over several steps sizes it for the maximum over those steps (the same holds for the
+ * step sizes below, which contain this one). */
 size_t fastvar_block_workspace_bytes(const fastvar_dims* dims, int B, int k);
 
 /*

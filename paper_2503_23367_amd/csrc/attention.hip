@@ -1194,6 +1194,9 @@ AttnSplitPlan attention_split_plan(int B, int H, int dh, int k_tokens, int L, si
     double best = rounds(wg128) < kWide * rounds(wg256) ? rounds(wg128) : kWide * rounds(wg256);
     best *= 0.97;    // a split has to win by more than the model's noise
     for (int wide = 0; wide <= (attn_wide_enabled() ? 1 : 0); ++wide) {
+        // with fewer than 128 workgroups of 128 queries the unsplit launch is the plain kernel's 64-query
+        // workgroups, which the model above does not describe and 256-query workgroups do not beat
+        if (wide && wg128 < 128) continue;
         const long wg = wide ? wg256 : wg128;
         for (int s = 2; s <= 4; ++s) {
             int per;

@@ -1186,9 +1186,9 @@ AttnSplitPlan attention_split_plan(int B, int H, int dh, int k_tokens, int L, si
     // Time model, in units of one 128-query workgroup walking all L keys: workgroups run in rounds of 256
     // (one per CU); a 256-query workgroup takes 1.86 units (twice the work, about 7 % faster); a workgroup
     // on one of s key ranges takes 1/s of that plus its prologue, its partial output and the merge: 4 % for
-    // two ranges, 18 % per extra range beyond (measured at 1152-3072 kept tokens, 5-13 K keys; with three
-    // rounds of workgroups the split lost in every case tried, so at most two are considered).  Unsplit,
-    // the launcher below takes the cheaper of the two workgroup sizes.
+    // two ranges, 18 % per extra range beyond (with three rounds of workgroups the split lost in every
+    // case tried, so at most two are considered).  Unsplit, the launcher below takes the cheaper of the
+    // two workgroup sizes.
     auto rounds = [](long wgs) { return (double)((wgs + 255) / 256); };
     const double kWide = 1.86;
     double best = rounds(wg128) < kWide * rounds(wg256) ? rounds(wg128) : kWide * rounds(wg256);
@@ -1203,7 +1203,11 @@ AttnSplitPlan attention_split_plan(int B, int H, int dh, int k_tokens, int L, si
             if (wg * s > 512 || !ranges_ok(s, wide ? 64 : 128, per)) continue;
             const size_t bytes = counter_bytes + (size_t)wg * s * (wide ? 4 : 2) * per_query_row;
             if (max_bytes && bytes > max_bytes) continue;
-            const double overhead = s == 2 ? 0.04 : 0.18 * (s - 1);
+            // one round of 128-query workgroups, or two ranges: the figures above; three or four ranges of
+            // 256-query workgroups, or two rounds: the fixed cost per range weighs more the shorter the
+            // range (measured with cold caches at 3.7-19 K keys: a loss below about 6 K keys)
+            const bool plain_case = wg * s <= 256 && (!wide || s == 2);
+            const double overhead = plain_case ? (s == 2 ? 0.04 : 0.18 * (s - 1)) : (s - 1) * (0.1 + 900.0 / L);
             const double cost = (wide ? kWide : 1.0) * rounds(wg * s) / s * (1.0 + overhead);
             if (cost < best) {
                 best = cost;

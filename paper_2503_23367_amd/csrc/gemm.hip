@@ -591,9 +591,9 @@ void launch_epi(GemmParams& p, hipStream_t stream) {
     //    with one wave per SIMD; they win whenever they still give (almost) every
     //    CU a tile.  The QKV GEMM uses 256x192 (N = 3D divides evenly) with eight
     //    waves of 64x96, whose smaller accumulator leaves room for the epilogue's
-    //    extra address state; the others 256x256, with eight waves of 128x64 when there is a single
-    //    round of tiles (two waves per SIMD cover each other's waits and halve the epilogue's issue
-    //    time) and four waves of 128x128 when there are several rounds.
+    //    extra address state; the others 256x256 with eight waves of 128x64 (two waves per SIMD cover
+    //    each other's waits and halve the epilogue's issue time; four waves of 128x128 are 13 % slower
+    //    on the 4096-row FC1 inside the step).
     //    Both need (almost) every CU to get a tile and the last round of tiles to be at least 80 % full.
     //  * otherwise 128x128 tiles: three 64-wide K stages with one workgroup per CU, or two stages with
     //    two per CU, whichever leaves fewer tile slots idle in its last round.  Shapes that give fewer
@@ -608,7 +608,7 @@ void launch_epi(GemmParams& p, hipStream_t stream) {
     const long big = EPI == EPI_QKV ? tiles192 : tiles256;
     int cfg;
     if (big >= 192 && fill(big, 256) >= 0.8)
-        cfg = EPI == EPI_QKV ? 12 : (tiles256 <= 256 ? 11 : 1);
+        cfg = EPI == EPI_QKV ? 12 : 11;
     else if (tiles128 <= 64)
         cfg = 16;
     else if (tiles128 <= 128)

@@ -70,12 +70,6 @@ __device__ __forceinline__ int chunk_key(int row) {
     return CPR == 16 ? (row & 15) : ((row >> 1) & 7);
 }
 
-#ifndef ATTN_SPAN_FULL
-#define ATTN_SPAN_FULL 0
-#endif
-#ifndef ATTN_VF_SPLIT
-#define ATTN_VF_SPLIT 0
-#endif
 constexpr int attn_waitcnt(int vm, bool lgkm) {
     return (vm & 0xF) | ((vm >> 4) << 14) | (0x7 << 4) | ((lgkm ? 0x0 : 0xF) << 8);
 }
@@ -284,7 +278,7 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
         constexpr int JHI_ = (LOAD_V_) ? K_LD + V_LD : K_LD;                                        \
         constexpr int NJ_ = JHI_ > JLO_ ? JHI_ - JLO_ : 0;                                          \
         constexpr int NFR_ = NV_ + NK_;                                                             \
-        constexpr int SPAN_ = (ATTN_SPAN_FULL || NJ_ > NFR_ / 2) ? NFR_ : NFR_ / 2;                 \
+        constexpr int SPAN_ = (NJ_ > NFR_ / 2) ? NFR_ : NFR_ / 2;                                   \
         const u32x4_t* v_base_ = lds + 2 * K_TILE + (((kt_) + 1) & 1) * V_TILE;                     \
         const u32x4_t* k_base_ = lds + ((kt_) & 1) * K_TILE + (kh * 64) * KCH;                      \
         bf16x8_t fr_[NV_ + NK_];                                                                    \
@@ -423,13 +417,8 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
         FV_PUBLISH()
         int kt = 1;
         for (; kt + 1 < KT; ++kt) {
-            if (ATTN_VF_SPLIT) {
-                FV_SOFTMAX(kt - 1, false, true, false, kt)
-                FV_MATRIX(kt, true, false, true)
-            } else {
-                FV_SOFTMAX(kt - 1, false, true, true, kt)
-                FV_MATRIX(kt, true, false, false)
-            }
+            FV_SOFTMAX(kt - 1, false, true, true, kt)
+            FV_MATRIX(kt, true, false, false)
             FV_PUBLISH()
         }
         if (kt < KT) {  // last tile
@@ -1107,12 +1096,8 @@ void launch_pipe(const AttnParams& p, int B, hipStream_t stream) {
     constexpr size_t tile_bytes = (size_t)2 * (64 * KSPLIT * (DH / 8) + DH * (8 * KSPLIT)) * 16;
     constexpr size_t merge_bytes = KSPLIT > 1 ? (size_t)QG * (DH / 32 * 16 + 2) * 2 * 64 * 4 : 0;
     constexpr size_t smem = tile_bytes > merge_bytes ? tile_bytes : merge_bytes;
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_pipe_kernel<DH, QG, KSPLIT>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        attr_set = true;
-    }
+    static std::once_flag once;
+    raise_lds_limit_once(once, &attention_pipe_kernel<DH, QG, KSPLIT>, smem);
     const int per_wg = QG * 64;
     attention_pipe_kernel<DH, QG, KSPLIT>
         <<<dim3((p.k_tokens + per_wg - 1) / per_wg, p.H, B), QG * KSPLIT * 64, smem, stream>>>(p);
@@ -1124,12 +1109,8 @@ void launch_pipe_split(const AttnParams& p, int B, hipStream_t stream) {
     constexpr size_t tile_bytes = (size_t)2 * (64 * KSPLIT * (DH / 8) + DH * (8 * KSPLIT)) * 16;
     constexpr size_t merge_bytes = KSPLIT > 1 ? (size_t)QG * (DH / 32 * 16 + 2) * 2 * 64 * 4 : 0;
     constexpr size_t smem = tile_bytes > merge_bytes ? tile_bytes : merge_bytes;
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_pipe_kernel<DH, QG, KSPLIT, true>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        attr_set = true;
-    }
+    static std::once_flag once;
+    raise_lds_limit_once(once, &attention_pipe_kernel<DH, QG, KSPLIT, true>, smem);
     attention_pipe_kernel<DH, QG, KSPLIT, true>
         <<<dim3(p.q_tiles * p.splits, p.H, B), QG * KSPLIT * 64, smem, stream>>>(p);
 }
@@ -1139,34 +1120,32 @@ void launch_cfg(const AttnParams& p, int B, hipStream_t stream) {
     constexpr size_t tile_bytes = (size_t)2 * (64 * KSPLIT * (DH / 8) + DH * (8 * KSPLIT)) * 16;
     constexpr size_t merge_bytes = KSPLIT > 1 ? (size_t)QG * (DH / 32 * 16 + 2) * QB * 64 * 4 : 0;
     constexpr size_t smem = tile_bytes > merge_bytes ? tile_bytes : merge_bytes;
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_kernel<DH, QB, QG, KSPLIT>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        attr_set = true;
-    }
+    static std::once_flag once;
+    raise_lds_limit_once(once, &attention_kernel<DH, QB, QG, KSPLIT>, smem);
     const int per_wg = QG * 32 * QB;
     attention_kernel<DH, QB, QG, KSPLIT>
         <<<dim3((p.k_tokens + per_wg - 1) / per_wg, p.H, B), QG * KSPLIT * 64, smem, stream>>>(p);
 }
 
-// Developer knob: FASTVAR_ATTN_WIDE=0 turns the 256-query / two-range variant off.
+// Tuning builds only (-DFASTVAR_DEV_KNOBS, never the product library, which reads no environment and keeps
+// no state): FASTVAR_ATTN_WIDE=0 turns the 256-query variants of the key-range split off, FASTVAR_ATTN_CFG
+// forces a kernel configuration.
 bool attn_wide_enabled() {
-    static int v = -1;
-    if (v < 0) {
-        const char* e = getenv("FASTVAR_ATTN_WIDE");
-        v = e ? atoi(e) : 1;
-    }
-    return v != 0;
+#ifdef FASTVAR_DEV_KNOBS
+    const char* e = getenv("FASTVAR_ATTN_WIDE");
+    return !e || atoi(e) != 0;
+#else
+    return true;
+#endif
 }
 
 int attn_cfg_override() {
-    static int v = -2;
-    if (v == -2) {
-        const char* e = getenv("FASTVAR_ATTN_CFG");
-        v = e ? atoi(e) : -1;
-    }
-    return v;
+#ifdef FASTVAR_DEV_KNOBS
+    const char* e = getenv("FASTVAR_ATTN_CFG");
+    return e ? atoi(e) : -1;
+#else
+    return -1;
+#endif
 }
 
 }  // namespace

@@ -568,9 +568,12 @@ int fastvar_scale_step_timed(const void* x, const int32_t* sched_h, const int32_
 
 size_t fastvar_step_sublayer_workspace_bytes(const fastvar_dims* dims, int B, int N, int k_attn, int k_ffn) {
     if (!dims || B <= 0 || N <= 0) return 0;
-    const int kmax = k_attn > k_ffn ? k_attn : k_ffn;
+    // the block scratch is laid out per kept count and its size is not monotone in it (the split plans of
+    // the GEMMs and of the attention change with the row count): the larger of the two layouts
+    const size_t blk_a = fastvar_block_workspace_bytes(dims, B, k_attn);
+    const size_t blk_f = fastvar_block_workspace_bytes(dims, B, k_ffn);
     return fastvar_select_workspace_bytes(B, N, dims->D) + fastvar_restore_workspace_bytes(B, N) +
-           fastvar_block_workspace_bytes(dims, B, kmax);
+           (blk_a > blk_f ? blk_a : blk_f);
 }
 
 int fastvar_attn_forward_pruned(const void* x, int N, const int32_t* idx, int B, int k, const fastvar_dims* dims,

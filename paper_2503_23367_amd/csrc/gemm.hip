@@ -552,13 +552,8 @@ void launch_cfg(GemmParams& p, hipStream_t stream) {
     constexpr size_t smem = (size_t)STAGES * (BM + BN) * BK * sizeof(bf16_t);
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
-    static bool attr_set = false;  // raising the dynamic-LDS limit is per function, once per process
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(
-            reinterpret_cast<const void*>(&gemm_nt_kernel<BM, BN, BK, STAGES, WGM, WGN, KG, EPI, SK>),
-            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        attr_set = true;
-    }
+    static std::once_flag once;  // raising the dynamic-LDS limit is per function, once per process
+    raise_lds_limit_once(once, &gemm_nt_kernel<BM, BN, BK, STAGES, WGM, WGN, KG, EPI, SK>, smem);
     if (!SK) p.splits = 1;
     gemm_nt_kernel<BM, BN, BK, STAGES, WGM, WGN, KG, EPI, SK>
         <<<dim3(p.tiles_m * p.tiles_n, SK ? p.splits : 1), 64 * WGM * WGN * KG, smem, stream>>>(p);
@@ -569,18 +564,20 @@ __global__ void zero_i32_kernel(int32_t* p, int n) {
     if (i < n) p[i] = 0;
 }
 
-// Developer knob: FASTVAR_GEMM_CFG (all epilogues) or FASTVAR_GEMM_CFG<e> (epilogue e = 0, 1, 2)
-// forces a tile configuration; unset means the heuristic below.
+// Tuning builds only (-DFASTVAR_DEV_KNOBS, never the product library, which reads no environment and keeps
+// no state): FASTVAR_GEMM_CFG (all epilogues) or FASTVAR_GEMM_CFG<e> (epilogue e = 0, 1, 2) forces a tile
+// configuration; unset means the heuristic below.
 int gemm_cfg_override(int epi) {
-    static int v[3] = {-2, -2, -2};
-    if (v[epi] == -2) {
-        char name[32];
-        snprintf(name, sizeof(name), "FASTVAR_GEMM_CFG%d", epi);
-        const char* e = getenv(name);
-        if (!e) e = getenv("FASTVAR_GEMM_CFG");
-        v[epi] = e ? atoi(e) : -1;
-    }
-    return v[epi];
+#ifdef FASTVAR_DEV_KNOBS
+    char name[32];
+    snprintf(name, sizeof(name), "FASTVAR_GEMM_CFG%d", epi);
+    const char* e = getenv(name);
+    if (!e) e = getenv("FASTVAR_GEMM_CFG");
+    return e ? atoi(e) : -1;
+#else
+    (void)epi;
+    return -1;
+#endif
 }
 
 template <int EPI>

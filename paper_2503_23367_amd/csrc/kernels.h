@@ -7,7 +7,20 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <mutex>
+
 namespace fv {
+
+// Raises a kernel's dynamic-LDS limit: a per-function attribute that has to be set once per process before
+// the first launch that asks for more than 64 KB.  The once_flag (one per launch site, i.e. per kernel
+// instantiation) makes concurrent first calls from several host threads safe.
+template <class Kernel>
+inline void raise_lds_limit_once(std::once_flag& once, Kernel kernel, size_t bytes) {
+    std::call_once(once, [&] {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)bytes);
+    });
+}
 
 // ---- selection (Sec. 3.3, Eq. 4-5) ----
 struct SelectPlan {

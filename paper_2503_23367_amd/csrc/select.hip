@@ -333,12 +333,8 @@ void launch_select(const void* x, int B, int N, int D, int k, int32_t* idx, int3
     const size_t mu_bytes = (size_t)plan.col_tiles * 512 * sizeof(double);
     score_kernel<<<dim3((N + kScoreRowsPerBlock - 1) / kScoreRowsPerBlock, B), kScoreThreads, mu_bytes, stream>>>(
         xb, mean, score, N, D);
-    static bool attr_set = false;  // maps above 16K tokens need more than the default 64 KB of dynamic LDS
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&topk_kernel),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, 32768 * (int)sizeof(uint32_t));
-        attr_set = true;
-    }
+    static std::once_flag once;  // maps above 16K tokens need more than the default 64 KB of dynamic LDS
+    raise_lds_limit_once(once, &topk_kernel, 32768 * sizeof(uint32_t));
     topk_kernel<<<dim3(B), kTopkThreads, (size_t)N * sizeof(uint32_t), stream>>>(score, N, k, idx, rank);
 }
 

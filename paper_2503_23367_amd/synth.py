@@ -129,6 +129,12 @@ _add(Workload("inf2b_1024px_s48_keep0.5", INF2B, SIDES_1024, 11, 9, 0.5, 1152, n
               prior_k={10: 960}))
 _add(Workload("inf2b_1024px_s64_keep0.4", INF2B, SIDES_1024, 12, 9, 0.4, 1638, n_blocks=32,
               prior_k={10: 960, 11: 1152}))
+# The same three pruned scales at batch 4.
+_add(Workload("inf2b_1024px_s40_keep0.6_b4", INF2B, SIDES_1024, 10, 9, 0.6, 960, B=4, n_blocks=32))
+_add(Workload("inf2b_1024px_s48_keep0.5_b4", INF2B, SIDES_1024, 11, 9, 0.5, 1152, B=4, n_blocks=32,
+              prior_k={10: 960}))
+_add(Workload("inf2b_1024px_s64_keep0.4_b4", INF2B, SIDES_1024, 12, 9, 0.4, 1638, B=4, n_blocks=32,
+              prior_k={10: 960, 11: 1152}))
 # Zero-shot 2K extension of the same stack.
 _add(Workload("inf2b_2k_s80_keep0.4", INF2B, SIDES_2K, 13, 12, 0.4, 2560, n_blocks=32))
 _add(Workload("inf2b_2k_s96_keep0.3", INF2B, SIDES_2K, 14, 12, 0.3, 2765, n_blocks=32,

@@ -78,6 +78,22 @@ def test_workspace_sizes_cover_the_stages():
     assert fb.fastvar_select_workspace_bytes(0, 16, 64) == 0
 
 
+def test_sublayer_workspace_covers_both_halves_whatever_their_kept_counts():
+    """The block scratch is not monotone in the kept count (k = 2560 needs more than k = 3072 at the large
+    model's widths), so the sub-layer step's size must be the larger of the two halves' layouts, not the
+    layout of the larger count: exactly what the entry point's own argument check asks for."""
+    d = fb.make_dims(2048, 16, 128, 8192)
+    B, N = 1, 4096
+    fixed = fb.fastvar_select_workspace_bytes(B, N, 2048) + fb.fastvar_restore_workspace_bytes(B, N)
+    ks = (0, 1, 64, 410, 1024, 1638, 2048, 2458, 2560, 3072, 4096)
+    sizes = {k: fb.fastvar_block_workspace_bytes(d, B, k) for k in ks}
+    assert any(sizes[a] > sizes[b] for a in ks for b in ks if a < b), "expected a non-monotone pair"
+    for ka in ks:
+        for kf in ks:
+            got = fb.fastvar_step_sublayer_workspace_bytes(d, B, N, ka, kf)
+            assert got == fixed + max(sizes[ka], sizes[kf]), (ka, kf)
+
+
 def test_argument_errors_are_reported_before_any_launch():
     """Fake (never dereferenced) pointers: every call must fail validation on the host."""
     L = fb.lib()

@@ -344,3 +344,67 @@ def test_scale_step_argument_errors():
     assert call(ws=empty_ws(256)) == fb.FASTVAR_EWORKSPACE
     torch.cuda.synchronize()
     assert torch.all(y == 0) and torch.all(tmp == 0)
+
+
+def _rand_layers(dims, n, B, L0, L_cap, hc, seed):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    r = lambda shape, std=1.0, mean=0.0: (torch.randn(shape, generator=g, device=DEV) * std + mean).to(torch.bfloat16)
+    D, F = dims.D, dims.F
+    out = []
+    for _ in range(n):
+        wt = dict(ln1_g=r((D,), 0.02, 1.0), ln1_b=r((D,), 0.02), w_qkv=r((3 * D, D), 0.02), b_qkv=r((3 * D,), 0.02),
+                  w_proj=r((D, D), 0.02), b_proj=r((D,), 0.02), ln2_g=r((D,), 0.02, 1.0), ln2_b=r((D,), 0.02),
+                  w_fc1=r((F, D), 0.02), b_fc1=r((F,), 0.02), w_fc2=r((D, F), 0.02), b_fc2=r((D,), 0.02))
+        kc = torch.zeros((B, dims.H, L_cap, dims.dh), dtype=torch.bfloat16, device=DEV)
+        vc = torch.zeros((B, dims.H, dims.dh, L_cap), dtype=torch.bfloat16, device=DEV)
+        if L0:
+            kc[:, :, :L0] = r((B, dims.H, L0, dims.dh))
+            vc[:, :, :, :L0] = r((B, dims.H, dims.dh, L0))
+        out.append(dict(wt=wt, w=fb.make_weights(wt), kc=kc, vc=vc, cache=r((B, hc * hc, D))))
+    return out
+
+
+@pytest.mark.parametrize("case", ["headline_two_blocks", "keep0.25_key_ranges", "structure_step_split_k"])
+def test_same_inputs_give_the_same_bits_every_run(case):
+    """Same inputs, same bits: the stack step run 20 times.  The headline step merges two key ranges per
+    query tile in its attention; the keep 0.25 step three; the structure step (144 tokens at the large
+    model's widths) splits K between workgroups in all four GEMMs.  All of them let the workgroup that
+    arrives last combine the partial results, so a result that depended on arrival order, or a partial
+    result read before it was complete, would show here as a changed bit.  Stops at the first difference."""
+    dims = synth.INF2B
+    d = fb.make_dims(dims.D, dims.H, dims.dh, dims.F)
+    if case == "structure_step_split_k":
+        B, side, L0 = 1, 12, 121
+        N = k = side * side
+        sides, step, cache_step, hc = [side, 2 * side], 0, 1, side
+    else:
+        wl = synth.WORKLOADS[synth.HEADLINE if case == "headline_two_blocks" else "inf2b_1024px_s64_keep0.25"]
+        B, N, k, L0 = 1, wl.N, wl.k, wl.L0_full
+        sides, step, cache_step, hc = list(wl.sides), wl.step, wl.cache_step, wl.hc
+    L_cap = (L0 + k + 7) // 8 * 8
+    print(f"[determinism] {case}: N={N} k={k} L0={L0}, 2 blocks, 20 runs", flush=True)
+    layers = _rand_layers(dims, 2, B, L0, L_cap, hc, seed=21)
+    arr = fb.make_layers(layers)
+    x = to_dev_bf16(synth.token_map(17, B, sides[step], sides[step], dims.D))
+    ws = empty_ws(fb.fastvar_step_workspace_bytes(d, B, N, k))
+    y = torch.empty((B, N, dims.D), dtype=torch.bfloat16, device=DEV)
+    tmp = torch.empty_like(y)
+    idx = torch.zeros((B, k), dtype=torch.int32, device=DEV)
+    first = None
+    for run in range(20):
+        ws.fill_(0xFF if run % 2 else 0x00)     # whatever the scratch held before must not matter
+        y.fill_(float("nan"))
+        tmp.fill_(float("nan"))
+        fb.fastvar_scale_step(x, sides, sides, step, cache_step, B, k, d, arr, L0, L_cap, y, tmp, idx, ws)
+        torch.cuda.synchronize()
+        got = [y.view(torch.int16).clone(), tmp.view(torch.int16).clone(), idx.clone()]
+        for ly in layers:
+            got.append(ly["kc"][:, :, L0:L0 + k].view(torch.int16).clone())
+            got.append(ly["vc"][:, :, :, L0:L0 + k].view(torch.int16).clone())
+        if first is None:
+            first = got
+            assert not torch.isnan(y.float()).any()
+            continue
+        for i, (a, b) in enumerate(zip(first, got)):
+            assert torch.equal(a, b), f"run {run}: tensor {i} differs from the first run"

@@ -22,7 +22,8 @@
  *   - Row-major everywhere.  A token map is [B, h*w, D] with token index
  *     n = i*w + j (row i, column j of the h x w grid).
  *   - The caller owns every buffer.  The library allocates nothing, keeps no
- *     state between calls and never synchronises: each call validates its
+ *     state between calls (one documented exception: the per-device scratch of
+ *     fastvar_select_pivotal_static) and never synchronises: each call validates its
  *     arguments on the host, enqueues its kernels on `stream`
  *     (a hipStream_t passed as void*; NULL = the default stream) and returns.
  *   - Return value: FASTVAR_OK (0) or a negative FASTVAR_E* code.  Arguments
@@ -173,6 +174,31 @@ size_t fastvar_step_sublayer_workspace_bytes(const fastvar_dims* dims, int B, in
 int fastvar_select_pivotal(const void* x, int B, int h, int w, int D, int k,
                            int32_t* idx_out, int32_t* rank_out, float* score_out,
                            void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * fastvar_select_pivotal for callers that cannot allocate or provide scratch
+ * memory: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, results and error codes as
+ * fastvar_select_pivotal (bit for bit the same idx, rank and score), without
+ * ws / ws_bytes: the column-sum partials, the mean and (when score_out is NULL)
+ * the scores live in a device array of FASTVAR_SELECT_STATIC_BYTES bytes that
+ * is part of the library's code object, one copy per GPU, held until the
+ * process ends.  The call allocates nothing and frees nothing.
+ *   - FASTVAR_ECAPACITY when fastvar_select_workspace_bytes(B, h*w, D) exceeds
+ *     FASTVAR_SELECT_STATIC_BYTES (8 MiB: e.g. B = 1 at 16384 x 2048, B = 2 at
+ *     4096 x 2048); nothing is launched then.
+ *   - The first call on a device looks up that device's copy of the array
+ *     (the one piece of per-process state this library keeps); FASTVAR_EHIP
+ *     if the runtime cannot resolve it.
+ *   - Every call on a GPU uses the same array, which keeps the last call's
+ *     contents; nothing in it has to start at zero (each kernel writes what
+ *     the next one reads).  Calls that overlap on one GPU (two streams, two
+ *     threads) race on it: serialise them, or use fastvar_select_pivotal with
+ *     a scratch buffer per stream.
+ */
+#define FASTVAR_SELECT_STATIC_BYTES (8u << 20)
+int fastvar_select_pivotal_static(const void* x, int B, int h, int w, int D, int k,
+                                  int32_t* idx_out, int32_t* rank_out, float* score_out, void* stream);
 
 /*
  * One transformer block on the kept tokens (Sec. 3.3, implementation paragraph:

@@ -52,7 +52,8 @@ EXPORTS = ("fastvar_version", "fastvar_strerror", "fastvar_keep_count", "fastvar
            "fastvar_residual_accumulate",
            "fastvar_select_workspace_bytes", "fastvar_block_workspace_bytes",
            "fastvar_restore_workspace_bytes", "fastvar_step_workspace_bytes",
-           "fastvar_select_pivotal", "fastvar_block_forward_pruned", "fastvar_restore",
+           "fastvar_select_pivotal", "fastvar_select_pivotal_static", "fastvar_block_forward_pruned",
+           "fastvar_restore",
            "fastvar_step", "fastvar_scale_step", "fastvar_scale_step_timed",
            "fastvar_step_sublayer_workspace_bytes", "fastvar_attn_forward_pruned",
            "fastvar_ffn_forward_pruned", "fastvar_step_sublayer", "fastvar_layernorm", "fastvar_gemm_bf16",
@@ -85,6 +86,8 @@ def lib() -> C.CDLL:
     L.fastvar_step_workspace_bytes.argtypes = [C.POINTER(Dims), i32, i32, i32]
     L.fastvar_select_pivotal.restype = i32
     L.fastvar_select_pivotal.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp]
+    L.fastvar_select_pivotal_static.restype = i32
+    L.fastvar_select_pivotal_static.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp]
     L.fastvar_block_forward_pruned.restype = i32
     L.fastvar_block_forward_pruned.argtypes = [vp, i32, vp, i32, i32, C.POINTER(Dims),
                                                C.POINTER(BlockWeights), vp, vp, i32, i32, vp, vp, sz, vp]
@@ -217,6 +220,15 @@ def fastvar_select_pivotal(x, B, h, w, D, k, idx_out, rank_out, score_out, ws) -
                                       _ptr(score_out), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
                                       _stream())
     _check(rc, "fastvar_select_pivotal")
+
+
+FASTVAR_SELECT_STATIC_BYTES = 8 << 20
+
+
+def fastvar_select_pivotal_static(x, B, h, w, D, k, idx_out, rank_out, score_out) -> None:
+    rc = lib().fastvar_select_pivotal_static(_ptr(x), B, h, w, D, k, _ptr(idx_out), _ptr(rank_out),
+                                             _ptr(score_out), _stream())
+    _check(rc, "fastvar_select_pivotal_static")
 
 
 def fastvar_block_forward_pruned(x, N, idx, B, k, dims: Dims, weights: BlockWeights, k_cache, v_cache,

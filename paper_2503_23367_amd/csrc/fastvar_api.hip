@@ -6,6 +6,8 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 
+#include <mutex>
+
 #include "kernels.h"
 
 namespace {
@@ -133,6 +135,33 @@ int check_restore(const void* y_kept, const int32_t* idx, const int32_t* rank, i
 }
 
 int launch_status() { return hipGetLastError() == hipSuccess ? FASTVAR_OK : FASTVAR_EHIP; }
+
+// Scratch of fastvar_select_pivotal_static: part of the code object, so every GPU the library runs on holds
+// its own copy at its own address.  In host code the array's name is only a handle for the symbol lookup
+// below, never a device address: kernels are given the looked-up pointer.
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char g_select_scratch[FASTVAR_SELECT_STATIC_BYTES];
+static_assert(sizeof(g_select_scratch) == FASTVAR_SELECT_STATIC_BYTES, "header and array agree");
+std::mutex g_select_scratch_mu;
+void* g_select_scratch_ptr[kMaxDevices] = {};
+
+// Device address of the current device's copy of the array, looked up once per device (with that device
+// current, as it is for the caller's launch) and kept.
+int select_scratch_address(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return FASTVAR_EHIP;
+    std::lock_guard<std::mutex> lock(g_select_scratch_mu);
+    if (!g_select_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_select_scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return FASTVAR_EHIP;
+        }
+        g_select_scratch_ptr[dev] = p;
+    }
+    *out = g_select_scratch_ptr[dev];
+    return FASTVAR_OK;
+}
 
 // Optional per-stage timing of the step entry points (fastvar_scale_step_timed): when a profile is
 // installed for the calling thread, an event is recorded on the launch stream after every stage.
@@ -344,6 +373,25 @@ int fastvar_select_pivotal(const void* x, int B, int h, int w, int D, int k, int
     const int N = h * w;
     const fv::SelectPlan plan = fv::select_plan(B, N, D);
     fv::launch_select(x, B, N, D, k, idx_out, rank_out, score_out, ws, plan, static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+int fastvar_select_pivotal_static(const void* x, int B, int h, int w, int D, int k, int32_t* idx_out,
+                                  int32_t* rank_out, float* score_out, void* stream) {
+    // sizes first: no HIP call is made for a request that cannot be served
+    if (B <= 0 || h <= 0 || w <= 0 || D <= 0) return FASTVAR_EINVAL;
+    if ((long)h * w > FASTVAR_MAX_TOKENS || D > kMaxWidth) return FASTVAR_ECAPACITY;
+    if ((double)B * h * w * D >= 2147483648.0 * 4.0) return FASTVAR_ECAPACITY;
+    const size_t need = fastvar_select_workspace_bytes(B, h * w, D);
+    if (need > sizeof(g_select_scratch)) return FASTVAR_ECAPACITY;
+    void* ws = nullptr;
+    int rc = select_scratch_address(&ws);
+    if (rc) return rc;
+    rc = check_select(x, B, h, w, D, k, idx_out, ws, need);
+    if (rc) return rc;
+    const int N = h * w;
+    fv::launch_select(x, B, N, D, k, idx_out, rank_out, score_out, ws, fv::select_plan(B, N, D),
+                      static_cast<hipStream_t>(stream));
     return launch_status();
 }
 

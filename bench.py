@@ -145,7 +145,7 @@ def time_kernel(fn, iters):
     return e0.elapsed_time(e1) / iters
 
 
-def kernel_table(wl, st, iters, block_ms):
+def kernel_table(wl, st, iters, block_ms, only=None):
     """Every stage of a block, timed two ways with HIP events on the launch stream.
     `ms`: inside the running step, from the library's own stopwatch variant of the step entry point
     (an event after every stage, averaged over the blocks of the stack and three steps): operands are
@@ -172,7 +172,7 @@ def kernel_table(wl, st, iters, block_ms):
         st["layers"] = fb.make_layers(st["blocks"])
         st["tmp"] = st["xa"].new_empty(st["xa"].shape)
     in_step = {}
-    reps = 3
+    reps = 0 if only is not None else 3
     for _ in range(reps):
         st["xa"].copy_(st["x_in"])
         _, ms = fb.fastvar_scale_step_timed(st["xa"], sides, sides, wl.step, wl.cache_step, B, k, d, st["layers"],
@@ -180,7 +180,7 @@ def kernel_table(wl, st, iters, block_ms):
         for n, v in ms.items():
             in_step[n] = in_step.get(n, 0.0) + v / reps
 
-    event_ms = max(0.0, (sum(in_step.values()) - block_ms) / len(in_step))
+    event_ms = max(0.0, (sum(in_step.values()) - block_ms) / len(in_step)) if in_step else 0.0
     in_step = {n: max(v - event_ms, 1e-6) for n, v in in_step.items()}
 
     # ---- back to back
@@ -218,6 +218,14 @@ def kernel_table(wl, st, iters, block_ms):
         ("restore", "restore", "hbm", (B * N * D + M * D + B * wl.hc * wl.hc * D) * b2,
          lambda: fb.fastvar_restore(yk, idx, rank, B, k, blk["cache"], wl.hc, wl.hc, wl.h, wl.h, D, y)),
     ]
+    if only is not None:
+        # profiling aid: the named launch alone, back to back (operands cache resident), nothing else
+        for name, stage, bound, work, fn in rows:
+            if name == only:
+                ms_iso = time_kernel(fn, iters)
+                log(f"  {name}: {ms_iso*1e3:.1f} us per launch back to back over {iters} launches")
+                return [dict(kernel=name, ms_back_to_back=round(ms_iso, 5), work=work)]
+        raise SystemExit(f"bench.py: no stage named {only!r}; stages: {[r[0] for r in rows]}")
     out = []
     log(f"  {'stage':28s} {'in the step':>12s} {'back to back':>13s}   (achieved: from the in-step time)")
     for name, stage, bound, work, fn in rows:
@@ -384,6 +392,10 @@ def main():
                     help="instead of the headline step: the model's whole scale schedule, unpruned and with the "
                          "last four steps pruned (one JSON line of its own)")
     ap.add_argument("--kernel-iters", type=int, default=20)
+    ap.add_argument("--kernel-loop", default=None, metavar="STAGE",
+                    help="profiling aid: run only this stage of the kernel table (e.g. 'qkv gemm') back to back "
+                         "--kernel-iters times through its component entry point and exit, no step and no JSON "
+                         "line: what a counter run of the stage with cache-resident operands is taken from")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-table", action="store_true")
     args = ap.parse_args()
@@ -421,6 +433,9 @@ def main():
     log(f"inputs resident after {time.perf_counter()-t0:.1f} s; "
         f"HBM in use {torch.cuda.memory_allocated()/2**30:.2f} GiB")
 
+    if args.kernel_loop:
+        kernel_table(wl, st, args.kernel_iters, 0.0, only=args.kernel_loop)
+        return
     for _ in range(args.warmup):
         run_step(wl, st)
     torch.cuda.synchronize()

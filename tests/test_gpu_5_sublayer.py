@@ -16,6 +16,7 @@ from paper_2503_23367_amd import binding as fb
 from paper_2503_23367_amd import synth
 from gpu_util import (DEV, cache_rows, empty_ws, from_dev_bf16, make_caches, max_rel, to_dev_bf16,
                       upload_weights)
+from test_gpu_4_block import branch_error
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-2
@@ -24,10 +25,9 @@ TINY64 = synth.BlockDims(D=192, H=3, dh=64, F=320)
 
 
 def branch_err(got, ref, base):
-    """Error of the residual branch (result minus the residual input), after allowing for the
-    bf16 rounding of the result itself, relative to the branch magnitude."""
-    e = np.max(np.abs((got.astype(np.float64) - base) - (ref - base)))
-    return max(0.0, e - 2.0 ** -8 * 1.001 * float(np.max(np.abs(ref)))) / float(np.max(np.abs(ref - base)))
+    """Error of the residual branch (result minus the residual input) after one bf16 rounding of the stored
+    result, element by element, relative to the branch magnitude."""
+    return branch_error(got, base, ref - base, ref)
 
 
 HALF_CASES = [

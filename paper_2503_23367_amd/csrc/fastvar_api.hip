@@ -180,12 +180,22 @@ inline void mark(hipStream_t st, int stage) {
     }
 }
 
+// The restoration's fill (Sec. 3.3, Eq. 6), handed to the gather launch of the layer it belongs to: the
+// pruned rows of y_out [B, h*w, D] are written from cache_map while the kept rows are normalised; the
+// layer's last GEMM then scatters the kept rows into y_out, which completes the restored map.
+struct Fill {
+    const int32_t* rank;
+    const void* cache_map;
+    int hc, wc, h, w;
+    void* y_out;
+};
+
 // Attention half of the block on the kept tokens: h1 = x[idx] + proj(attn(LN1(x[idx]))).
 // Scratch used: a, q, rows of the block plan.
 // `scatter`: h1_out is a [B, N, D] map and row m goes to the kept token's own row of it.
 void enqueue_attn(const void* x, int N, const int32_t* idx, int B, int k, const fastvar_dims* d,
                   const fastvar_block_weights* w, void* kc, void* vc, int L0, int L_cap, void* h1_out, void* ws,
-                  hipStream_t st, bool scatter = false) {
+                  hipStream_t st, bool scatter = false, const Fill* fill = nullptr) {
     const BlockPlan bp = block_plan(d, B, k);
     char* base = static_cast<char*>(ws);
     void* buf_a = base + bp.off_a;
@@ -195,7 +205,11 @@ void enqueue_attn(const void* x, int N, const int32_t* idx, int B, int k, const 
     const int M = B * k;
 
     // a1 = LN1(x[idx]); without an index list every token is kept, in order
-    if (idx)
+    if (idx && fill)
+        fv::launch_gather_layernorm_fill(x, idx, B, N, k, d->D, w->ln1_g, w->ln1_b, d->ln_eps, rows, buf_a,
+                                         fill->rank, fill->cache_map, fill->hc, fill->wc, fill->h, fill->w,
+                                         fill->y_out, st);
+    else if (idx)
         fv::launch_gather_layernorm(x, idx, B, N, k, d->D, w->ln1_g, w->ln1_b, d->ln_eps, rows, buf_a, st);
     else
         fv::launch_layernorm(x, M, d->D, w->ln1_g, w->ln1_b, d->ln_eps, buf_a, st);
@@ -232,7 +246,8 @@ void enqueue_attn(const void* x, int N, const int32_t* idx, int B, int k, const 
 // `scatter_rows`: y is a [B, N, D] map and row m goes to row scatter_rows[m] of it (the absolute row of
 // the kept token, as left in the plan's row list by the gather).
 void enqueue_ffn(const void* src, int N, const int32_t* idx, int B, int k, const fastvar_dims* d,
-                 const fastvar_block_weights* w, void* y, void* ws, hipStream_t st, bool scatter = false) {
+                 const fastvar_block_weights* w, void* y, void* ws, hipStream_t st, bool scatter = false,
+                 const Fill* fill = nullptr) {
     const BlockPlan bp = block_plan(d, B, k);
     char* base = static_cast<char*>(ws);
     void* buf_q = base + bp.off_q;
@@ -242,7 +257,11 @@ void enqueue_ffn(const void* src, int N, const int32_t* idx, int B, int k, const
     const int M = B * k;
 
     // a2 = LN2(s)
-    if (idx)
+    if (idx && fill)
+        fv::launch_gather_layernorm_fill(src, idx, B, N, k, d->D, w->ln2_g, w->ln2_b, d->ln_eps, rows, buf_q,
+                                         fill->rank, fill->cache_map, fill->hc, fill->wc, fill->h, fill->w,
+                                         fill->y_out, st);
+    else if (idx)
         fv::launch_gather_layernorm(src, idx, B, N, k, d->D, w->ln2_g, w->ln2_b, d->ln_eps, rows, buf_q, st);
     else
         fv::launch_layernorm(src, M, d->D, w->ln2_g, w->ln2_b, d->ln_eps, buf_q, st);
@@ -280,9 +299,9 @@ void zero_splitk_counters(void* ws, const fastvar_dims* d, int B, int k, hipStre
 
 void enqueue_block(const void* x, int N, const int32_t* idx, int B, int k, const fastvar_dims* d,
                    const fastvar_block_weights* w, void* kc, void* vc, int L0, int L_cap, void* y, void* ws,
-                   hipStream_t st, bool scatter = false) {
+                   hipStream_t st, bool scatter = false, const Fill* fill = nullptr) {
     void* buf_h1 = static_cast<char*>(ws) + block_plan(d, B, k).off_h1;
-    enqueue_attn(x, N, idx, B, k, d, w, kc, vc, L0, L_cap, buf_h1, ws, st);
+    enqueue_attn(x, N, idx, B, k, d, w, kc, vc, L0, L_cap, buf_h1, ws, st, false, idx ? fill : nullptr);
     enqueue_ffn(buf_h1, 0, nullptr, B, k, d, w, y, ws, st, scatter && idx);
 }
 
@@ -478,10 +497,14 @@ int fastvar_step(const void* x, const int32_t* sched_h, const int32_t* sched_w, 
     hipStream_t st = static_cast<hipStream_t>(stream);
     zero_splitk_counters(ws_blk, dims, B, k, st);
     fv::launch_select(x, B, N, D, k, idx_out, rank, nullptr, ws_sel, fv::select_plan(B, N, D), st);
-    // The block's last GEMM writes the kept rows of y_out itself; restoration fills the others.
+    // Restoration has no launch of its own: the pruned rows of y_out are filled by extra workgroups of the
+    // gather + LayerNorm launch, the kept rows are written by the block's last GEMM.  With nothing kept
+    // the step is the upsampled cache.
+    const Fill fill{rank, cache_map, hc, wc, h, w, y_out};
     if (k > 0)
-        enqueue_block(x, N, idx_out, B, k, dims, weights, k_cache, v_cache, L0, L_cap, y_out, ws_blk, st, true);
-    fv::launch_restore(nullptr, rank, B, k, cache_map, hc, wc, h, w, D, y_out, st);
+        enqueue_block(x, N, idx_out, B, k, dims, weights, k_cache, v_cache, L0, L_cap, y_out, ws_blk, st, true, &fill);
+    else
+        fv::launch_restore(nullptr, rank, B, k, cache_map, hc, wc, h, w, D, y_out, st);
     rc = launch_status();
     if (rc == FASTVAR_OK) *kv_len = L0 + k;
     return rc;
@@ -559,17 +582,17 @@ int fastvar_scale_step(const void* x, const int32_t* sched_h, const int32_t* sch
         if (dense) {
             enqueue_block(src, N, nullptr, B, k, dims, ly.weights, ly.k_cache, ly.v_cache, L0, L_cap, dst, ws_blk, st);
         } else {
-            // the restoration of the layer before left the column-sum partials of its output here
-            fv::launch_select(src, B, N, D, k, idx_out, rank, nullptr, ws_sel, sp, st, l > 0);
+            fv::launch_select(src, B, N, D, k, idx_out, rank, nullptr, ws_sel, sp, st);
             mark(st, FASTVAR_STAGE_SELECT);
-            if (k > 0)
+            // restoration rides in the block's first launch (pruned rows) and its last (kept rows)
+            const Fill fill{rank, ly.cache_map, hc, wc, h, w, dst};
+            if (k > 0) {
                 enqueue_block(src, N, idx_out, B, k, dims, ly.weights, ly.k_cache, ly.v_cache, L0, L_cap, dst, ws_blk,
-                              st, true);
-            if (l + 1 < n_layers)
-                fv::launch_restore_colsum(nullptr, rank, B, k, ly.cache_map, hc, wc, h, w, D, dst, ws_sel, sp, st);
-            else
+                              st, true, &fill);
+            } else {
                 fv::launch_restore(nullptr, rank, B, k, ly.cache_map, hc, wc, h, w, D, dst, st);
-            mark(st, FASTVAR_STAGE_RESTORE);
+                mark(st, FASTVAR_STAGE_RESTORE);
+            }
         }
     }
     if (capture &&
@@ -700,14 +723,20 @@ int fastvar_step_sublayer(const void* x, const int32_t* sched_h, const int32_t* 
     const fv::SelectPlan sp = fv::select_plan(B, N, D);
     zero_splitk_counters(ws_blk, dims, B, k_attn, st);
     fv::launch_select(x, B, N, D, k_attn, idx_attn_out, rank, nullptr, ws_sel, sp, st);
+    // each half's restoration rides in its own gather launch (pruned rows) and last GEMM (kept rows)
+    const Fill fill_a{rank, cache_map_attn, hc, wc, h, w, x_mid};
     if (k_attn > 0)
-        enqueue_attn(x, N, idx_attn_out, B, k_attn, dims, weights, k_cache, v_cache, L0, L_cap, x_mid, ws_blk, st, true);
-    // the first restoration also leaves the column-sum partials of x_mid for the second selection
-    fv::launch_restore_colsum(nullptr, rank, B, k_attn, cache_map_attn, hc, wc, h, w, D, x_mid, ws_sel, sp, st);
-    fv::launch_select(x_mid, B, N, D, k_ffn, idx_ffn_out, rank, nullptr, ws_sel, sp, st, true);
+        enqueue_attn(x, N, idx_attn_out, B, k_attn, dims, weights, k_cache, v_cache, L0, L_cap, x_mid, ws_blk, st, true,
+                     &fill_a);
+    else
+        fv::launch_restore(nullptr, rank, B, k_attn, cache_map_attn, hc, wc, h, w, D, x_mid, st);
+    fv::launch_select(x_mid, B, N, D, k_ffn, idx_ffn_out, rank, nullptr, ws_sel, sp, st);
     zero_splitk_counters(ws_blk, dims, B, k_ffn, st);   // the two halves lay the scratch out for their own k
-    if (k_ffn > 0) enqueue_ffn(x_mid, N, idx_ffn_out, B, k_ffn, dims, weights, y_out, ws_blk, st, true);
-    fv::launch_restore(nullptr, rank, B, k_ffn, cache_map_ffn, hc, wc, h, w, D, y_out, st);
+    const Fill fill_f{rank, cache_map_ffn, hc, wc, h, w, y_out};
+    if (k_ffn > 0)
+        enqueue_ffn(x_mid, N, idx_ffn_out, B, k_ffn, dims, weights, y_out, ws_blk, st, true, &fill_f);
+    else
+        fv::launch_restore(nullptr, rank, B, k_ffn, cache_map_ffn, hc, wc, h, w, D, y_out, st);
     rc = launch_status();
     if (rc == FASTVAR_OK) *kv_len = L0 + k_attn;
     return rc;

@@ -634,6 +634,10 @@ void launch_epi(GemmParams& p, hipStream_t stream) {
         case 15: launch_cfg<64, 128, 64, 3, 2, 2, 1, EPI>(p, stream); break;
         case 16: launch_cfg<64, 64, 64, 4, 2, 2, 1, EPI>(p, stream); break;
         case 17: launch_cfg<128, 64, 64, 3, 2, 2, 1, EPI>(p, stream); break;
+        case 21: launch_cfg<256, 256, 32, 4, 2, 4, 1, EPI>(p, stream); break;
+        case 22: launch_cfg<256, 256, 32, 5, 2, 4, 1, EPI>(p, stream); break;
+        case 25: launch_cfg<128, 128, 32, 6, 2, 2, 1, EPI>(p, stream); break;
+        case 26: launch_cfg<128, 128, 64, 4, 2, 2, 1, EPI>(p, stream); break;
         default: launch_cfg<128, 128, 64, 2, 2, 2, 1, EPI>(p, stream); break;
     }
 }

@@ -33,24 +33,13 @@ struct SelectPlan {
     size_t bytes;
 };
 SelectPlan select_plan(int B, int N, int D);
-// partials_ready: the chunk partials of the column sums are already in the scratch (left there by
-// launch_restore_colsum for this very map), so the first pass over x is skipped.
 void launch_select(const void* x, int B, int N, int D, int k, int32_t* idx, int32_t* rank,
-                   float* score_out, void* ws, const SelectPlan& plan, hipStream_t stream,
-                   bool partials_ready = false);
+                   float* score_out, void* ws, const SelectPlan& plan, hipStream_t stream);
 
 // ---- restoration (Sec. 3.3, Eq. 6) ----
 void launch_rank_from_idx(const int32_t* idx, int32_t* rank, int B, int N, int k, hipStream_t stream);
 void launch_restore(const void* y_kept, const int32_t* rank, int B, int k, const void* cache_map,
                     int hc, int wc, int h, int w, int D, void* y_out, hipStream_t stream);
-// Restoration that also leaves, in the selection scratch `select_ws` laid out by `plan`, the fp64
-// column-sum partials of the map it writes: exactly what the first pass of a selection on y_out
-// would compute (same chunks, same order of additions), so that the selection of the next layer can
-// start from them.
-void launch_restore_colsum(const void* y_kept, const int32_t* rank, int B, int k, const void* cache_map,
-                           int hc, int wc, int h, int w, int D, void* y_out, void* select_ws,
-                           const SelectPlan& plan, hipStream_t stream);
-
 // Eq. 2 on fp32 maps [B, h*w, C] (C % 4 == 0): r_out = resample(r_prev [B, hp*wp, C]) + f_k (bf16).
 // r_prev or f_k may be null (not both).
 void launch_residual_accumulate(const float* r_prev, int hp, int wp, const void* f_k, int h, int w, int B, int C,
@@ -63,6 +52,13 @@ void launch_residual_accumulate(const float* r_prev, int hp, int wp, const void*
 void launch_gather_layernorm(const void* x, const int32_t* idx, int B, int N, int k, int D,
                              const void* gamma, const void* beta, float eps, int32_t* rows_out,
                              void* a_out, hipStream_t stream);
+// The same launch carrying the restoration's fill as well (Sec. 3.3, Eq. 6): extra workgroups write every
+// pruned row (rank[b,n] < 0) of y_out [B, N, D] from cache_map [B, hc*wc, D] resampled to h x w (N = h*w).
+// y_out must not be x.  Kept rows of y_out are not touched.
+void launch_gather_layernorm_fill(const void* x, const int32_t* idx, int B, int N, int k, int D, const void* gamma,
+                                  const void* beta, float eps, int32_t* rows_out, void* a_out, const int32_t* rank,
+                                  const void* cache_map, int hc, int wc, int h, int w, void* y_out,
+                                  hipStream_t stream);
 // a = LayerNorm(rows of `in`), M rows.
 void launch_layernorm(const void* in, int M, int D, const void* gamma, const void* beta, float eps,
                       void* a_out, hipStream_t stream);

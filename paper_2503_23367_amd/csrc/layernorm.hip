@@ -2,8 +2,12 @@
 // plain LayerNorm before the MLP.  One wave per token row; the row is held in
 // registers (two-pass mean / biased variance in fp32); 16-byte loads and stores.
 // HBM bound: reads k*D bf16, writes k*D bf16.
+// The gather launch can also carry the restoration's fill (Sec. 3.3, Eq. 6): the pruned slots of the
+// restored map depend only on the selection and on the cached map, not on the block's output, so extra
+// workgroups of the same launch write them while the first ones normalise the kept rows.
 #include "common.h"
 #include "kernels.h"
+#include "resample.h"
 
 namespace fv {
 
@@ -20,14 +24,11 @@ __device__ __forceinline__ void unpack8(const uint4& v, float (&f)[8]) {
 // Row m of the output reads input row (idx ? b*N + idx[m] : m), b = m / k; that
 // row index is also written to rows_out[m] when asked for.
 template <int CH>
-__global__ __launch_bounds__(256) void layernorm_rows_kernel(const bf16_t* __restrict__ in,
-                                                             const int32_t* __restrict__ idx, int N, int k,
-                                                             int M, int D, const bf16_t* __restrict__ gamma,
-                                                             const bf16_t* __restrict__ beta, float eps,
-                                                             int32_t* __restrict__ rows_out,
-                                                             bf16_t* __restrict__ out) {
+__device__ __forceinline__ void layernorm_row(const bf16_t* __restrict__ in, const int32_t* __restrict__ idx, int N,
+                                              int k, int M, int D, const bf16_t* __restrict__ gamma,
+                                              const bf16_t* __restrict__ beta, float eps,
+                                              int32_t* __restrict__ rows_out, bf16_t* __restrict__ out, int m) {
     const int lane = threadIdx.x & 63;
-    const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (m >= M) return;
     size_t src_row = (size_t)m;
     if (idx) src_row = (size_t)(m / k) * N + idx[m];
@@ -94,6 +95,54 @@ __global__ __launch_bounds__(256) void layernorm_rows_kernel(const bf16_t* __res
     }
 }
 
+template <int CH>
+__global__ __launch_bounds__(256) void layernorm_rows_kernel(const bf16_t* __restrict__ in,
+                                                             const int32_t* __restrict__ idx, int N, int k,
+                                                             int M, int D, const bf16_t* __restrict__ gamma,
+                                                             const bf16_t* __restrict__ beta, float eps,
+                                                             int32_t* __restrict__ rows_out,
+                                                             bf16_t* __restrict__ out) {
+    layernorm_row<CH>(in, idx, N, k, M, D, gamma, beta, eps, rows_out, out, blockIdx.x * 4 + (threadIdx.x >> 6));
+}
+
+// The same launch with the restoration's fill behind it: workgroups [0, ln_blocks) normalise the kept rows,
+// the others walk the token rows of the restored map (eight per workgroup, two per wave) and write the
+// pruned ones (rank < 0) from the cached map; kept rows are left to the block's last GEMM.
+struct FillParams {
+    const int32_t* rank;      // [B, N]
+    const bf16_t* cache_map;  // [B, hc*wc, D]
+    bf16_t* y_out;            // [B, N, D]
+    int hc, wc, h, w;
+    int blocks_per_sample;
+};
+constexpr int kFillRowsPerWave = 1;
+
+template <int CH>
+__global__ __launch_bounds__(256) void gather_layernorm_fill_kernel(const bf16_t* __restrict__ in,
+                                                                    const int32_t* __restrict__ idx, int N, int k,
+                                                                    int M, int D, const bf16_t* __restrict__ gamma,
+                                                                    const bf16_t* __restrict__ beta, float eps,
+                                                                    int32_t* __restrict__ rows_out,
+                                                                    bf16_t* __restrict__ out, int ln_blocks,
+                                                                    const FillParams f) {
+    if ((int)blockIdx.x < ln_blocks) {
+        layernorm_row<CH>(in, idx, N, k, M, D, gamma, beta, eps, rows_out, out, blockIdx.x * 4 + (threadIdx.x >> 6));
+        return;
+    }
+    const int fb = blockIdx.x - ln_blocks;
+    const int b = fb / f.blocks_per_sample;
+    const int blk = fb - b * f.blocks_per_sample;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int rr = 0; rr < kFillRowsPerWave; ++rr) {
+        const int n = (blk * 4 + wave) * kFillRowsPerWave + rr;
+        if (n >= N) break;
+        if (f.rank[(size_t)b * N + n] >= 0) continue;
+        fill_pruned_row_any(f.cache_map + (size_t)b * f.hc * f.wc * D, f.hc, f.wc, f.h, f.w, D, n, lane,
+                        f.y_out + ((size_t)b * N + n) * D);
+    }
+}
+
 void dispatch(const void* in, const int32_t* idx, int N, int k, int M, int D, const void* gamma,
               const void* beta, float eps, int32_t* rows_out, void* out, hipStream_t stream) {
     const dim3 grid((M + 3) / 4), block(256);
@@ -115,6 +164,32 @@ void dispatch(const void* in, const int32_t* idx, int N, int k, int M, int D, co
 void launch_gather_layernorm(const void* x, const int32_t* idx, int B, int N, int k, int D, const void* gamma,
                              const void* beta, float eps, int32_t* rows_out, void* a_out, hipStream_t stream) {
     dispatch(x, idx, N, k, B * k, D, gamma, beta, eps, rows_out, a_out, stream);
+}
+
+void launch_gather_layernorm_fill(const void* x, const int32_t* idx, int B, int N, int k, int D, const void* gamma,
+                                  const void* beta, float eps, int32_t* rows_out, void* a_out, const int32_t* rank,
+                                  const void* cache_map, int hc, int wc, int h, int w, void* y_out,
+                                  hipStream_t stream) {
+    const int M = B * k;
+    const int ln_blocks = (M + 3) / 4;
+    FillParams f;
+    f.rank = rank;
+    f.cache_map = static_cast<const bf16_t*>(cache_map);
+    f.y_out = static_cast<bf16_t*>(y_out);
+    f.hc = hc; f.wc = wc; f.h = h; f.w = w;
+    f.blocks_per_sample = (N + 4 * kFillRowsPerWave - 1) / (4 * kFillRowsPerWave);
+    const dim3 grid(ln_blocks + B * f.blocks_per_sample), block(256);
+    const int ch = (D + 511) / 512;
+#define FV_LNF_CASE(CHV)                                                                                 \
+    gather_layernorm_fill_kernel<CHV><<<grid, block, 0, stream>>>(                                       \
+        static_cast<const bf16_t*>(x), idx, N, k, M, D, static_cast<const bf16_t*>(gamma),               \
+        static_cast<const bf16_t*>(beta), eps, rows_out, static_cast<bf16_t*>(a_out), ln_blocks, f)
+    if (ch <= 1) FV_LNF_CASE(1);
+    else if (ch <= 2) FV_LNF_CASE(2);
+    else if (ch <= 4) FV_LNF_CASE(4);
+    else if (ch <= 8) FV_LNF_CASE(8);
+    else FV_LNF_CASE(16);
+#undef FV_LNF_CASE
 }
 
 void launch_layernorm(const void* in, int M, int D, const void* gamma, const void* beta, float eps, void* a_out,

@@ -319,16 +319,15 @@ SelectPlan select_plan(int B, int N, int D) {
 }
 
 void launch_select(const void* x, int B, int N, int D, int k, int32_t* idx, int32_t* rank, float* score_out,
-                   void* ws, const SelectPlan& plan, hipStream_t stream, bool partials_ready) {
+                   void* ws, const SelectPlan& plan, hipStream_t stream) {
     char* w = static_cast<char*>(ws);
     double* partial = reinterpret_cast<double*>(w + plan.off_partial);
     double* mean = reinterpret_cast<double*>(w + plan.off_mean);
     float* score = score_out ? score_out : reinterpret_cast<float*>(w + plan.off_score);
     const bf16_t* xb = static_cast<const bf16_t*>(x);
 
-    if (!partials_ready)
-        colsum_partial_kernel<<<dim3(plan.col_tiles, plan.n_chunks, B), 256, 0, stream>>>(
-            xb, partial, N, D, plan.rows_per_chunk, plan.n_chunks);
+    colsum_partial_kernel<<<dim3(plan.col_tiles, plan.n_chunks, B), 256, 0, stream>>>(
+        xb, partial, N, D, plan.rows_per_chunk, plan.n_chunks);
     colsum_finalize_kernel<<<dim3((D + 63) / 64, B), 64 * kFinGroups, 0, stream>>>(partial, mean, N, D, plan.n_chunks);
     const size_t mu_bytes = (size_t)plan.col_tiles * 512 * sizeof(double);
     score_kernel<<<dim3((N + kScoreRowsPerBlock - 1) / kScoreRowsPerBlock, B), kScoreThreads, mu_bytes, stream>>>(

@@ -305,8 +305,10 @@ def test_timed_scale_step_gives_the_same_result_and_stage_times():
         assert set(ms) == set(fb.STAGES)
         pruned = step > cache_step
         for name, v in ms.items():
-            if name in ("select", "restore") and not pruned:
-                assert v == 0.0
+            # restoration has no launch of its own while something is kept: the pruned rows are filled inside
+            # the gather + LayerNorm launch, the kept rows by the block's last GEMM
+            if (name == "select" and not pruned) or name == "restore":
+                assert v == 0.0, (name, v)
             else:
                 assert 0.0 < v < 50.0, (name, v)
     with pytest.raises(fb.FastvarError):

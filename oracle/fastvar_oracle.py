@@ -36,7 +36,13 @@ design notes):
   * block internals (pre-LN, eps, 1/sqrt(dh), erf-GELU, biases) come from the
     workload definition, not the paper;
   * nothing is masked at decode time: queries of the current scale see every
-    cached key of earlier scales and every kept key of the current scale.
+    cached key of earlier scales and every kept key of the current scale;
+  * rotary positions (Sec. 4.1 names backbones that use them; the paper gives no
+    formula): axial 2-D rotary embedding on q and k, interleaved pairs, the first
+    half of the pairs turned by the token's grid row and the second half by its
+    grid column, each kept token carrying the position of its own slot in the
+    token map (the positions are gathered with the same index set as the tokens);
+    cached keys were rotated when they were appended.
 """
 from __future__ import annotations
 
@@ -164,10 +170,45 @@ def attention(q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: float) -> np.n
     return out
 
 
+def rope2d_angles(h: int, w: int, dh: int, base: float = 10000.0,
+                  ref_h: Optional[int] = None, ref_w: Optional[int] = None) -> np.ndarray:
+    """Rotation angles of the axial 2-D rotary embedding for every slot of an h x w token map.
+
+    Returns [h*w, dh/2] (fp64): pair t of a head's dh/2 interleaved pairs (2t, 2t+1) is turned by
+    angle[n, t] = pos * base**(-t'/(dh/4)), where for the first dh/4 pairs pos is the row coordinate of
+    token n = i*w + j and t' = t, for the other dh/4 pairs pos is the column coordinate and
+    t' = t - dh/4.  Coordinates are i * ref_h/h and j * ref_w/w: the grid of this scale laid over a
+    reference grid (by default its own, i.e. plain integer coordinates), so that the maps of a
+    multi-scale schedule can share one coordinate frame.
+    """
+    assert dh % 4 == 0
+    ref_h = h if ref_h is None else ref_h
+    ref_w = w if ref_w is None else ref_w
+    q = dh // 4
+    freq = np.asarray([float(base) ** (-(t / q)) for t in range(q)], dtype=F64)
+    ii = np.repeat(np.arange(h, dtype=F64) * (float(ref_h) / h), w)
+    jj = np.tile(np.arange(w, dtype=F64) * (float(ref_w) / w), h)
+    return np.concatenate([ii[:, None] * freq[None, :], jj[:, None] * freq[None, :]], axis=1)
+
+
+def apply_rope(v: np.ndarray, angles: np.ndarray) -> np.ndarray:
+    """Turn the interleaved pairs of v [..., T, H, dh] by angles [..., T, dh/2] (the same for every head):
+    (a, b) -> (a cos - b sin, a sin + b cos)."""
+    v = np.asarray(v, F64)
+    c = np.cos(angles)[..., None, :]
+    s = np.sin(angles)[..., None, :]
+    a, b = v[..., 0::2], v[..., 1::2]
+    out = np.empty_like(v)
+    out[..., 0::2] = a * c - b * s
+    out[..., 1::2] = a * s + b * c
+    return out
+
+
 def block_forward_pruned(xk: np.ndarray, W: Dict[str, np.ndarray], H: int,
                          k_cache: np.ndarray, v_cache: np.ndarray,
                          eps: float = 1e-6, scale: Optional[float] = None,
-                         return_parts: bool = False, rows: Optional[np.ndarray] = None):
+                         return_parts: bool = False, rows: Optional[np.ndarray] = None,
+                         rope: Optional[np.ndarray] = None):
     """One pre-LN block on kept tokens xk [B,k,D].
 
     k_cache / v_cache [B, L0, H, dh] hold the keys/values of all earlier
@@ -181,6 +222,11 @@ def block_forward_pruned(xk: np.ndarray, W: Dict[str, np.ndarray], H: int,
     the outputs to those kept tokens: every kept token still contributes its
     key and value, but queries, attention and the MLP are evaluated only for
     the chosen rows, so single outputs of a large step can be checked.
+
+    `rope` [B, k, dh/2]: rotary angles of the kept tokens (rope2d_angles of the
+    token map, gathered with the kept index set).  Queries and new keys are
+    turned by them before attention; the returned k_new are the turned keys
+    (what enters the cache).  The cached keys are taken as they are.
     """
     xk = np.asarray(xk, F64)
     B, k, D = xk.shape
@@ -192,6 +238,9 @@ def block_forward_pruned(xk: np.ndarray, W: Dict[str, np.ndarray], H: int,
     q = qkv[..., 0 * D:1 * D].reshape(B, k, H, dh)
     kn = qkv[..., 1 * D:2 * D].reshape(B, k, H, dh)
     vn = qkv[..., 2 * D:3 * D].reshape(B, k, H, dh)
+    if rope is not None:
+        q = apply_rope(q, rope)
+        kn = apply_rope(kn, rope)
     if rows is not None:
         rows = np.asarray(rows, dtype=np.int64)
         q = q[:, rows]

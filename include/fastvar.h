@@ -38,6 +38,19 @@
  *   v_cache [B, H, dh, L_cap]   value columns, cache position contiguous
  * Rows / columns [0, L0) hold the earlier scales; a block call writes
  * positions [L0, L0+k) and the caller then treats the length as L0+k.
+ * A caller that holds keys and values token-major, [B, L, H, dh], fills these
+ * caches once with  k_cache = K.permute(0, 2, 1, 3)  (positions [0, L) of an
+ * L_cap-long axis) and  v_cache = V.permute(0, 2, 3, 1);  rows the library
+ * appends read back as  K[b, l, h, :] = k_cache[b, h, l, :]  and
+ * V[b, l, h, :] = v_cache[b, h, :, l].
+ *
+ * Scratch: there is no single workspace-size function; each entry point has
+ * its own (fastvar_select_workspace_bytes, fastvar_block_workspace_bytes,
+ * fastvar_restore_workspace_bytes, fastvar_step_workspace_bytes,
+ * fastvar_step_sublayer_workspace_bytes), because the selection, the block
+ * and the whole step need different buffers and a caller of one stage should
+ * not pay for the others.  fastvar_step_workspace_bytes(dims, B, N, k) is the
+ * one that covers a whole step.
  */
 #ifndef FASTVAR_H
 #define FASTVAR_H
@@ -412,6 +425,41 @@ int fastvar_gemm_bf16(const void* A, const void* W, const void* bias, const void
 int fastvar_qkv_gemm(const void* a, const void* w_qkv, const void* b_qkv, int B, int k,
                      const fastvar_dims* dims /* host */, void* q_out, void* k_cache, void* v_cache,
                      int L0, int L_cap, void* stream);
+
+/*
+ * Rotary positions (Sec. 4.1: the backbones the method is applied to, HART and
+ * Infinity, carry 2-D rotary position embeddings; the paper gives no formula,
+ * the reading is in the design notes).  Axial 2-D rotary embedding on
+ * interleaved pairs: pair t of a head's dh/2 pairs (channels 2t, 2t+1) is
+ * turned by  pos * base^(-t'/(dh/4)),  the first dh/4 pairs by the grid row of
+ * the token's slot (t' = t), the others by its grid column (t' = t - dh/4);
+ * coordinates are i * ref_h / h and j * ref_w / w, i.e. the h x w map laid over
+ * a ref_h x ref_w reference grid (pass ref = own size for integer coordinates).
+ * What makes it part of this path: a kept token keeps the position of its own
+ * slot, so the tables are read through the kept index set.
+ *
+ * fastvar_rope2d_table fills cos_out / sin_out [h*w, dh/2] fp32 (device,
+ * 16-byte aligned; dh a multiple of 8) for every slot of the map.
+ */
+int fastvar_rope2d_table(int h, int w, int dh, double base, int ref_h, int ref_w, float* cos_out, float* sin_out,
+                         void* stream);
+
+/* fastvar_qkv_gemm with q and the new keys turned (values are not): row m of
+ * `a` is the token at slot idx[m] of its sample's map of N slots (idx [B, k],
+ * or NULL when k == N: row t is slot t); tables from fastvar_rope2d_table for
+ * that map.  The cache receives the turned keys; earlier cache rows are taken
+ * as already turned. */
+int fastvar_qkv_gemm_rope(const void* a, const void* w_qkv, const void* b_qkv, const int32_t* idx, int B, int N,
+                          int k, const fastvar_dims* dims /* host */, const float* rope_cos, const float* rope_sin,
+                          void* q_out, void* k_cache, void* v_cache, int L0, int L_cap, void* stream);
+
+/* fastvar_block_forward_pruned with rotary positions on q and the new keys
+ * (same arguments, plus the two tables [N, dh/2] of the map x). */
+int fastvar_block_forward_pruned_rope(const void* x, int N, const int32_t* idx, int B, int k,
+                                      const fastvar_dims* dims /* host */,
+                                      const fastvar_block_weights* weights /* host */, const float* rope_cos,
+                                      const float* rope_sin, void* k_cache, void* v_cache, int L0, int L_cap,
+                                      void* y_kept_out, void* ws, size_t ws_bytes, void* stream);
 
 /* o[B*k, D] = softmax(q K^T * softmax_scale) V per head over cache positions
  * [0, L), no mask (Sec. 3.1: queries of the current scale see the cached keys

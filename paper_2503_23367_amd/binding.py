@@ -57,7 +57,8 @@ EXPORTS = ("fastvar_version", "fastvar_strerror", "fastvar_keep_count", "fastvar
            "fastvar_step", "fastvar_scale_step", "fastvar_scale_step_timed",
            "fastvar_step_sublayer_workspace_bytes", "fastvar_attn_forward_pruned",
            "fastvar_ffn_forward_pruned", "fastvar_step_sublayer", "fastvar_layernorm", "fastvar_gemm_bf16",
-           "fastvar_qkv_gemm", "fastvar_attention")
+           "fastvar_qkv_gemm", "fastvar_attention", "fastvar_rope2d_table", "fastvar_qkv_gemm_rope",
+           "fastvar_block_forward_pruned_rope")
 
 
 def lib() -> C.CDLL:
@@ -128,6 +129,13 @@ def lib() -> C.CDLL:
     L.fastvar_qkv_gemm.argtypes = [vp, vp, vp, i32, i32, C.POINTER(Dims), vp, vp, vp, i32, i32, vp]
     L.fastvar_attention.restype = i32
     L.fastvar_attention.argtypes = [vp, vp, vp, i32, i32, C.POINTER(Dims), i32, i32, vp, vp]
+    L.fastvar_rope2d_table.restype = i32
+    L.fastvar_rope2d_table.argtypes = [i32, i32, i32, C.c_double, i32, i32, vp, vp, vp]
+    L.fastvar_qkv_gemm_rope.restype = i32
+    L.fastvar_qkv_gemm_rope.argtypes = [vp, vp, vp, vp, i32, i32, i32, C.POINTER(Dims), vp, vp, vp, vp, vp, i32, i32, vp]
+    L.fastvar_block_forward_pruned_rope.restype = i32
+    L.fastvar_block_forward_pruned_rope.argtypes = [vp, i32, vp, i32, i32, C.POINTER(Dims), C.POINTER(BlockWeights),
+                                                    vp, vp, vp, vp, i32, i32, vp, vp, sz, vp]
     _lib = L
     return L
 
@@ -371,3 +379,24 @@ def fastvar_attention(q, k_cache, v_cache, B, k, dims: Dims, L, L_cap, o) -> Non
     rc = lib().fastvar_attention(_ptr(q), _ptr(k_cache), _ptr(v_cache), B, k, C.byref(dims), L, L_cap,
                                  _ptr(o), _stream())
     _check(rc, "fastvar_attention")
+
+
+def fastvar_rope2d_table(h, w, dh, base, ref_h, ref_w, cos_out, sin_out) -> None:
+    rc = lib().fastvar_rope2d_table(h, w, dh, base, ref_h, ref_w, _ptr(cos_out), _ptr(sin_out), _stream())
+    _check(rc, "fastvar_rope2d_table")
+
+
+def fastvar_qkv_gemm_rope(a, w_qkv, b_qkv, idx, B, N, k, dims: Dims, rope_cos, rope_sin, q_out, k_cache, v_cache,
+                          L0, L_cap) -> None:
+    rc = lib().fastvar_qkv_gemm_rope(_ptr(a), _ptr(w_qkv), _ptr(b_qkv), _ptr(idx), B, N, k, C.byref(dims),
+                                     _ptr(rope_cos), _ptr(rope_sin), _ptr(q_out), _ptr(k_cache), _ptr(v_cache),
+                                     L0, L_cap, _stream())
+    _check(rc, "fastvar_qkv_gemm_rope")
+
+
+def fastvar_block_forward_pruned_rope(x, N, idx, B, k, dims: Dims, weights: BlockWeights, rope_cos, rope_sin,
+                                      k_cache, v_cache, L0, L_cap, y_kept_out, ws) -> None:
+    rc = lib().fastvar_block_forward_pruned_rope(_ptr(x), N, _ptr(idx), B, k, C.byref(dims), C.byref(weights),
+                                                 _ptr(rope_cos), _ptr(rope_sin), _ptr(k_cache), _ptr(v_cache),
+                                                 L0, L_cap, _ptr(y_kept_out), _ptr(ws), _nbytes(ws), _stream())
+    _check(rc, "fastvar_block_forward_pruned_rope")

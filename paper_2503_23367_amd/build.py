@@ -17,7 +17,7 @@ CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libfastvar.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["fastvar_api.hip", "select.hip", "restore.hip", "layernorm.hip", "gemm.hip", "attention.hip"]
+SOURCES = ["fastvar_api.hip", "select.hip", "restore.hip", "layernorm.hip", "rope.hip", "gemm.hip", "attention.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -190,12 +190,18 @@ struct Fill {
     void* y_out;
 };
 
+// Rotary tables [N, dh/2] fp32 for the map the block's tokens come from (fastvar_rope2d_table).
+struct Rope {
+    const float* cos;
+    const float* sin;
+};
+
 // Attention half of the block on the kept tokens: h1 = x[idx] + proj(attn(LN1(x[idx]))).
 // Scratch used: a, q, rows of the block plan.
 // `scatter`: h1_out is a [B, N, D] map and row m goes to the kept token's own row of it.
 void enqueue_attn(const void* x, int N, const int32_t* idx, int B, int k, const fastvar_dims* d,
                   const fastvar_block_weights* w, void* kc, void* vc, int L0, int L_cap, void* h1_out, void* ws,
-                  hipStream_t st, bool scatter = false, const Fill* fill = nullptr) {
+                  hipStream_t st, bool scatter = false, const Fill* fill = nullptr, const Rope* rope = nullptr) {
     const BlockPlan bp = block_plan(d, B, k);
     char* base = static_cast<char*>(ws);
     void* buf_a = base + bp.off_a;
@@ -220,6 +226,9 @@ void enqueue_attn(const void* x, int N, const int32_t* idx, int B, int k, const 
     g.q_out = buf_q; g.k_cache = kc; g.v_cache = vc;
     g.D = d->D; g.H = d->H; g.dh = d->dh; g.k_tokens = k; g.L0 = L0; g.L_cap = L_cap;
     g.splitk_ws = sk;
+    if (rope) {   // q and the new keys are turned by the angles of each kept token's own slot
+        g.rope_cos = rope->cos; g.rope_sin = rope->sin; g.rope_rows = idx ? rows : nullptr; g.rope_N = N;
+    }
     fv::launch_gemm(fv::EPI_QKV, g, st);
     mark(st, FASTVAR_STAGE_QKV);
     // o = softmax(q K^T * scale) V over cache positions [0, L0+k)
@@ -299,9 +308,9 @@ void zero_splitk_counters(void* ws, const fastvar_dims* d, int B, int k, hipStre
 
 void enqueue_block(const void* x, int N, const int32_t* idx, int B, int k, const fastvar_dims* d,
                    const fastvar_block_weights* w, void* kc, void* vc, int L0, int L_cap, void* y, void* ws,
-                   hipStream_t st, bool scatter = false, const Fill* fill = nullptr) {
+                   hipStream_t st, bool scatter = false, const Fill* fill = nullptr, const Rope* rope = nullptr) {
     void* buf_h1 = static_cast<char*>(ws) + block_plan(d, B, k).off_h1;
-    enqueue_attn(x, N, idx, B, k, d, w, kc, vc, L0, L_cap, buf_h1, ws, st, false, idx ? fill : nullptr);
+    enqueue_attn(x, N, idx, B, k, d, w, kc, vc, L0, L_cap, buf_h1, ws, st, false, idx ? fill : nullptr, rope);
     enqueue_ffn(buf_h1, 0, nullptr, B, k, d, w, y, ws, st, scatter && idx);
 }
 
@@ -425,6 +434,33 @@ int fastvar_block_forward_pruned(const void* x, int N, const int32_t* idx, int B
     zero_splitk_counters(ws, dims, B, k, static_cast<hipStream_t>(stream));
     enqueue_block(x, N, idx, B, k, dims, weights, k_cache, v_cache, L0, L_cap, y_kept_out, ws,
                   static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+int fastvar_rope2d_table(int h, int w, int dh, double base, int ref_h, int ref_w, float* cos_out, float* sin_out,
+                         void* stream) {
+    if (!cos_out || !sin_out || h <= 0 || w <= 0 || ref_h <= 0 || ref_w <= 0 || !(base > 0.0) || !isfinite(base))
+        return FASTVAR_EINVAL;
+    if ((long)h * w > FASTVAR_MAX_TOKENS) return FASTVAR_ECAPACITY;
+    if (dh <= 0 || dh % 8 != 0 || !aligned16(cos_out) || !aligned16(sin_out)) return FASTVAR_EALIGN;
+    fv::launch_rope2d_table(h, w, dh, base, ref_h, ref_w, cos_out, sin_out, static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+int fastvar_block_forward_pruned_rope(const void* x, int N, const int32_t* idx, int B, int k,
+                                      const fastvar_dims* dims, const fastvar_block_weights* weights,
+                                      const float* rope_cos, const float* rope_sin, void* k_cache, void* v_cache,
+                                      int L0, int L_cap, void* y_kept_out, void* ws, size_t ws_bytes, void* stream) {
+    if (!rope_cos || !rope_sin) return FASTVAR_EINVAL;
+    if (!aligned16(rope_cos) || !aligned16(rope_sin)) return FASTVAR_EALIGN;
+    const int rc = check_block(x, N, idx, B, k, dims, weights, k_cache, v_cache, L0, L_cap, y_kept_out, ws,
+                               ws_bytes);
+    if (rc) return rc;
+    if (k == 0) return FASTVAR_OK;
+    const Rope rope{rope_cos, rope_sin};
+    zero_splitk_counters(ws, dims, B, k, static_cast<hipStream_t>(stream));
+    enqueue_block(x, N, idx, B, k, dims, weights, k_cache, v_cache, L0, L_cap, y_kept_out, ws,
+                  static_cast<hipStream_t>(stream), false, nullptr, &rope);
     return launch_status();
 }
 
@@ -789,6 +825,28 @@ int fastvar_qkv_gemm(const void* a, const void* w_qkv, const void* b_qkv, int B,
     g.A = a; g.W = w_qkv; g.bias = b_qkv; g.M = B * k; g.N = 3 * dims->D; g.K = dims->D;
     g.q_out = q_out; g.k_cache = k_cache; g.v_cache = v_cache;
     g.D = dims->D; g.H = dims->H; g.dh = dims->dh; g.k_tokens = k; g.L0 = L0; g.L_cap = L_cap;
+    fv::launch_gemm(fv::EPI_QKV, g, static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+int fastvar_qkv_gemm_rope(const void* a, const void* w_qkv, const void* b_qkv, const int32_t* idx, int B, int N,
+                          int k, const fastvar_dims* dims, const float* rope_cos, const float* rope_sin, void* q_out,
+                          void* k_cache, void* v_cache, int L0, int L_cap, void* stream) {
+    const int rc = check_dims(dims);
+    if (rc) return rc;
+    if (!a || !w_qkv || !q_out || !k_cache || !v_cache || !rope_cos || !rope_sin || B <= 0 || N <= 0 || k <= 0 ||
+        k > N || L0 < 0 || L_cap <= 0 || (!idx && k != N))
+        return FASTVAR_EINVAL;
+    if ((long)L0 + k > L_cap) return FASTVAR_ECAPACITY;
+    if (L_cap % 8 != 0 || !aligned16(a) || !aligned16(w_qkv) || !aligned16(q_out) || !aligned16(k_cache) ||
+        !aligned16(v_cache) || (b_qkv && !aligned16(b_qkv)) || !aligned16(rope_cos) || !aligned16(rope_sin))
+        return FASTVAR_EALIGN;
+    if ((double)B * k * 3.0 * dims->D >= 2147483648.0) return FASTVAR_ECAPACITY;
+    fv::GemmArgs g{};
+    g.A = a; g.W = w_qkv; g.bias = b_qkv; g.M = B * k; g.N = 3 * dims->D; g.K = dims->D;
+    g.q_out = q_out; g.k_cache = k_cache; g.v_cache = v_cache;
+    g.D = dims->D; g.H = dims->H; g.dh = dims->dh; g.k_tokens = k; g.L0 = L0; g.L_cap = L_cap;
+    g.rope_cos = rope_cos; g.rope_sin = rope_sin; g.rope_rows = idx; g.rope_N = N;
     fv::launch_gemm(fv::EPI_QKV, g, static_cast<hipStream_t>(stream));
     return launch_status();
 }

@@ -37,6 +37,11 @@ __device__ __forceinline__ float gelu_fast(float v) {
     return v * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
+// Internal fourth epilogue: EPI_QKV with the rotary embedding of q and the new keys (an instantiation of its
+// own, so that the plain QKV GEMM carries none of its registers).
+constexpr int EPI_QKV_ROPE = 3;
+constexpr bool is_qkv(int epi) { return epi == EPI_QKV || epi == EPI_QKV_ROPE; }
+
 struct GemmParams {
     const bf16_t* A;
     const bf16_t* W;
@@ -50,6 +55,10 @@ struct GemmParams {
     bf16_t* k_cache;
     bf16_t* v_cache;
     int D, H, dh, k_tokens, L0, L_cap;
+    const float* rope_cos;     // optional [rope_N, dh/2] tables: q and the new keys are turned in the epilogue
+    const float* rope_sin;
+    const int32_t* rope_rows;  // slot of output row m = rope_rows[m] % rope_N (NULL: its token index)
+    int rope_N;
     int tiles_m, tiles_n;
     int splits;        // split-K slices (grid.y); 1 unless the kernel is instantiated with SK
     float* sk_part;    // [tile][slice][BM*BN] fp32 partial tiles, accumulator-register order
@@ -62,12 +71,14 @@ struct ColDest {
     bf16_t* ptr;
     long batch_stride;
     int row_stride;
+    int d;   // EPI_QKV: channel of the column inside its head
 };
 
 template <int EPI>
 __device__ __forceinline__ ColDest col_dest(const GemmParams& p, int n) {
     ColDest c;
-    if (EPI != EPI_QKV) {
+    c.d = 0;
+    if (!is_qkv(EPI)) {
         c.ptr = p.out + n;
         c.row_stride = p.N;
         c.batch_stride = (long)p.k_tokens * p.N;
@@ -77,6 +88,7 @@ __device__ __forceinline__ ColDest col_dest(const GemmParams& p, int n) {
     const int f = n - sec * p.D;
     const int hh = f / p.dh;
     const int d = f - hh * p.dh;
+    c.d = d;
     if (sec == 0) {
         c.ptr = p.q_out + f;
         c.row_stride = p.D;
@@ -455,7 +467,7 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
     const bool col_ok = ncol < p.N && rsub < RPP;  // N % 8 == 0: the whole group is in or out
     const ColDest cd = col_dest<EPI>(p, col_ok ? ncol : 0);
     bool row_path = col_ok;
-    if (EPI == EPI_QKV) row_path = col_ok && ncol < 2 * p.D;  // the V section is stored transposed below
+    if (is_qkv(EPI)) row_path = col_ok && ncol < 2 * p.D;  // the V section is stored transposed below
 
     static_for<0, MI>([&](auto mi_c) {
         constexpr int mi = decltype(mi_c)::value;
@@ -471,7 +483,7 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
         const int m_slab = m0 + wm * WTM + mi * 32;
         // (sample, token) of this lane's first row; later passes step by RPP rows
         int bq = 0, tq = 0;
-        if (EPI == EPI_QKV) {
+        if (is_qkv(EPI)) {
             bq = (m_slab + rsub) / p.k_tokens;
             tq = (m_slab + rsub) - bq * p.k_tokens;
         }
@@ -491,24 +503,39 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
                     v[4] += bf16_lo(rr.z); v[5] += bf16_hi(rr.z);
                     v[6] += bf16_lo(rr.w); v[7] += bf16_hi(rr.w);
                 }
+                if (EPI == EPI_QKV_ROPE) {
+                    // rotary embedding of q and the new keys (this path holds no V column): the lane's
+                    // eight columns are four interleaved pairs of one head, turned by the angles of the
+                    // token's own slot in the map
+                    const int slot = p.rope_rows ? p.rope_rows[m] % p.rope_N : tq;
+                    const size_t at = (size_t)slot * (p.dh >> 1) + (cd.d >> 1);
+                    const f32x4_t cs = *reinterpret_cast<const f32x4_t*>(p.rope_cos + at);
+                    const f32x4_t sn = *reinterpret_cast<const f32x4_t*>(p.rope_sin + at);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float a = v[2 * j], b = v[2 * j + 1];
+                        v[2 * j] = a * cs[j] - b * sn[j];
+                        v[2 * j + 1] = a * sn[j] + b * cs[j];
+                    }
+                }
                 u32x4_t o;
                 o.x = pack_bf16x2(v[0], v[1]);
                 o.y = pack_bf16x2(v[2], v[3]);
                 o.z = pack_bf16x2(v[4], v[5]);
                 o.w = pack_bf16x2(v[6], v[7]);
                 bf16_t* dst;
-                if (EPI == EPI_QKV)
+                if (is_qkv(EPI))
                     dst = cd.ptr + (long)bq * cd.batch_stride + (long)tq * cd.row_stride;
                 else
                     dst = p.out + (EPI == EPI_BIAS_RES && p.out_rows ? (size_t)p.out_rows[m] : (size_t)m) * p.N + ncol;
                 *reinterpret_cast<u32x4_t*>(dst) = o;
             }
-            if (EPI == EPI_QKV) {
+            if (is_qkv(EPI)) {
                 tq += RPP;
                 while (tq >= p.k_tokens) { tq -= p.k_tokens; ++bq; }
             }
         }
-        if (EPI == EPI_QKV) {
+        if (is_qkv(EPI)) {
             // V section: cache positions are contiguous along the token (row) axis, so
             // lanes walk the rows of a column: lane l handles row l%32 of columns
             // l/32, l/32+2, ... of each 32-column block that lies in the V section.
@@ -602,18 +629,19 @@ void launch_epi(GemmParams& p, hipStream_t stream) {
     const long tiles128 = (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
     // fraction of the chip's tile slots that do useful work when `tiles` tiles run `slots` at a time
     auto fill = [](long tiles, long slots) { return (double)tiles / (double)(((tiles + slots - 1) / slots) * slots); };
-    const long big = EPI == EPI_QKV ? tiles192 : tiles256;
+    const long big = is_qkv(EPI) ? tiles192 : tiles256;
     int cfg;
     if (big >= 192 && fill(big, 256) >= 0.8)
-        cfg = EPI == EPI_QKV ? 12 : 11;
+        cfg = is_qkv(EPI) ? 12 : 11;
     else if (tiles128 <= 64)
         cfg = 16;
     else if (tiles128 <= 128)
         cfg = 17;
     else   // one three-stage workgroup per CU, or two two-stage ones (about 8 % faster per tile when both fill)
         cfg = 1.08 * fill(tiles128, 512) >= fill(tiles128, 256) ? 6 : 7;
-    if (gemm_cfg_override(EPI) >= 0) cfg = gemm_cfg_override(EPI);
-    if (p.sk_part && gemm_cfg_override(EPI) < 0) {
+    constexpr int knob = EPI == EPI_QKV_ROPE ? (int)EPI_QKV : EPI;
+    if (gemm_cfg_override(knob) >= 0) cfg = gemm_cfg_override(knob);
+    if (p.sk_part && gemm_cfg_override(knob) < 0) {
         // few output tiles: split K between workgroups (the caller sized the scratch with the same plan)
         const SplitKPlan sk = gemm_splitk_plan(p.M, p.N, p.K);
         if (sk.splits > 1) {
@@ -684,6 +712,7 @@ void launch_gemm(GemmEpilogue epi, const GemmArgs& a, hipStream_t stream) {
     p.k_cache = static_cast<bf16_t*>(a.k_cache);
     p.v_cache = static_cast<bf16_t*>(a.v_cache);
     p.D = a.D; p.H = a.H; p.dh = a.dh; p.k_tokens = a.k_tokens; p.L0 = a.L0; p.L_cap = a.L_cap;
+    p.rope_cos = a.rope_cos; p.rope_sin = a.rope_sin; p.rope_rows = a.rope_rows; p.rope_N = a.rope_N;
     p.tiles_m = p.tiles_n = 0;
     p.splits = 1;
     p.sk_part = nullptr;
@@ -696,7 +725,10 @@ void launch_gemm(GemmEpilogue epi, const GemmArgs& a, hipStream_t stream) {
         }
     }
     switch (epi) {
-        case EPI_QKV: launch_epi<EPI_QKV>(p, stream); break;
+        case EPI_QKV:
+            if (a.rope_cos) launch_epi<EPI_QKV_ROPE>(p, stream);
+            else launch_epi<EPI_QKV>(p, stream);
+            break;
         case EPI_BIAS_RES: launch_epi<EPI_BIAS_RES>(p, stream); break;
         case EPI_BIAS_GELU: launch_epi<EPI_BIAS_GELU>(p, stream); break;
     }

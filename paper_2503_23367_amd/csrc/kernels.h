@@ -83,6 +83,13 @@ struct GemmArgs {
     void* k_cache;  // [B, H, L_cap, dh]
     void* v_cache;  // [B, H, dh, L_cap]
     int D, H, dh, k_tokens, L0, L_cap;
+    // EPI_QKV, optional: rotary embedding of q and the new keys.  rope_cos / rope_sin [rope_N, dh/2] fp32
+    // (launch_rope2d_table); the slot of output row m is rope_rows[m] % rope_N (a row list that is absolute,
+    // b*N + n, or per sample, n, gives the same slot), or with rope_rows == NULL its token index m % k_tokens.
+    const float* rope_cos = nullptr;
+    const float* rope_sin = nullptr;
+    const int32_t* rope_rows = nullptr;
+    int rope_N = 0;
     // Optional scratch for the split-K path of shapes with few output tiles (gemm_splitk_plan):
     // [counters | partial tiles]; the counters must be zero on entry and are zero again on exit.
     void* splitk_ws = nullptr;
@@ -106,6 +113,10 @@ struct SplitKPlan {
 SplitKPlan gemm_splitk_plan(int M, int N, int K);
 // zero the n counters at the head of a split-K scratch area
 void launch_zero_i32(int32_t* p, int n, hipStream_t stream);
+
+// cos / sin tables [h*w, dh/2] fp32 of the axial 2-D rotary embedding (see rope.hip).
+void launch_rope2d_table(int h, int w, int dh, double base, int ref_h, int ref_w, float* cos_out, float* sin_out,
+                         hipStream_t stream);
 
 struct AttnArgs {
     const void* q;        // [B*k, D] bf16 (feature = head*dh + d)

@@ -976,32 +976,43 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
     }
 #undef FP_PUBLISH
     if (KVS) {
-        // Every key range leaves its partial result (statistics, then the accumulator, register-major)
-        // and counts itself in at the query tile's counter; the workgroup that arrives last combines
-        // all ranges exactly, in range order (its own from registers), normalises and stores.  The
-        // partials and the counter are accessed with device-scope relaxed atomics, coherent across
-        // the chip's L2s by themselves; every thread waits for its own stores to be acknowledged
-        // before the barrier that precedes the count.  Nobody waits for anybody.
-        constexpr int SLOTS = 2 * QB + DB * QB * 16;
+        // Every key range leaves its partial result (statistics, then the accumulator) and counts itself in at
+        // the query tile's counter; the workgroup that arrives last combines all ranges exactly, in range
+        // order (its own from registers), normalises and stores.  The partials go out and come back as
+        // 16 bytes per lane with the device-scope cache policy (written through to, and read from, the
+        // memory side of the chip's eight L2s, where they are coherent by themselves); the counter is a
+        // device-scope relaxed atomic; every thread waits for its own stores to be acknowledged before the
+        // barrier that precedes the count.  Nobody waits for anybody.
+        // Layout per (query tile, range): [vector][QG*64 lanes][4 floats]; vector 0 holds the statistics
+        // (running maxima, then row sums, of the lane's two query blocks), vector 1 + (db*QB + qb)*4 + g
+        // the accumulator registers 4g .. 4g+3 of block (db, qb).
+        static_assert(QB == 2, "the statistics of the two query blocks fill one 16-byte vector");
+        constexpr int VECS = 1 + DB * QB * 4;
+        constexpr int kDeviceScope = 16;   // cache-policy bit of the buffer accesses below
         const size_t tile_id = ((size_t)b * p.H + head) * p.q_tiles + q_tile;
-        float* part0 = p.part + tile_id * p.splits * (size_t)(SLOTS * (QG * 64)) + qg * 64 + lane;
-        const size_t sstride = (size_t)SLOTS * (QG * 64);
+        const uint32_t vstride = (uint32_t)VECS * (QG * 64) * 16;     // bytes per (tile, range)
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            reinterpret_cast<char*>(p.part) + tile_id * p.splits * (size_t)vstride, 0, 0x7FFFFFFF, 0x00020000);
+        const uint32_t lane_off = (uint32_t)(qg * 64 + lane) * 16u;
         float l_tot[QB];
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) l_tot[qb] = l_run[qb] + other_half(l_run[qb]);
         if (kh == 0) {
-            float* part = part0 + split * sstride;
+            const uint32_t mine = (uint32_t)split * vstride + lane_off;
+            const f32x4_t st = {m_run[0], m_run[1], l_tot[0], l_tot[1]};
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, st), rsrc, mine, 0, kDeviceScope);
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                __hip_atomic_store(part + qb * (QG * 64), m_run[qb], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(part + (QB + qb) * (QG * 64), l_tot[qb], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int db = 0; db < DB; ++db)
 #pragma unroll
-                for (int db = 0; db < DB; ++db)
+                for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        __hip_atomic_store(part + (2 * QB + (db * QB + qb) * 16 + r) * (QG * 64), acc[db][qb][r],
-                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
+                    for (int g = 0; g < 4; ++g) {
+                        const f32x4_t v = {acc[db][qb][4 * g + 0], acc[db][qb][4 * g + 1], acc[db][qb][4 * g + 2],
+                                           acc[db][qb][4 * g + 3]};
+                        __builtin_amdgcn_raw_buffer_store_b128(
+                            __builtin_bit_cast(u32x4_t, v), rsrc,
+                            mine + (uint32_t)(1 + (db * QB + qb) * 4 + g) * (QG * 64 * 16), 0, kDeviceScope);
+                    }
         }
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(attn_waitcnt(0, true));   // own stores acknowledged
@@ -1014,24 +1025,25 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
         if (arrived != p.splits - 1) return;
         if (tid == 0) __hip_atomic_store(p.split_cnt + tile_id, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (kh != 0) return;
+        // statistics of every range (at most four), own from registers
+        float ms[4][QB], ls[4][QB];
+        for (int s2 = 0; s2 < p.splits; ++s2) {
+            f32x4_t st = {m_run[0], m_run[1], l_tot[0], l_tot[1]};
+            if (s2 != split)
+                st = __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
+                                                     rsrc, (uint32_t)s2 * vstride + lane_off, 0, kDeviceScope));
+            ms[s2 & 3][0] = st[0]; ms[s2 & 3][1] = st[1];
+            ls[s2 & 3][0] = st[2]; ls[s2 & 3][1] = st[3];
+        }
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-            // statistics of every range (at most four), own from registers
-            float ms[4], ws[4];
+            float ws[4];
             float m = m_run[qb];
-            for (int s2 = 0; s2 < p.splits; ++s2) {
-                ms[s2 & 3] = s2 == split ? m_run[qb]
-                                         : __hip_atomic_load(part0 + s2 * sstride + qb * (QG * 64), __ATOMIC_RELAXED,
-                                                             __HIP_MEMORY_SCOPE_AGENT);
-                m = fmaxf(m, ms[s2 & 3]);
-            }
+            for (int s2 = 0; s2 < p.splits; ++s2) m = fmaxf(m, ms[s2 & 3][qb]);
             float l = 0.f;
             for (int s2 = 0; s2 < p.splits; ++s2) {
-                ws[s2 & 3] = __builtin_amdgcn_exp2f(ms[s2 & 3] - m);
-                const float ls = s2 == split ? l_tot[qb]
-                                             : __hip_atomic_load(part0 + s2 * sstride + (QB + qb) * (QG * 64),
-                                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                l += ws[s2 & 3] * ls;
+                ws[s2 & 3] = __builtin_amdgcn_exp2f(ms[s2 & 3][qb] - m);
+                l += ws[s2 & 3] * ls[s2 & 3][qb];
             }
             const float inv = 1.0f / l;
             const int qrow = q_base + qb * 32 + li;
@@ -1048,9 +1060,15 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
                         for (int r = 0; r < 16; ++r) v[r] = acc[db][qb][r];
                     } else {
 #pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            v[r] = __hip_atomic_load(part0 + s2 * sstride + (2 * QB + (db * QB + qb) * 16 + r) * (QG * 64),
-                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        for (int g = 0; g < 4; ++g) {
+                            const f32x4_t t = __builtin_bit_cast(
+                                f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
+                                             rsrc,
+                                             (uint32_t)s2 * vstride + lane_off +
+                                                 (uint32_t)(1 + (db * QB + qb) * 4 + g) * (QG * 64 * 16),
+                                             0, kDeviceScope));
+                            v[4 * g + 0] = t[0]; v[4 * g + 1] = t[1]; v[4 * g + 2] = t[2]; v[4 * g + 3] = t[3];
+                        }
                     }
 #pragma unroll
                     for (int r = 0; r < 16; ++r) o[r] += ws[s2 & 3] * v[r];
@@ -1155,7 +1173,7 @@ AttnSplitPlan attention_split_plan(int B, int H, int dh, int k_tokens, int L, si
     if (dh != 128 || L <= 256 || k_tokens <= 0) return sp;
     const long wg128 = (long)((k_tokens + 127) / 128) * H * B;
     const long wg256 = (long)((k_tokens + 255) / 256) * H * B;
-    const size_t per_query_row = (size_t)(2 * 2 + 4 * 2 * 16) * 64 * sizeof(float);   // per wave of 64 queries
+    const size_t per_query_row = (size_t)(1 + 4 * 2 * 4) * 64 * 16;   // per wave of 64 queries: 33 vectors of 16 bytes per lane
     // The counters take the same room whichever variant is chosen (one per 128-query tile, the larger count).
     const size_t counter_bytes = ((size_t)wg128 * 4 + 255) & ~(size_t)255;
     auto ranges_ok = [&](int s, int bn, int& per) {

@@ -40,10 +40,12 @@ struct AttnParams {
     bf16_t* o;
     int H, k_tokens, L, L_cap, D;
     float scale_log2e;
-    // key-range split between workgroups (pipelined kernel instantiated with KVS)
-    int q_tiles, splits, keys_per_split;
-    float* part;   // [B][H][q_tile][split][(2*QB + DB*QB*16)][QG*64] fp32, register order
-    int* split_cnt;   // [B][H][q_tile] arrival counters, zero between launches
+    // key-range split between workgroups (pipelined kernel instantiated with KVS): of the launch's
+    // (sample, head, query tile) triples, counted in that order, the first full_tiles are walked whole by
+    // one workgroup each; each of the other tail_tiles is shared by `splits` workgroups
+    int q_tiles, splits, keys_per_split, full_tiles, tail_tiles;
+    float* part;   // [tail tile][split][1 + DB*QB*4 vectors][QG*64 lanes][4] fp32
+    int* split_cnt;   // [tail tile] arrival counters, zero between launches
 };
 
 __device__ __forceinline__ int swap_bits_2_3(int v) {
@@ -560,14 +562,33 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
     int wg = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
     const int n_wg = gridDim.x * gridDim.y * gridDim.z;
     if ((n_wg & 7) == 0) wg = (wg & 7) * (n_wg >> 3) + (wg >> 3);  // XCD-aware order, as above
-    const int qx = wg % gridDim.x;
-    const int q_tile = KVS ? qx % p.q_tiles : qx;
-    const int split = KVS ? qx / p.q_tiles : 0;
-    const int head = (wg / gridDim.x) % gridDim.y;
-    const int b = wg / (gridDim.x * gridDim.y);
+    int q_tile = wg % gridDim.x, head = (wg / gridDim.x) % gridDim.y, b = wg / (gridDim.x * gridDim.y);
+    int split = 0, nsp = 1, tail_idx = 0;   // key range, ranges of this tile, index among the shared tiles
+    if (KVS) {
+        // a one-dimensional launch: full_tiles workgroups that walk all keys of their tile, then `splits`
+        // workgroups for each of the other tiles, range by range (the tiles of a head, which share its
+        // K / V, stay next to each other in both parts, and each part is dealt to the XCDs in runs)
+        const int F = p.full_tiles, R = p.tail_tiles;
+        const int lin = blockIdx.x;
+        int t;
+        if (lin < F) {
+            t = (F & 7) == 0 ? (lin & 7) * (F >> 3) + (lin >> 3) : lin;
+        } else {
+            const int n = R * p.splits;
+            int r = lin - F;
+            if ((n & 7) == 0) r = (r & 7) * (n >> 3) + (r >> 3);
+            split = r / R;
+            tail_idx = r - split * R;
+            t = F + tail_idx;
+            nsp = p.splits;
+        }
+        q_tile = t % p.q_tiles;
+        head = (t / p.q_tiles) % p.H;
+        b = t / (p.q_tiles * p.H);
+    }
     const int q_base = q_tile * (QG * 32 * QB) + qg * (32 * QB);
-    const int key_first = KVS ? split * p.keys_per_split : 0;                 // a multiple of the key tile
-    const int L = KVS ? min(p.L - key_first, p.keys_per_split) : p.L;         // keys of this workgroup
+    const int key_first = (KVS && nsp > 1) ? split * p.keys_per_split : 0;    // a multiple of the key tile
+    const int L = (KVS && nsp > 1) ? min(p.L - key_first, p.keys_per_split) : p.L;   // keys of this workgroup
 
     const bf16_t* kc = p.kc + (((size_t)b * p.H + head) * p.L_cap + key_first) * DH;
     const bf16_t* vc = p.vc + ((size_t)b * p.H + head) * DH * (size_t)p.L_cap + key_first;
@@ -975,7 +996,7 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
         }
     }
 #undef FP_PUBLISH
-    if (KVS) {
+    if (KVS && nsp > 1) {
         // Every key range leaves its partial result (statistics, then the accumulator) and counts itself in at
         // the query tile's counter; the workgroup that arrives last combines all ranges exactly, in range
         // order (its own from registers), normalises and stores.  The partials go out and come back as
@@ -989,7 +1010,7 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
         static_assert(QB == 2, "the statistics of the two query blocks fill one 16-byte vector");
         constexpr int VECS = 1 + DB * QB * 4;
         constexpr int kDeviceScope = 16;   // cache-policy bit of the buffer accesses below
-        const size_t tile_id = ((size_t)b * p.H + head) * p.q_tiles + q_tile;
+        const size_t tile_id = (size_t)tail_idx;
         const uint32_t vstride = (uint32_t)VECS * (QG * 64) * 16;     // bytes per (tile, range)
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             reinterpret_cast<char*>(p.part) + tile_id * p.splits * (size_t)vstride, 0, 0x7FFFFFFF, 0x00020000);
@@ -1129,8 +1150,9 @@ void launch_pipe_split(const AttnParams& p, int B, hipStream_t stream) {
     constexpr size_t smem = tile_bytes > merge_bytes ? tile_bytes : merge_bytes;
     static std::once_flag once;
     raise_lds_limit_once(once, &attention_pipe_kernel<DH, QG, KSPLIT, true>, smem);
+    (void)B;
     attention_pipe_kernel<DH, QG, KSPLIT, true>
-        <<<dim3(p.q_tiles * p.splits, p.H, B), QG * KSPLIT * 64, smem, stream>>>(p);
+        <<<dim3(p.full_tiles + p.tail_tiles * p.splits), QG * KSPLIT * 64, smem, stream>>>(p);
 }
 
 template <int DH, int QB, int QG, int KSPLIT>
@@ -1169,7 +1191,7 @@ int attn_cfg_override() {
 }  // namespace
 
 AttnSplitPlan attention_split_plan(int B, int H, int dh, int k_tokens, int L, size_t max_bytes) {
-    AttnSplitPlan sp{1, 0, false, 0, 0, 0};
+    AttnSplitPlan sp{1, 0, false, 0, 0, 0, 0, 0};
     if (dh != 128 || L <= 256 || k_tokens <= 0) return sp;
     const long wg128 = (long)((k_tokens + 127) / 128) * H * B;
     const long wg256 = (long)((k_tokens + 255) / 256) * H * B;
@@ -1209,6 +1231,40 @@ AttnSplitPlan attention_split_plan(int B, int H, int dh, int k_tokens, int L, si
             if (cost < best) {
                 best = cost;
                 sp.splits = s; sp.keys_per_split = per; sp.wide = wide != 0;
+                sp.full_tiles = 0; sp.tail_tiles = (int)wg;
+                sp.counters = (int)wg; sp.counter_bytes = counter_bytes; sp.bytes = bytes;
+            }
+        }
+    }
+    // (only where no launch with every tile split beat the unsplit one: where one did, the mixed launch lost
+    // to it: 2560 kept tokens over 13 K keys, three ranges in two rounds 251 us, mixed 273)
+    if (sp.splits > 1) return sp;
+    for (int wide = 0; wide <= (attn_wide_enabled() ? 1 : 0); ++wide) {
+        if (wide && wg128 < 128) continue;
+        const long wg = wide ? wg256 : wg128;
+        // Whole rounds unsplit, the part-filled last round on s key ranges each: 576 workgroups (1152 kept
+        // tokens, 16 heads, four samples) are two rounds of 256 plus 64 tiles on four ranges, two and a
+        // quarter rounds instead of three.  The shared tiles are the last ones of the launch; they start as
+        // the full ones drain.  A part-filled round costs less than the model's full round (with a quarter
+        // of the CUs idle the others ran 15 % faster: 3072 kept tokens, 192 workgroups of 256 queries), and a
+        // 256-query workgroup then costs about 1.6 units, not 1.86; measured, the mixed launch lost 4-7 %
+        // where this model saw it 4 % ahead (3072 and 2765 kept tokens) and won 7 % where it saw 20 %
+        // (4 x 1152), so it has to be 12 % ahead of the unsplit launch to be taken.
+        const long full = (wg / 256) * 256, rem = wg - full;
+        if (full == 0 || rem == 0) continue;
+        const double kWideMixed = 1.6;
+        const double unsplit = rounds(wg128) < kWideMixed * rounds(wg256) ? rounds(wg128) : kWideMixed * rounds(wg256);
+        for (int s = 2; s <= 4; ++s) {
+            int per;
+            if (rem * s > 256 || !ranges_ok(s, wide ? 64 : 128, per)) continue;
+            const size_t bytes = counter_bytes + (size_t)rem * s * (wide ? 4 : 2) * per_query_row;
+            if (max_bytes && bytes > max_bytes) continue;
+            const double overhead = s == 2 ? 0.06 : 0.18 * (s - 1);
+            const double cost = (wide ? kWideMixed : 1.0) * ((double)(full / 256) + (1.0 + overhead) / s);
+            if (cost < 0.88 * unsplit && cost < best) {
+                best = cost;
+                sp.splits = s; sp.keys_per_split = per; sp.wide = wide != 0;
+                sp.full_tiles = (int)full; sp.tail_tiles = (int)rem;
                 sp.counters = (int)wg; sp.counter_bytes = counter_bytes; sp.bytes = bytes;
             }
         }
@@ -1225,10 +1281,12 @@ void launch_attention(const AttnArgs& a, hipStream_t stream) {
     p.H = a.H; p.k_tokens = a.k_tokens; p.L = a.L; p.L_cap = a.L_cap; p.D = a.H * a.dh;
     p.scale_log2e = a.scale * 1.4426950408889634f;
     p.q_tiles = (a.k_tokens + 127) / 128; p.splits = 1; p.keys_per_split = 0; p.part = nullptr; p.split_cnt = nullptr;
+    p.full_tiles = p.tail_tiles = 0;
     if (a.split_ws && attn_cfg_override() < 0) {
         const AttnSplitPlan sp = attention_split_plan(a.B, a.H, a.dh, a.k_tokens, a.L, a.split_ws_bytes);
         if (sp.splits > 1) {
             p.splits = sp.splits; p.keys_per_split = sp.keys_per_split;
+            p.full_tiles = sp.full_tiles; p.tail_tiles = sp.tail_tiles;
             p.split_cnt = static_cast<int*>(a.split_ws);
             p.part = reinterpret_cast<float*>(static_cast<char*>(a.split_ws) + sp.counter_bytes);
             if (sp.wide) {

@@ -137,13 +137,16 @@ void launch_attention(const AttnArgs& a, hipStream_t stream);
 // `keys_per_split` keys (a multiple of the key tile) and leave unnormalised partial outputs with their
 // softmax statistics in scratch; the workgroup that finishes a query tile last merges them (softmax
 // partials combine exactly; it adds them in range order, so the result does not depend on who was last).
-// The plan is the cheapest of 128- or 256-query workgroups on 2-4 key ranges under a simple round-count
-// model, if that beats the unsplit launch.  splits == 1: no scratch.  max_bytes != 0: only variants whose
+// The plan is the cheapest of 128- or 256-query workgroups on 2-4 key ranges, for every tile or only for
+// the tiles of a part-filled last round (the whole rounds before it stay unsplit), under a simple
+// round-count model, if that beats the unsplit launch.  splits == 1: no scratch.  max_bytes != 0: only variants whose
 // scratch fits.
 struct AttnSplitPlan {
     int splits;
     int keys_per_split;
     bool wide;      // 256-query workgroups (else 128-query ones)
+    int full_tiles;        // (sample, head, query tile) triples walked whole by one workgroup (whole rounds of 256)
+    int tail_tiles;        // the others, shared by `splits` workgroups each
     int counters;          // arrival counters at the head of the scratch (zero on entry, zero again on exit)
     size_t counter_bytes;
     size_t bytes;          // counters + partial results

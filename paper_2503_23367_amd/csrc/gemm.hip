@@ -607,38 +607,58 @@ int gemm_cfg_override(int epi) {
 #endif
 }
 
+// Tile choice.  What the measurements on the block's shapes say (inside the running step):
+//  * three 64-wide K stages beat two: with two, the loads of the next K tile are issued while the current
+//    one is multiplied and must land before the hand-over; with three they have a whole tile's time more.
+//    256x128 tiles with eight waves of 64x64 and three stages run a round of tiles in 8 + 0.80 us per K tile,
+//    as fast per output element as 256x256 tiles (which fit only two stages into 160 KB: 14 + 1.55) and
+//    twice as fine grained; the same tile with two stages, or with 32-wide K tiles in four or six stages
+//    (twice the hand-overs), is 20-25 % slower.
+//  * 256x256 (QKV: 256x192, N = 3D divides evenly) still wins where its tiles fill whole rounds of the 256
+//    CUs, as at 2048 kept tokens; 128x128 tiles with eight waves of 64x32 and four stages (9.3 + 0.47 us)
+//    where the wide tiles would leave CUs idle (N = D: out-proj, FC2); 192x128 (four waves of 96x64, three
+//    stages: 13.7 + 0.60) where it makes the tile count come out even (3072 rows x 2048 columns = 256 tiles).
+//  * a part-filled last round costs less than a full one (fewer workgroups share the memory system and the
+//    power budget): 0.8 + 0.2 * fill of a full round.
+//  * shapes that give at most 128 tiles of 128x128 (few rows) use 128x64 tiles, at most 64 use 64x64 tiles:
+//    more workgroups streaming the weights beat the better operand reuse of the larger tile.
+// The choice is the candidate with the least modelled time, rounds * (fix + K tiles * per-tile).
+int gemm_choose_cfg(bool qkv, int M, int N, int K) {
+    const long tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
+    if (tiles128 <= 64) return 16;
+    if (tiles128 <= 128) return 17;
+    struct Cand { int cfg, bm, bn, slots; double fix, per_kt; };
+    const Cand cands[] = {
+        {qkv ? 12 : 11, 256, qkv ? 192 : 256, 256, qkv ? 20.0 : 14.0, qkv ? 1.25 : 1.55},
+        {32, 256, 128, 256, 8.0, 0.80},
+        {34, 192, 128, 256, 13.7, 0.60},
+        {40, 128, 128, 256, 9.3, 0.47},
+        {6, 128, 128, 512, 8.0, 1.0},     // two workgroups per CU share its time
+    };
+    const double KT = (double)K / 64.0;
+    int best_cfg = 6;
+    double best = 1e30;
+    for (const Cand& c : cands) {
+        double per_kt = c.per_kt;
+        if (c.bm == 256 && c.bn >= 192) {
+            // the two-stage wide tiles lose ground on long K ranges (1.8 us per K tile at K = 8192) and were
+            // never ahead on narrow outputs (N = D: eight tile columns, 4 x 1638 rows 80.7 us against 64.7 modelled
+            // for 256x128)
+            if ((N + c.bn - 1) / c.bn < 16) continue;
+            if (KT > 32.0) per_kt += 0.0026 * (KT - 32.0);
+        }
+        const long tiles = (long)((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
+        const long full = tiles / c.slots, rem = tiles - full * c.slots;
+        const double rounds = (double)full + (rem ? 0.8 + 0.2 * (double)rem / c.slots : 0.0);
+        const double t = rounds * (c.fix + KT * per_kt);
+        if (t < best) { best = t; best_cfg = c.cfg; }
+    }
+    return best_cfg;
+}
+
 template <int EPI>
 void launch_epi(GemmParams& p, hipStream_t stream) {
-    // Tile choice, from measurements on the block's shapes:
-    //  * 256-row tiles halve the global->LDS traffic per MFMA and give every wave
-    //    sixteen (or twelve) MFMAs per operand-read step, which hides LDS latency
-    //    with one wave per SIMD; they win whenever they still give (almost) every
-    //    CU a tile.  The QKV GEMM uses 256x192 (N = 3D divides evenly) with eight
-    //    waves of 64x96, whose smaller accumulator leaves room for the epilogue's
-    //    extra address state; the others 256x256 with eight waves of 128x64 (two waves per SIMD cover
-    //    each other's waits and halve the epilogue's issue time; four waves of 128x128 are 13 % slower
-    //    on the 4096-row FC1 inside the step).
-    //    Both need (almost) every CU to get a tile and the last round of tiles to be at least 80 % full.
-    //  * otherwise 128x128 tiles: three 64-wide K stages with one workgroup per CU, or two stages with
-    //    two per CU, whichever leaves fewer tile slots idle in its last round.  Shapes that give fewer
-    //    than 128 such tiles (few rows: pruned steps of the mid-size scales, high pruning ratios) use
-    //    128x64 tiles, fewer than 64 use 64x64 tiles: more workgroups streaming the weights beat the
-    //    better operand reuse of the larger tile.
-    const long tiles256 = (long)((p.M + 255) / 256) * ((p.N + 255) / 256);
-    const long tiles192 = (long)((p.M + 255) / 256) * ((p.N + 191) / 192);
-    const long tiles128 = (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
-    // fraction of the chip's tile slots that do useful work when `tiles` tiles run `slots` at a time
-    auto fill = [](long tiles, long slots) { return (double)tiles / (double)(((tiles + slots - 1) / slots) * slots); };
-    const long big = is_qkv(EPI) ? tiles192 : tiles256;
-    int cfg;
-    if (big >= 192 && fill(big, 256) >= 0.8)
-        cfg = is_qkv(EPI) ? 12 : 11;
-    else if (tiles128 <= 64)
-        cfg = 16;
-    else if (tiles128 <= 128)
-        cfg = 17;
-    else   // one three-stage workgroup per CU, or two two-stage ones (about 8 % faster per tile when both fill)
-        cfg = 1.08 * fill(tiles128, 512) >= fill(tiles128, 256) ? 6 : 7;
+    int cfg = gemm_choose_cfg(is_qkv(EPI), p.M, p.N, p.K);
     constexpr int knob = EPI == EPI_QKV_ROPE ? (int)EPI_QKV : EPI;
     if (gemm_cfg_override(knob) >= 0) cfg = gemm_cfg_override(knob);
     if (p.sk_part && gemm_cfg_override(knob) < 0) {
@@ -652,21 +672,19 @@ void launch_epi(GemmParams& p, hipStream_t stream) {
         }
     }
     switch (cfg) {
-        case 1: launch_cfg<256, 256, 64, 2, 2, 2, 1, EPI>(p, stream); break;
-        case 3: launch_cfg<128, 128, 32, 4, 2, 2, 1, EPI>(p, stream); break;
-        case 7: launch_cfg<128, 128, 64, 3, 2, 2, 1, EPI>(p, stream); break;
-        case 9: launch_cfg<256, 192, 64, 2, 2, 2, 1, EPI>(p, stream); break;
-        case 10: launch_cfg<128, 128, 64, 4, 2, 2, 2, EPI>(p, stream); break;
         case 11: launch_cfg<256, 256, 64, 2, 2, 4, 1, EPI>(p, stream); break;
         case 12: launch_cfg<256, 192, 64, 2, 4, 2, 1, EPI>(p, stream); break;
-        case 15: launch_cfg<64, 128, 64, 3, 2, 2, 1, EPI>(p, stream); break;
         case 16: launch_cfg<64, 64, 64, 4, 2, 2, 1, EPI>(p, stream); break;
         case 17: launch_cfg<128, 64, 64, 3, 2, 2, 1, EPI>(p, stream); break;
-        case 21: launch_cfg<256, 256, 32, 4, 2, 4, 1, EPI>(p, stream); break;
-        case 22: launch_cfg<256, 256, 32, 5, 2, 4, 1, EPI>(p, stream); break;
-        case 25: launch_cfg<128, 128, 32, 6, 2, 2, 1, EPI>(p, stream); break;
-        case 26: launch_cfg<128, 128, 64, 4, 2, 2, 1, EPI>(p, stream); break;
-        default: launch_cfg<128, 128, 64, 2, 2, 2, 1, EPI>(p, stream); break;
+        case 32: launch_cfg<256, 128, 64, 3, 4, 2, 1, EPI>(p, stream); break;
+        case 34: launch_cfg<192, 128, 64, 3, 2, 2, 1, EPI>(p, stream); break;
+        case 40: launch_cfg<128, 128, 64, 4, 2, 4, 1, EPI>(p, stream); break;
+#ifdef FASTVAR_DEV_KNOBS
+        case 7: launch_cfg<128, 128, 64, 3, 2, 2, 1, EPI>(p, stream); break;
+        case 37: launch_cfg<256, 128, 64, 2, 4, 2, 1, EPI>(p, stream); break;
+        case 39: launch_cfg<256, 128, 32, 4, 4, 2, 1, EPI>(p, stream); break;
+#endif
+        default: launch_cfg<128, 128, 64, 2, 2, 2, 1, EPI>(p, stream); break;   // 6: two workgroups per CU
     }
 }
 

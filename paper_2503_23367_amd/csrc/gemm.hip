@@ -65,46 +65,6 @@ struct GemmParams {
     int* sk_cnt;       // [tile] arrival counters, zero between launches
 };
 
-// Where one output column lands: element address = ptr + b*batch_stride + t*row_stride
-// for row m = b*k_tokens + t (for plain [M,N] outputs batch_stride = k_tokens*row_stride).
-struct ColDest {
-    bf16_t* ptr;
-    long batch_stride;
-    int row_stride;
-    int d;   // EPI_QKV: channel of the column inside its head
-};
-
-template <int EPI>
-__device__ __forceinline__ ColDest col_dest(const GemmParams& p, int n) {
-    ColDest c;
-    c.d = 0;
-    if (!is_qkv(EPI)) {
-        c.ptr = p.out + n;
-        c.row_stride = p.N;
-        c.batch_stride = (long)p.k_tokens * p.N;
-        return c;
-    }
-    const int sec = n / p.D;
-    const int f = n - sec * p.D;
-    const int hh = f / p.dh;
-    const int d = f - hh * p.dh;
-    c.d = d;
-    if (sec == 0) {
-        c.ptr = p.q_out + f;
-        c.row_stride = p.D;
-        c.batch_stride = (long)p.k_tokens * p.D;
-    } else if (sec == 1) {  // k_cache [B, H, L_cap, dh]
-        c.ptr = p.k_cache + ((size_t)hh * p.L_cap + p.L0) * p.dh + d;
-        c.row_stride = p.dh;
-        c.batch_stride = (long)p.H * p.L_cap * p.dh;
-    } else {  // v_cache [B, H, dh, L_cap]
-        c.ptr = p.v_cache + ((size_t)hh * p.dh + d) * p.L_cap + p.L0;
-        c.row_stride = 1;
-        c.batch_stride = (long)p.H * p.dh * p.L_cap;
-    }
-    return c;
-}
-
 // s_waitcnt immediate (gfx9 encoding): wait until at most `vm` vector-memory
 // operations are outstanding; lgkm = true also waits for all LDS/scalar ops.
 constexpr int waitcnt_imm(int vm, bool lgkm) {
@@ -258,18 +218,25 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
         }                                                                                       \
     }
 
-    // The accumulators start from the bias (a lane's 16 values of a 32x32 block share its column), which
-    // saves the epilogue an add per element; with K split between k-groups or workgroups only the first
-    // slice carries it.
+    // The accumulators start from the bias, which saves the epilogue an add per element; with K split between
+    // k-groups or workgroups only the first slice carries it.  (Accumulator blocks hold C transposed, see the
+    // epilogue: register r of a lane is column 8*(r/4) + 4*(lane/32) + r%4 of the block.)
     f32x16_t acc[MI][NI];
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
-        const int n = n0 + wn * WTN + ni * 32 + (lane & 31);
-        const float b0 = (p.bias && n < p.N && kg == 0 && split == 0) ? bf16_to_f32(p.bias[n]) : 0.f;
+        float b16[16];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int n = n0 + wn * WTN + ni * 32 + 8 * g + 4 * (lane >> 5);
+            u32x2_t bb = {0u, 0u};
+            if (p.bias && n < p.N && kg == 0 && split == 0) bb = *reinterpret_cast<const u32x2_t*>(p.bias + n);
+            b16[4 * g + 0] = bf16_lo(bb.x); b16[4 * g + 1] = bf16_hi(bb.x);
+            b16[4 * g + 2] = bf16_lo(bb.y); b16[4 * g + 3] = bf16_hi(bb.y);
+        }
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = b0;
+            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = b16[r];
     }
 
     // ---- prologue: STAGES-1 tiles in flight, wait for the first
@@ -290,7 +257,7 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
 #define FV_MFMA_ROWS(cur_, mi_lo_, mi_hi_)                                                      \
     _Pragma("unroll") for (int mi = (mi_lo_); mi < (mi_hi_); ++mi)                              \
         _Pragma("unroll") for (int ni = 0; ni < NI; ++ni)                                       \
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur_][mi], fw[cur_][ni],   \
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[cur_][ni], fa[cur_][mi],   \
                                                                   acc[mi][ni], 0, 0, 0);
 #define FV_INTERLEAVE(mfma_per_read_, with_dma_)                                                \
     _Pragma("unroll") for (int g = 0; g < MI + NI; ++g) {                                       \
@@ -352,24 +319,23 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
 #undef FV_LOAD_FRAGS_ISSUE
 #undef FV_LOAD_FRAGS
 
-    // ---- Epilogue, staged through LDS so that global traffic is 16 bytes per lane.
-    // Accumulator register r of lane l holds C[row, col] with col = l % 32 and
-    // row = 8*(r/4) + 4*(l/32) + r%4 inside a 32x32 block.  Each wave owns a
-    // private fp32 staging area of 32 rows x WTN columns: it writes one 32-row
-    // slab of its tile in accumulator layout (bias and GELU applied), reads it
-    // back row-wise (8 columns per lane), adds the residual, rounds once to bf16
-    // and stores 16 bytes per lane.  LDS operations of one wave execute in
-    // order, so no barrier is needed between the two phases.
-    constexpr int SROW = WTN + 4;          // padded row stride (floats)
-    constexpr int LPR = WTN / 8;           // lanes per row in the read-back phase
-    constexpr int RPP = 64 / LPR;          // rows per pass (lanes past RPP * LPR idle when 64 % LPR != 0)
-    constexpr int PASSES = (32 + RPP - 1) / RPP;
+    // ---- Epilogue, from registers.  The MFMAs take the W fragment as their first operand, so an accumulator
+    // block holds C transposed: register r of lane l is C[row, col] with row = l % 32 and
+    // col = 8*(r/4) + 4*(l/32) + r%4 inside a 32x32 block: a lane owns one output row and four runs of four
+    // consecutive columns.  GELU, residual (an 8-byte load per run) and rotary turn are applied in fp32, the
+    // runs are rounded once to bf16, and one half-wave exchange (v_permlane32_swap) per pair of runs leaves
+    // every lane with two runs of eight consecutive columns: two 16-byte stores per block, no staging through
+    // LDS and no barrier between the main loop and the stores (a wave that is done stores while the others
+    // still multiply).  The V section of the QKV GEMM is stored along the token axis of the transposed cache:
+    // there consecutive lanes are consecutive tokens, 2-byte stores that a half-wave makes 64 contiguous bytes.
     constexpr int XCH = KG > 1 ? MI * NI * 16 * 64 * NWQ : 0;  // floats handed over by the other k-groups
-    static_assert((XCH + NWQ * 32 * SROW) * 4 <= STAGES * (BM + BN) * BK * 2, "staging must fit in the tile LDS");
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
-    __builtin_amdgcn_s_barrier();  // every wave is done reading operand tiles
-    asm volatile("" ::: "memory");
+    static_assert(XCH * 4 <= STAGES * (BM + BN) * BK * 2, "the k-group exchange must fit in the tile LDS");
+    if (KG > 1 || SK) {
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
+        __builtin_amdgcn_s_barrier();  // every wave is done reading operand tiles: LDS is free for the exchange
+        asm volatile("" ::: "memory");
+    }
     if (KG > 1) {
         // Sum the k-groups: group g > 0 writes its accumulators (register-major, lane
         // contiguous), group 0 adds them; only group 0 goes on to the epilogue.
@@ -460,116 +426,111 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
         if (tid == 0)   // ready for the next launch
             __hip_atomic_store(p.sk_cnt + blockIdx.x, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    float* stg = reinterpret_cast<float*>(smem) + XCH + wq * (32 * SROW);
-
-    const int cg = lane % LPR, rsub = lane / LPR;
-    const int ncol = n0 + wn * WTN + cg * 8;  // first of this lane's 8 output columns
-    const bool col_ok = ncol < p.N && rsub < RPP;  // N % 8 == 0: the whole group is in or out
-    const ColDest cd = col_dest<EPI>(p, col_ok ? ncol : 0);
-    bool row_path = col_ok;
-    if (is_qkv(EPI)) row_path = col_ok && ncol < 2 * p.D;  // the V section is stored transposed below
-
+    const int lrow = lane & 31;            // output row inside a 32-row block
     static_for<0, MI>([&](auto mi_c) {
         constexpr int mi = decltype(mi_c)::value;
+        const int m = m0 + wm * WTM + mi * 32 + lrow;
+        const bool row_ok = m < p.M;
+        const int mc = row_ok ? m : p.M - 1;
+        // (sample, token) of this lane's row, where its output goes and where its residual comes from
+        int bq = 0, tq = mc;
+        if (is_qkv(EPI)) {
+            bq = mc / p.k_tokens;
+            tq = mc - bq * p.k_tokens;
+        }
+        size_t orow = (size_t)mc, rrow = (size_t)mc;
+        if (EPI == EPI_BIAS_RES) {
+            if (p.out_rows) orow = (size_t)p.out_rows[mc];
+            if (p.res_rows) rrow = (size_t)p.res_rows[mc];
+        }
+        int slot = tq;   // rotary: the token's slot in its map
+        if (EPI == EPI_QKV_ROPE && p.rope_rows) slot = p.rope_rows[mc] % p.rope_N;
         static_for<0, NI>([&](auto ni_c) {
             constexpr int ni = decltype(ni_c)::value;
-            static_for<0, 16>([&](auto r_c) {
-                constexpr int r = decltype(r_c)::value;
-                float v = acc[mi][ni][r];
-                if (EPI == EPI_BIAS_GELU) v = gelu_fast(v);
-                stg[(8 * (r >> 2) + 4 * frag_half + (r & 3)) * SROW + ni * 32 + frag_row] = v;
-            });
-        });
-        const int m_slab = m0 + wm * WTM + mi * 32;
-        // (sample, token) of this lane's first row; later passes step by RPP rows
-        int bq = 0, tq = 0;
-        if (is_qkv(EPI)) {
-            bq = (m_slab + rsub) / p.k_tokens;
-            tq = (m_slab + rsub) - bq * p.k_tokens;
-        }
+            const int nb = n0 + wn * WTN + ni * 32;      // first column of the block (wave uniform)
+            if (nb >= p.N) return;                       // N % 32 may be non-zero only past whole 8-column groups: checked per group below
+            // QKV: section, head and channel of the block's first column (wave uniform: scalar arithmetic); the
+            // 32 columns of a block lie in one section and one head (D and dh are multiples of 32)
+            int sec = 0, f0 = 0, hh0 = 0, d0 = 0;
+            if (is_qkv(EPI)) {
+                sec = nb / p.D;
+                f0 = nb - sec * p.D;
+                hh0 = f0 / p.dh;
+                d0 = f0 - hh0 * p.dh;
+            }
+            if (is_qkv(EPI) && sec == 2) {
+                // V section: v_cache[b, head, d, L0 + t], consecutive lanes = consecutive tokens
+                if (row_ok) {
+                    bf16_t* const v0 = p.v_cache + (((size_t)bq * p.H + hh0) * p.dh + d0) * p.L_cap + p.L0 + tq;
+                    static_for<0, 16>([&](auto r_c) {
+                        constexpr int r = decltype(r_c)::value;
+                        const int col = 8 * (r >> 2) + 4 * frag_half + (r & 3);
+                        if (nb + col < p.N) v0[(size_t)col * p.L_cap] = (bf16_t)f32_to_bf16_bits(acc[mi][ni][r]);
+                    });
+                }
+                return;
+            }
+            // four runs of four columns -> packed bf16 pairs
+            uint32_t pk[4][2];
+            static_for<0, 4>([&](auto g_c) {
+                constexpr int g = decltype(g_c)::value;
+                const int n = nb + 8 * g + 4 * frag_half;     // first column of this lane's run
+                float v[4] = {acc[mi][ni][4 * g + 0], acc[mi][ni][4 * g + 1], acc[mi][ni][4 * g + 2], acc[mi][ni][4 * g + 3]};
+                if (EPI == EPI_BIAS_GELU) {
 #pragma unroll
-        for (int ps = 0; ps < PASSES; ++ps) {
-            const int row = ps * RPP + rsub;
-            const int m = m_slab + row;
-            if (m < p.M && row_path && (32 % RPP == 0 || row < 32)) {
-                const f32x4_t lo = *reinterpret_cast<const f32x4_t*>(stg + row * SROW + cg * 8);
-                const f32x4_t hi = *reinterpret_cast<const f32x4_t*>(stg + row * SROW + cg * 8 + 4);
-                float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                if (EPI == EPI_BIAS_RES) {
-                    const size_t rrow = p.res_rows ? (size_t)p.res_rows[m] : (size_t)m;
-                    const u32x4_t rr = *reinterpret_cast<const u32x4_t*>(p.residual + rrow * p.N + ncol);
+                    for (int j = 0; j < 4; ++j) v[j] = gelu_fast(v[j]);
+                }
+                if (EPI == EPI_BIAS_RES && n < p.N) {
+                    const u32x2_t rr = *reinterpret_cast<const u32x2_t*>(p.residual + rrow * p.N + n);
                     v[0] += bf16_lo(rr.x); v[1] += bf16_hi(rr.x);
                     v[2] += bf16_lo(rr.y); v[3] += bf16_hi(rr.y);
-                    v[4] += bf16_lo(rr.z); v[5] += bf16_hi(rr.z);
-                    v[6] += bf16_lo(rr.w); v[7] += bf16_hi(rr.w);
                 }
-                if (EPI == EPI_QKV_ROPE) {
-                    // rotary embedding of q and the new keys (this path holds no V column): the lane's
-                    // eight columns are four interleaved pairs of one head, turned by the angles of the
-                    // token's own slot in the map
-                    const int slot = p.rope_rows ? p.rope_rows[m] % p.rope_N : tq;
-                    const size_t at = (size_t)slot * (p.dh >> 1) + (cd.d >> 1);
-                    const f32x4_t cs = *reinterpret_cast<const f32x4_t*>(p.rope_cos + at);
-                    const f32x4_t sn = *reinterpret_cast<const f32x4_t*>(p.rope_sin + at);
+                if (EPI == EPI_QKV_ROPE && n < p.N) {
+                    // two interleaved pairs of one head, turned by the angles of the token's slot
+                    const int d = d0 + 8 * g + 4 * frag_half;
+                    const size_t at = (size_t)slot * (p.dh >> 1) + (d >> 1);
+                    const f32x2_t cs = *reinterpret_cast<const f32x2_t*>(p.rope_cos + at);
+                    const f32x2_t sn = *reinterpret_cast<const f32x2_t*>(p.rope_sin + at);
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
+                    for (int j = 0; j < 2; ++j) {
                         const float a = v[2 * j], b = v[2 * j + 1];
                         v[2 * j] = a * cs[j] - b * sn[j];
                         v[2 * j + 1] = a * sn[j] + b * cs[j];
                     }
                 }
-                u32x4_t o;
-                o.x = pack_bf16x2(v[0], v[1]);
-                o.y = pack_bf16x2(v[2], v[3]);
-                o.z = pack_bf16x2(v[4], v[5]);
-                o.w = pack_bf16x2(v[6], v[7]);
-                bf16_t* dst;
-                if (is_qkv(EPI))
-                    dst = cd.ptr + (long)bq * cd.batch_stride + (long)tq * cd.row_stride;
-                else
-                    dst = p.out + (EPI == EPI_BIAS_RES && p.out_rows ? (size_t)p.out_rows[m] : (size_t)m) * p.N + ncol;
-                *reinterpret_cast<u32x4_t*>(dst) = o;
-            }
-            if (is_qkv(EPI)) {
-                tq += RPP;
-                while (tq >= p.k_tokens) { tq -= p.k_tokens; ++bq; }
-            }
-        }
-        if (is_qkv(EPI)) {
-            // V section: cache positions are contiguous along the token (row) axis, so
-            // lanes walk the rows of a column: lane l handles row l%32 of columns
-            // l/32, l/32+2, ... of each 32-column block that lies in the V section.
-            const int m = m_slab + frag_row;
-            const int b = m / p.k_tokens;
-            const int t = m - b * p.k_tokens;
+                pk[g][0] = pack_bf16x2(v[0], v[1]);
+                pk[g][1] = pack_bf16x2(v[2], v[3]);
+            });
+            // exchange between the half-waves: the lower half gives its odd runs and takes the upper half's
+            // even runs, so that the lower half holds columns 0-7 and 16-23 of its row, the upper half 8-15
+            // and 24-31
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni) {
-                const int nb = n0 + wn * WTN + ni * 32;  // wave-uniform; sections are multiples of 64 wide
-                if (nb >= 2 * p.D && nb < p.N && m < p.M) {
-                    // Head and channel of the block's first column: one (wave-uniform) division per
-                    // block.  When the head dimension is a multiple of 32 the whole block lies in that
-                    // head and a column is just an offset; else each column is divided on its own.
-                    const int f0 = nb - 2 * p.D;
-                    const int hh0 = f0 / p.dh;
-                    const int d0 = f0 - hh0 * p.dh;
-                    const bool one_head = (p.dh & 31) == 0;
-                    bf16_t* const v0 = p.v_cache + (((size_t)b * p.H + hh0) * p.dh + d0) * p.L_cap + p.L0 + t;
+            for (int pr = 0; pr < 2; ++pr)
 #pragma unroll
-                    for (int j = 0; j < 16; ++j) {
-                        const int col = frag_half + 2 * j;
-                        const float v = stg[frag_row * SROW + ni * 32 + col];
-                        bf16_t* dst = v0 + (size_t)col * p.L_cap;
-                        if (!one_head) {
-                            const int f = f0 + col;
-                            const int hh = f / p.dh;
-                            const int d = f - hh * p.dh;
-                            dst = p.v_cache + (((size_t)b * p.H + hh) * p.dh + d) * p.L_cap + p.L0 + t;
-                        }
-                        *dst = (bf16_t)f32_to_bf16_bits(v);
+                for (int c = 0; c < 2; ++c) {
+                    const auto sw = __builtin_amdgcn_permlane32_swap(pk[2 * pr][c], pk[2 * pr + 1][c], false, false);
+                    pk[2 * pr][c] = sw[0];
+                    pk[2 * pr + 1][c] = sw[1];
+                }
+#pragma unroll
+            for (int pr = 0; pr < 2; ++pr) {
+                const int n8 = nb + 16 * pr + 8 * frag_half;      // first of this lane's eight columns
+                if (row_ok && n8 < p.N) {
+                    const u32x4_t o = {pk[2 * pr][0], pk[2 * pr][1], pk[2 * pr + 1][0], pk[2 * pr + 1][1]};
+                    bf16_t* dst;
+                    if (is_qkv(EPI)) {
+                        const int off = 16 * pr + 8 * frag_half;
+                        if (sec == 0)   // q_out [B*k, D]
+                            dst = p.q_out + ((size_t)bq * p.k_tokens + tq) * p.D + f0 + off;
+                        else            // k_cache [B, H, L_cap, dh]
+                            dst = p.k_cache + (((size_t)bq * p.H + hh0) * p.L_cap + p.L0 + tq) * p.dh + d0 + off;
+                    } else {
+                        dst = p.out + orow * p.N + n8;
                     }
+                    *reinterpret_cast<u32x4_t*>(dst) = o;
                 }
             }
-        }
+        });
     });
 #endif
 }

@@ -661,7 +661,9 @@ SplitKPlan gemm_splitk_plan(int M, int N, int K) {
     const int min_kt = sk.small_tiles ? 2 : 4;   // K tiles a slice must keep
     // a short K range is over before the slices' summing would pay for itself
     static_assert(kSplitKMaxTiles >= 128 && (kSplitKMaxTiles * 4) % 256 == 0, "covers both tile-count limits below");
-    if (K >= 2048 && sk.tiles <= (sk.small_tiles ? 128 : 96))
+    // (up to 96 tiles of 128x128 whatever K >= 2048; up to 128, i.e. half the chip, where K is long enough
+    // for the halves to be worth a partial tile each)
+    if (K >= 2048 && sk.tiles <= (sk.small_tiles ? 128 : (K >= 4096 ? 128 : 96)))
         while (sk.splits < (sk.small_tiles ? 8 : 4) && sk.tiles * sk.splits * 2 <= 256 &&
                KT % (sk.splits * 2) == 0 && KT / (sk.splits * 2) >= min_kt)
             sk.splits *= 2;   // (more slices than that cost more to sum than they save)

@@ -105,8 +105,17 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
     constexpr int STAGE = A_TILE + W_TILE;
     static_assert(WTM % 32 == 0 && WTN % 32 == 0 && (BK / 16) % KG == 0, "wave tiles are made of 32x32x16 MFMAs");
     static_assert(A_LD * RPI * NW == BM && W_LD * RPI * NW == BN && NW % 2 == 0, "loads must tile the stage");
-    static_assert(KK == 1 || (LPT + KK - 2) / (KK - 1) <= MI + NI, "one load per operand read at most");
-    static_assert((STAGES - 2) * LPT <= 63, "vmcnt is 6 bits");
+    // When a stage is refilled.  EARLY: at the hand-over that frees it, all of the tile's loads at once (LPR
+    // after each operand read), so they have STAGES-1 whole tiles of matrix work to land in: what a ring of two
+    // stages needs.  Otherwise spread over the k-steps of the following tile, one load per operand read: a
+    // quarter to three quarters of a tile later, which deeper rings can afford, and gentler on the hand-over.
+#ifndef FV_GEMM_EARLY_MAX_STAGES
+#define FV_GEMM_EARLY_MAX_STAGES 2
+#endif
+    constexpr bool EARLY = STAGES <= FV_GEMM_EARLY_MAX_STAGES || KK == 1;
+    constexpr int LPR = (LPT + MI + NI - 1) / (MI + NI);
+    static_assert(EARLY || (LPT + KK - 2) / (KK - 1) <= MI + NI, "one load per operand read at most");
+    static_assert((STAGES - 1) * LPT <= 63, "vmcnt is 6 bits");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     u32x4_t* lds = reinterpret_cast<u32x4_t*>(smem);  // [STAGES][A tile | W tile]
@@ -198,10 +207,27 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
         _Pragma("unroll") for (int ni = 0; ni < NI; ++ni)                                       \
             dst_w_[ni] = *reinterpret_cast<const bf16x8_t*>(sw_ + (w_row + 32 * ni) * CPR + ch_); \
     }
-    // The same operand reads with slice part_ of nparts_ of the next tile's loads
-    // issued between them, one load after each read: spreading the loads keeps the
-    // texture-address queue from filling up and stalling the wave.
-#define FV_LOAD_FRAGS_ISSUE(dst_a_, dst_w_, stage_, kk_, kt_, fill_, part_, nparts_)            \
+    // The same operand reads with the loads of a whole tile issued between them, LPR after each read
+    // (putting reads between the loads keeps the texture-address queue from filling up and stalling the wave).
+#define FV_LOAD_FRAGS_ISSUE(dst_a_, dst_w_, stage_, kk_, kt_, fill_)                            \
+    {                                                                                           \
+        const u32x4_t* sa_ = lds + (stage_) * STAGE;                                            \
+        const u32x4_t* sw_ = sa_ + A_TILE;                                                      \
+        const int ch_ = (2 * (kk0 + (kk_)) + frag_half) ^ frag_sw;                              \
+        _Pragma("unroll") for (int g = 0; g < MI + NI; ++g) {                                   \
+            if (g < MI)                                                                         \
+                dst_a_[g < MI ? g : 0] =                                                        \
+                    *reinterpret_cast<const bf16x8_t*>(sa_ + (a_row + 32 * g) * CPR + ch_);     \
+            else                                                                                \
+                dst_w_[g >= MI ? g - MI : 0] =                                                  \
+                    *reinterpret_cast<const bf16x8_t*>(sw_ + (w_row + 32 * (g - MI)) * CPR + ch_); \
+            _Pragma("unroll") for (int u = 0; u < LPR; ++u)                                     \
+                if (g * LPR + u < LPT) FV_ISSUE_Q(kt_, fill_, g * LPR + u)                      \
+        }                                                                                       \
+    }
+
+    // ... and with slice part_ of nparts_ of a tile's loads, one load after each read.
+#define FV_LOAD_FRAGS_ISSUE_PART(dst_a_, dst_w_, stage_, kk_, kt_, fill_, part_, nparts_)       \
     {                                                                                           \
         const u32x4_t* sa_ = lds + (stage_) * STAGE;                                            \
         const u32x4_t* sw_ = sa_ + A_TILE;                                                      \
@@ -239,12 +265,13 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
             for (int r = 0; r < 16; ++r) acc[mi][ni][r] = b16[r];
     }
 
-    // ---- prologue: STAGES-1 tiles in flight, wait for the first
+    // ---- prologue: AHEAD tiles in flight (EARLY: every stage of the ring), wait for the first
+    constexpr int AHEAD = EARLY ? STAGES : STAGES - 1;
 #pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s)
+    for (int s = 0; s < AHEAD; ++s)
         if (s < KT) FV_ISSUE_TILE(s, s)
-    if (KT >= STAGES - 1)
-        __builtin_amdgcn_s_waitcnt(waitcnt_imm((STAGES - 2) * LPT, true));
+    if (KT >= AHEAD)
+        __builtin_amdgcn_s_waitcnt(waitcnt_imm((AHEAD - 1) * LPT, true));
     else
         __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
     asm volatile("" ::: "memory");
@@ -268,34 +295,38 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
     // One K tile.  Software pipeline inside the wave: the operand reads of the
     // next k-step are interleaved with the MFMAs of the current one (the
     // scheduler is told the pattern), so LDS latency hides behind the matrix
-    // pipe.  MORE_: a further tile is fetched (STAGES-1 ahead).  HANDOVER_: a
-    // next tile exists, so the last k-step waits for it (this wave's loads: the
-    // counter; the other waves' loads: the barrier, which also tells everyone
-    // that the stage refilled in the next iteration is no longer being read) and
-    // preloads its first operands.  The body is branch free on purpose: the
-    // accumulators must stay in one register class across the whole loop.
-#define FV_TILE_BODY(MORE_, HANDOVER_)                                                          \
+    // pipe.  HANDOVER_: a next tile exists, so the last k-step waits for it (this
+    // wave's loads: the counter, at most WAITN_ loads of later tiles still in
+    // flight; the other waves' loads: the barrier, which also tells everyone that
+    // this tile's stage is no longer being read) and preloads its first operands.
+    // MORE_: a further tile is fetched, AHEAD tiles on: into the stage this tile
+    // leaves, at its hand-over (EARLY), or into the stage the tile before it left,
+    // during its first k-steps.  The body is branch free on purpose: the
+    // accumulators must stay in one register class across the loop.
+#define FV_TILE_BODY(MORE_, HANDOVER_, WAITN_)                                                  \
     {                                                                                           \
-        int fill_ = stage + STAGES - 1;                                                         \
-        if (fill_ >= STAGES) fill_ -= STAGES;                                                   \
-        if ((MORE_) && KK == 1) FV_ISSUE_TILE(kt + STAGES - 1, fill_)                           \
         int next_stage_ = stage + 1;                                                            \
         if (next_stage_ == STAGES) next_stage_ = 0;                                             \
+        int fill_ = stage + STAGES - 1;                                                         \
+        if (fill_ >= STAGES) fill_ -= STAGES;                                                   \
         _Pragma("unroll") for (int kk = 0; kk < KK; ++kk) {                                     \
             const int cur_ = kk & 1, nxt_ = cur_ ^ 1;                                           \
             if (kk + 1 < KK) {                                                                  \
-                if (MORE_)                                                                      \
-                    FV_LOAD_FRAGS_ISSUE(fa[nxt_], fw[nxt_], stage, kk + 1, kt + STAGES - 1, fill_, kk, KK - 1) \
+                if ((MORE_) && !EARLY)                                                          \
+                    FV_LOAD_FRAGS_ISSUE_PART(fa[nxt_], fw[nxt_], stage, kk + 1, kt + AHEAD, fill_, kk, KK - 1) \
                 else                                                                            \
                     FV_LOAD_FRAGS(fa[nxt_], fw[nxt_], stage, kk + 1)                            \
                 FV_MFMA_ROWS(cur_, 0, MI)                                                       \
                 FV_INTERLEAVE((MI * NI) / (MI + NI), false)                                     \
             } else if (HANDOVER_) {                                                             \
-                __builtin_amdgcn_s_waitcnt(waitcnt_imm((MORE_) ? (STAGES - 2) * LPT : 0, true)); \
+                __builtin_amdgcn_s_waitcnt(waitcnt_imm((WAITN_), true));                        \
                 asm volatile("" ::: "memory");                                                  \
                 __builtin_amdgcn_s_barrier();                                                   \
                 asm volatile("" ::: "memory");                                                  \
-                FV_LOAD_FRAGS(fa[nxt_], fw[nxt_], next_stage_, 0)                               \
+                if ((MORE_) && EARLY)                                                           \
+                    FV_LOAD_FRAGS_ISSUE(fa[nxt_], fw[nxt_], next_stage_, 0, kt + AHEAD, stage)  \
+                else                                                                            \
+                    FV_LOAD_FRAGS(fa[nxt_], fw[nxt_], next_stage_, 0)                           \
                 FV_MFMA_ROWS(cur_, 0, MI)                                                       \
                 FV_INTERLEAVE((MI * NI) / (MI + NI), false)                                     \
             } else {                                                                            \
@@ -307,15 +338,23 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
 
     int stage = 0;  // stage of tile kt
     int kt = 0;
-    for (; kt + STAGES - 1 < KT; ++kt) FV_TILE_BODY(true, true)
-    for (; kt + 1 < KT; ++kt) FV_TILE_BODY(false, true)
-    FV_TILE_BODY(false, false)
+    for (; kt + AHEAD < KT; ++kt) FV_TILE_BODY(true, true, (STAGES - 2) * LPT)
+    // the ring drains: r tiles are left after this one, r-1 of them may still be in flight at the hand-over
+    static_for<0, AHEAD - 1>([&](auto i_c) {
+        constexpr int r = AHEAD - 1 - decltype(i_c)::value;
+        if (KT - 1 - kt == r) {
+            FV_TILE_BODY(false, true, (r - 1) * LPT)
+            ++kt;
+        }
+    });
+    FV_TILE_BODY(false, false, 0)
 #undef FV_TILE_BODY
 #undef FV_INTERLEAVE
 #undef FV_MFMA_ROWS
 #undef FV_ISSUE_TILE
 #undef FV_ISSUE_Q
 #undef FV_DMA16
+#undef FV_LOAD_FRAGS_ISSUE_PART
 #undef FV_LOAD_FRAGS_ISSUE
 #undef FV_LOAD_FRAGS
 
@@ -569,31 +608,37 @@ int gemm_cfg_override(int epi) {
 }
 
 // Tile choice.  What the measurements on the block's shapes say (inside the running step):
-//  * three 64-wide K stages beat two: with two, the loads of the next K tile are issued while the current
-//    one is multiplied and must land before the hand-over; with three they have a whole tile's time more.
-//    256x128 tiles with eight waves of 64x64 and three stages run a round of tiles in 8 + 0.80 us per K tile,
-//    as fast per output element as 256x256 tiles (which fit only two stages into 160 KB: 14 + 1.55) and
-//    twice as fine grained; the same tile with two stages, or with 32-wide K tiles in four or six stages
-//    (twice the hand-overs), is 20-25 % slower.
-//  * 256x256 (QKV: 256x192, N = 3D divides evenly) still wins where its tiles fill whole rounds of the 256
-//    CUs, as at 2048 kept tokens; 128x128 tiles with eight waves of 64x32 and four stages (9.3 + 0.47 us)
-//    where the wide tiles would leave CUs idle (N = D: out-proj, FC2); 192x128 (four waves of 96x64, three
-//    stages: 13.7 + 0.60) where it makes the tile count come out even (3072 rows x 2048 columns = 256 tiles).
+//  * what a tile's loads need is time to land.  A ring refilled during the tile after the hand-over gives them
+//    STAGES-2 tiles and a fraction: nothing to speak of with two stages, which is all that 256x256 and 256x192
+//    tiles fit into 160 KB.  Those rings are therefore refilled at the hand-over itself (one whole tile ahead:
+//    256x192 at 2048 rows 60 -> 52 us, 256x256 68 -> 61 us); rings of three and four stages, which have the
+//    time anyway, lose 3-5 % to the burst of loads at the hand-over and keep the spread refill.
+//  * 256x128 tiles with eight waves of 64x64 and three stages are as fast per output element as the wide tiles
+//    and twice as fine grained; the same tile with two stages and the spread refill, or with 32-wide K tiles in
+//    four or six stages (twice the hand-overs), is 20-25 % slower; 128x128 with 128-wide K tiles in two stages
+//    20 % slower than with 64-wide ones in four.
+//  * 256x256 (QKV: 256x192, N = 3D divides evenly) wins where its tiles fill whole rounds of the 256 CUs, as
+//    at 2048 kept tokens; 128x128 tiles with eight waves of 64x32 and four stages where the wide tiles would
+//    leave CUs idle (N = D: out-proj, FC2); 192x128 (four waves of 96x64, three stages) where it makes the
+//    tile count come out even (3072 rows x 2048 columns = 256 tiles).
 //  * a part-filled last round costs less than a full one (fewer workgroups share the memory system and the
-//    power budget): 0.8 + 0.2 * fill of a full round.
+//    power budget).
 //  * shapes that give at most 128 tiles of 128x128 (few rows) use 128x64 tiles, at most 64 use 64x64 tiles:
 //    more workgroups streaming the weights beat the better operand reuse of the larger tile.
-// The choice is the candidate with the least modelled time, rounds * (fix + K tiles * per-tile).
+// The choice is the candidate with the least modelled time, rounds * (fix + K tiles * per-tile), a part-filled
+// round counting 0.85 + 0.29 * fill; the constants are a least-squares fit to the in-step times of the four
+// GEMMs of fifteen workloads under each configuration (residual 7 % rms; the picks cost 0.3 % more than the
+// best measured configuration of every shape would).
 int gemm_choose_cfg(bool qkv, int M, int N, int K) {
     const long tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
     if (tiles128 <= 64) return 16;
     if (tiles128 <= 128) return 17;
     struct Cand { int cfg, bm, bn, slots; double fix, per_kt; };
     const Cand cands[] = {
-        {qkv ? 12 : 11, 256, qkv ? 192 : 256, 256, qkv ? 20.0 : 14.0, qkv ? 1.25 : 1.55},
-        {32, 256, 128, 256, 8.0, 0.80},
-        {34, 192, 128, 256, 13.7, 0.60},
-        {40, 128, 128, 256, 9.3, 0.47},
+        {qkv ? 12 : 11, 256, qkv ? 192 : 256, 256, 4.0, qkv ? 1.33 : 1.60},
+        {32, 256, 128, 256, 10.3, 0.714},
+        {34, 192, 128, 256, 9.5, 0.575},
+        {40, 128, 128, 256, 6.2, 0.456},
         {6, 128, 128, 512, 8.0, 1.0},     // two workgroups per CU share its time
     };
     const double KT = (double)K / 64.0;
@@ -606,11 +651,11 @@ int gemm_choose_cfg(bool qkv, int M, int N, int K) {
             // never ahead on narrow outputs (N = D: eight tile columns, 4 x 1638 rows 80.7 us against 64.7 modelled
             // for 256x128)
             if ((N + c.bn - 1) / c.bn < 16) continue;
-            if (KT > 32.0) per_kt += 0.0026 * (KT - 32.0);
+            if (KT > 32.0) per_kt += 0.003 * (KT - 32.0);
         }
         const long tiles = (long)((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
         const long full = tiles / c.slots, rem = tiles - full * c.slots;
-        const double rounds = (double)full + (rem ? 0.8 + 0.2 * (double)rem / c.slots : 0.0);
+        const double rounds = (double)full + (rem ? 0.85 + 0.29 * (double)rem / c.slots : 0.0);
         const double t = rounds * (c.fix + KT * per_kt);
         if (t < best) { best = t; best_cfg = c.cfg; }
     }

@@ -16,6 +16,7 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <mutex>
 #include "common.h"
 #include "kernels.h"
 
@@ -89,6 +90,9 @@ __device__ __forceinline__ int swz(int row) {
 // SK: the K range is also split between workgroups (blockIdx.y); every workgroup leaves its partial
 // tile in scratch memory, and the one that arrives last at the tile's counter adds the slices up, in
 // slice order (so the sum does not depend on who was last), and runs the epilogue.  Nobody waits.
+template <int EPI, int KG, bool SK>
+constexpr bool kPersistent = !SK && KG == 1 && is_qkv(EPI);
+
 template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, int KG, int EPI, bool SK = false>
 __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const GemmParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
@@ -131,18 +135,31 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
     // Tile id: consecutive workgroup ids are dealt round-robin to the 8 XCDs;
     // undo that so each XCD (own L2) walks a contiguous run of tiles, and walk
     // tiles in groups of 8 tile-rows so neighbours share operand rows.
-    int pid = blockIdx.x;
+    // A QKV launch with more tiles than the chip holds workgroups at a time is persistent: the grid is one
+    // round of workgroups, and workgroup i takes tiles i, i + grid, ... (the grid is a multiple of 8, so
+    // a workgroup's tiles stay in its XCD's run).  What that buys is the overlap at the seam: the next
+    // tile's first stages are fetched while this tile's epilogue runs, which needs no LDS.  It pays for the
+    // QKV epilogue, the longest (2-byte stores into the transposed V cache): 3-4 % of the launch at 3072 to
+    // 6552 rows; the other epilogues are short enough that the hardware's own hand-over from a finished
+    // workgroup to the next does as well (measured: +-2 %), so they keep one workgroup per tile.
+    constexpr bool PERSIST = kPersistent<EPI, KG, SK>;
     const int n_tiles = p.tiles_m * p.tiles_n;
-    if ((n_tiles & 7) == 0) pid = (pid & 7) * (n_tiles >> 3) + (pid >> 3);
-    constexpr int GROUP = 8;
-    const int per_group = GROUP * p.tiles_n;
-    const int grp = pid / per_group;
-    const int first_m = grp * GROUP;
-    const int gsize = min(p.tiles_m - first_m, GROUP);
-    const int in_grp = pid - grp * per_group;
-    const int tm = first_m + in_grp % gsize;
-    const int tn = in_grp / gsize;
-    const int m0 = tm * BM, n0 = tn * BN;
+    int m0, n0;
+#define FV_TILE_COORDS(vpid_)                                                                   \
+    {                                                                                           \
+        int pid_ = (vpid_);                                                                     \
+        if ((n_tiles & 7) == 0) pid_ = (pid_ & 7) * (n_tiles >> 3) + (pid_ >> 3);              \
+        constexpr int GROUP = 8;                                                                \
+        const int per_group_ = GROUP * p.tiles_n;                                               \
+        const int grp_ = pid_ / per_group_;                                                     \
+        const int first_m_ = grp_ * GROUP;                                                      \
+        const int gsize_ = min(p.tiles_m - first_m_, GROUP);                                    \
+        const int in_grp_ = pid_ - grp_ * per_group_;                                           \
+        m0 = (first_m_ + in_grp_ % gsize_) * BM;                                                \
+        n0 = (in_grp_ / gsize_) * BN;                                                           \
+    }
+    int vpid = blockIdx.x;
+    FV_TILE_COORDS(vpid)
     static_assert(!SK || KG == 1, "split-K across workgroups is written for one k-group");
     const int n_splits = SK ? p.splits : 1;
     const int split = SK ? (int)blockIdx.y : 0;
@@ -161,12 +178,14 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
     // Per-lane byte offsets of the loads; they do not change along K (the scalar
     // base pointer advances instead), so a load costs no vector arithmetic.
     uint32_t a_off[A_LD], w_off[W_LD];
-#pragma unroll
-    for (int j = 0; j < A_LD; ++j)
-        a_off[j] = (uint32_t)(min(m0 + (wave + NW * j) * RPI + ld_row, p.M - 1) * p.K + ld_chunk * 8) * 2u;
-#pragma unroll
-    for (int j = 0; j < W_LD; ++j)
-        w_off[j] = (uint32_t)(min(n0 + (wave + NW * j) * RPI + ld_row, p.N - 1) * p.K + ld_chunk * 8) * 2u;
+#define FV_TILE_OFFSETS()                                                                       \
+    {                                                                                           \
+        _Pragma("unroll") for (int j = 0; j < A_LD; ++j)                                        \
+            a_off[j] = (uint32_t)(min(m0 + (wave + NW * j) * RPI + ld_row, p.M - 1) * p.K + ld_chunk * 8) * 2u; \
+        _Pragma("unroll") for (int j = 0; j < W_LD; ++j)                                        \
+            w_off[j] = (uint32_t)(min(n0 + (wave + NW * j) * RPI + ld_row, p.N - 1) * p.K + ld_chunk * 8) * 2u; \
+    }
+    FV_TILE_OFFSETS()
 
     // The loads are issued through inline assembly: the compiler's own model of
     // this instruction makes it drain every outstanding LDS operation before the
@@ -244,6 +263,14 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
         }                                                                                       \
     }
 
+    // ---- prologue: AHEAD tiles in flight (EARLY: every stage of the ring)
+    constexpr int AHEAD = EARLY ? STAGES : STAGES - 1;
+#define FV_ISSUE_PROLOGUE()                                                                     \
+    _Pragma("unroll") for (int s = 0; s < AHEAD; ++s)                                           \
+        if (s < KT) FV_ISSUE_TILE(s, s)
+    FV_ISSUE_PROLOGUE()
+    bool first_tile = true;
+    for (;;) {   // the tiles of this workgroup
     // The accumulators start from the bias, which saves the epilogue an add per element; with K split between
     // k-groups or workgroups only the first slice carries it.  (Accumulator blocks hold C transposed, see the
     // epilogue: register r of a lane is column 8*(r/4) + 4*(lane/32) + r%4 of the block.)
@@ -265,12 +292,10 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
             for (int r = 0; r < 16; ++r) acc[mi][ni][r] = b16[r];
     }
 
-    // ---- prologue: AHEAD tiles in flight (EARLY: every stage of the ring), wait for the first
-    constexpr int AHEAD = EARLY ? STAGES : STAGES - 1;
-#pragma unroll
-    for (int s = 0; s < AHEAD; ++s)
-        if (s < KT) FV_ISSUE_TILE(s, s)
-    if (KT >= AHEAD)
+    // ---- wait for the first K tile.  (A later tile of a persistent workgroup waits for everything: its
+    // loads went out before the previous epilogue's stores and residual loads, and the counter says
+    // nothing about the order in which loads and stores complete.)
+    if (first_tile && KT >= AHEAD)
         __builtin_amdgcn_s_waitcnt(waitcnt_imm((AHEAD - 1) * LPT, true));
     else
         __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
@@ -348,15 +373,21 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
         }
     });
     FV_TILE_BODY(false, false, 0)
-#undef FV_TILE_BODY
-#undef FV_INTERLEAVE
-#undef FV_MFMA_ROWS
-#undef FV_ISSUE_TILE
-#undef FV_ISSUE_Q
-#undef FV_DMA16
-#undef FV_LOAD_FRAGS_ISSUE_PART
-#undef FV_LOAD_FRAGS_ISSUE
-#undef FV_LOAD_FRAGS
+
+    // ---- the seam of a persistent workgroup: once every wave has read its last operands, the next tile's
+    // first stages are fetched; the epilogue of this tile (m0e, n0e) runs under their flight
+    const int m0e = m0, n0e = n0;
+    const int vnext = vpid + (int)gridDim.x;
+    const bool has_next = PERSIST && vnext < n_tiles;
+    if (has_next) {
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, true));
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        FV_TILE_COORDS(vnext)
+        FV_TILE_OFFSETS()
+        FV_ISSUE_PROLOGUE()
+    }
 
     // ---- Epilogue, from registers.  The MFMAs take the W fragment as their first operand, so an accumulator
     // block holds C transposed: register r of lane l is C[row, col] with row = l % 32 and
@@ -417,7 +448,7 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
         float* mine = part + (size_t)split * (BM * BN);
         static_for<0, MI>([&](auto mi_c) {
             constexpr int mi = decltype(mi_c)::value;
-            if (m0 + wm * WTM + mi * 32 < p.M) {
+            if (m0e + wm * WTM + mi * 32 < p.M) {
                 static_for<0, NI * 16>([&](auto j_c) {
                     constexpr int j = decltype(j_c)::value;
                     __hip_atomic_store(mine + (mi * NI * 16 + j) * (NWQ * 64), acc[mi][j / 16][j % 16],
@@ -438,7 +469,7 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
         // sum the slices in slice order; several slices' loads in flight at a time (128 registers' worth)
         static_for<0, MI>([&](auto mi_c) {
             constexpr int mi = decltype(mi_c)::value;
-            if (m0 + wm * WTM + mi * 32 < p.M) {
+            if (m0e + wm * WTM + mi * 32 < p.M) {
                 float sum[NI * 16];
                 _Pragma("unroll") for (int j = 0; j < NI * 16; ++j) sum[j] = 0.f;
                 constexpr int SG = 8 / NI > 0 ? 8 / NI : 1;
@@ -468,7 +499,7 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
     const int lrow = lane & 31;            // output row inside a 32-row block
     static_for<0, MI>([&](auto mi_c) {
         constexpr int mi = decltype(mi_c)::value;
-        const int m = m0 + wm * WTM + mi * 32 + lrow;
+        const int m = m0e + wm * WTM + mi * 32 + lrow;
         const bool row_ok = m < p.M;
         const int mc = row_ok ? m : p.M - 1;
         // (sample, token) of this lane's row, where its output goes and where its residual comes from
@@ -486,7 +517,7 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
         if (EPI == EPI_QKV_ROPE && p.rope_rows) slot = p.rope_rows[mc] % p.rope_N;
         static_for<0, NI>([&](auto ni_c) {
             constexpr int ni = decltype(ni_c)::value;
-            const int nb = n0 + wn * WTN + ni * 32;      // first column of the block (wave uniform)
+            const int nb = n0e + wn * WTN + ni * 32;      // first column of the block (wave uniform)
             if (nb >= p.N) return;                       // N % 32 may be non-zero only past whole 8-column groups: checked per group below
             // QKV: section, head and channel of the block's first column (wave uniform: scalar arithmetic); the
             // 32 columns of a block lie in one section and one head (D and dh are multiples of 32)
@@ -571,7 +602,38 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
             }
         });
     });
+    if (!has_next) break;
+    vpid = vnext;
+    first_tile = false;
+    }   // the tiles of this workgroup
+#undef FV_TILE_BODY
+#undef FV_INTERLEAVE
+#undef FV_MFMA_ROWS
+#undef FV_ISSUE_PROLOGUE
+#undef FV_ISSUE_TILE
+#undef FV_ISSUE_Q
+#undef FV_DMA16
+#undef FV_LOAD_FRAGS_ISSUE_PART
+#undef FV_LOAD_FRAGS_ISSUE
+#undef FV_LOAD_FRAGS
+#undef FV_TILE_OFFSETS
+#undef FV_TILE_COORDS
 #endif
+}
+
+// Compute units of the current device (asked once per process and device).
+inline int compute_units() {
+    static std::mutex mu;
+    static int cus[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    std::lock_guard<std::mutex> lock(mu);
+    if (cus[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cus[dev] = n;
+    }
+    return cus[dev];
 }
 
 template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, int KG, int EPI, bool SK = false>
@@ -582,8 +644,16 @@ void launch_cfg(GemmParams& p, hipStream_t stream) {
     static std::once_flag once;  // raising the dynamic-LDS limit is per function, once per process
     raise_lds_limit_once(once, &gemm_nt_kernel<BM, BN, BK, STAGES, WGM, WGN, KG, EPI, SK>, smem);
     if (!SK) p.splits = 1;
+    // one round of workgroups when there are more tiles than the chip holds at a time (the kernel then walks
+    // the rest itself); as many workgroups per CU as fit into its 160 KB of LDS
+    int grid = p.tiles_m * p.tiles_n;
+    if (kPersistent<EPI, KG, SK>) {
+        constexpr int per_cu = (int)((160u << 10) / smem) > 0 ? (int)((160u << 10) / smem) : 1;
+        const int slots = compute_units() * per_cu;
+        if (grid > slots && slots % 8 == 0) grid = slots;
+    }
     gemm_nt_kernel<BM, BN, BK, STAGES, WGM, WGN, KG, EPI, SK>
-        <<<dim3(p.tiles_m * p.tiles_n, SK ? p.splits : 1), 64 * WGM * WGN * KG, smem, stream>>>(p);
+        <<<dim3(grid, SK ? p.splits : 1), 64 * WGM * WGN * KG, smem, stream>>>(p);
 }
 
 __global__ void zero_i32_kernel(int32_t* p, int n) {

@@ -90,6 +90,9 @@ def test_gemm_exact_small_integers():
     (synth.BlockDims(256, 2, 128, 512), 3, 70, 45, 128),
     (synth.D16, 1, 128, 424, 688),
     (synth.INF2B, 1, 300, 0, 304),
+    # more tiles than one round of workgroups (the launch walks its tiles itself), ragged last row tiles
+    (synth.INF2B, 2, 1500, 100, 1608),
+    (synth.D30, 8, 410, 70, 480),
 ])
 def test_qkv_gemm_appends_to_caches(dims, B, k, L0, L_cap):
     print(f"[qkv] D={dims.D} H={dims.H} dh={dims.dh} B={B} k={k} L0={L0}", flush=True)

@@ -78,11 +78,12 @@ def check_block_rope(name, dims, B, h, w, k, L0, L_cap, seed, ref=None, rows=Non
         assert max_rel(kn_plain, kn) > 10 * TOL
     if scale is not None:     # peaked attention: the block output itself tells the two apart
         assert max_rel(y_plain, yo) > 2 * TOL
-    return max_rel(y_plain, yo)
+    # cache rows outside [L0, L0 + k) keep their bits
     kb, kb0 = kc.view(torch.int16), kc0.view(torch.int16)
     vb, vb0 = vc.view(torch.int16), vc0.view(torch.int16)
     assert torch.equal(kb[:, :, :L0], kb0[:, :, :L0]) and torch.equal(kb[:, :, L0 + k:], kb0[:, :, L0 + k:])
     assert torch.equal(vb[:, :, :, :L0], vb0[:, :, :, :L0]) and torch.equal(vb[:, :, :, L0 + k:], vb0[:, :, :, L0 + k:])
+    return max_rel(y_plain, yo)
 
 
 ROPE_CASES = [
@@ -116,10 +117,13 @@ def test_block_with_rope_headline_size_sampled_rows():
     check_block_rope("headline_sampled", wl.dims, 1, wl.h, wl.h, wl.k, wl.L0_full, 8480, seed=24, rows=rows)
 
 
-def test_qkv_gemm_rope_component_and_values_untouched():
+@pytest.mark.parametrize("dims,B,h,w,k,L0,L_cap", [
+    (synth.D16, 2, 10, 12, 50, 17, 72),
+    (synth.INF2B, 2, 48, 48, 1500, 100, 1608),    # more tiles than one round of workgroups
+])
+def test_qkv_gemm_rope_component_and_values_untouched(dims, B, h, w, k, L0, L_cap):
     """The component entry point with a per-sample index list: q and K turned by the slots' angles, V the
     same bits as the plain QKV GEMM writes."""
-    dims, B, h, w, k, L0, L_cap = synth.D16, 2, 10, 12, 50, 17, 72
     print(f"[qkv+rope] D={dims.D} dh={dims.dh} B={B} N={h*w} k={k}", flush=True)
     N = h * w
     rng = np.random.default_rng(8)

@@ -301,12 +301,15 @@ def cpu_baseline(wl, st, n_blocks, target_seconds=12.0, max_reps=16):
                 block_seconds=round(dt, 3), affinity_cores=cores, blas_threads=blas)
 
 
-def schedule_bench(wl, n_blocks, steps, warmup, keeps=(0.6, 0.5, 0.0, 0.0)):
+def schedule_bench(wl, n_blocks, steps, warmup, keeps=(0.6, 0.5, 0.0, 0.0), graphs=False):
     """The whole scale schedule of the workload's model through fastvar_scale_step, twice: every step
     unpruned, and with the last len(keeps) steps pruned to the given keep ratios after a cache capture
     at the step before them (the paper's setting for this model: pruning ratios 40, 50, 100, 100 % on
     the last four steps).  Token maps are seeded synthetic ones per scale (the tokenizer and the
-    residual accumulation between scales are outside the library).  Returns a dict for the JSON line."""
+    residual accumulation between scales are outside the library).  graphs: every scale's call is captured
+    into a HIP graph once (the library allocates nothing and clears its counters with a kernel, so its calls
+    can be captured) and the timed images replay the graphs: the small scales are bound by launches, not by
+    work.  Returns a dict for the JSON line."""
     import torch
     from paper_2503_23367_amd import binding as fb
     dev = "cuda:0"
@@ -356,19 +359,40 @@ def schedule_bench(wl, n_blocks, steps, warmup, keeps=(0.6, 0.5, 0.0, 0.0)):
                    for i in range(K) for pruned in (False, True))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
 
+    captured = {}
+
+    def capture(pruned):
+        """One graph per scale; an eager call first, so that nothing happens for the first time under capture."""
+        kv = 0
+        for i in range(K):
+            args = (xs[i], sides, sides, i, cache_step, B, k_of(i, pruned), d, arr, kv, L_cap, y, tmp, idx, ws)
+            kv_next = fb.fastvar_scale_step(*args)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                fb.fastvar_scale_step(*args)
+            captured[(pruned, i)] = g
+            kv = kv_next
+
     def one_image(pruned, stamps=None):
         kv = 0
         for i in range(K):
             if stamps is not None:
                 stamps[i].record()
-            kv = fb.fastvar_scale_step(xs[i], sides, sides, i, cache_step, B, k_of(i, pruned), d, arr, kv, L_cap,
-                                       y, tmp, idx, ws)
+            if graphs:
+                captured[(pruned, i)].replay()
+                kv += k_of(i, pruned)
+            else:
+                kv = fb.fastvar_scale_step(xs[i], sides, sides, i, cache_step, B, k_of(i, pruned), d, arr, kv,
+                                           L_cap, y, tmp, idx, ws)
         if stamps is not None:
             stamps[K].record()
         return kv
 
     out = {}
     for name, pruned in (("unpruned", False), ("fastvar", True)):
+        if graphs:
+            capture(pruned)
         for _ in range(warmup):
             one_image(pruned)
         torch.cuda.synchronize()
@@ -385,7 +409,8 @@ def schedule_bench(wl, n_blocks, steps, warmup, keeps=(0.6, 0.5, 0.0, 0.0)):
     out["speedup"] = round(out["unpruned"]["ms_per_image"] / out["fastvar"]["ms_per_image"], 3)
     out["last_two_scales_share_unpruned"] = round(sum(out["unpruned"]["ms_per_scale"][-2:]) /
                                                   sum(out["unpruned"]["ms_per_scale"]), 3)
-    return dict(sides=sides, cache_step=cache_step, keep_ratios=list(keeps), blocks=n_blocks, **out)
+    return dict(sides=sides, cache_step=cache_step, keep_ratios=list(keeps), blocks=n_blocks, hip_graphs=bool(graphs),
+                **out)
 
 
 def main():
@@ -401,6 +426,8 @@ def main():
     ap.add_argument("--schedule", action="store_true",
                     help="instead of the headline step: the model's whole scale schedule, unpruned and with the "
                          "last four steps pruned (one JSON line of its own)")
+    ap.add_argument("--graphs", action="store_true",
+                    help="with --schedule: capture every scale's call into a HIP graph once and replay the graphs")
     ap.add_argument("--kernel-iters", type=int, default=20)
     ap.add_argument("--kernel-loop", default=None, metavar="STAGE",
                     help="profiling aid: run only this stage of the kernel table (e.g. 'qkv gemm') back to back "
@@ -426,7 +453,7 @@ def main():
     n_blocks = args.blocks or wl.n_blocks
     log(f"workload {wl.name}: B={wl.B} N={wl.N} k={wl.k} L0={wl.L0_full} D={wl.dims.D} blocks={n_blocks}")
     if args.schedule:
-        res = schedule_bench(wl, n_blocks, args.steps, args.warmup)
+        res = schedule_bench(wl, n_blocks, args.steps, args.warmup, graphs=args.graphs)
         print(json.dumps({"metric": "whole scale schedule, transformer stack only: ms per image unpruned vs "
                                     "FastVAR pruning schedule", "value": res["speedup"], "unit": "x (unpruned / pruned)",
                           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -435,7 +462,7 @@ def main():
                           "config": {"workload": wl.name + " (all scales)", **{k: res[k] for k in
                                      ("sides", "cache_step", "keep_ratios", "blocks")}},
                           "schedule": {k: res[k] for k in ("unpruned", "fastvar", "speedup",
-                                                             "last_two_scales_share_unpruned")}}), flush=True)
+                                                             "last_two_scales_share_unpruned", "hip_graphs")}}), flush=True)
         return
     t0 = time.perf_counter()
     st = build_state(wl, n_blocks, wiring=args.wiring)

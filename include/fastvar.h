@@ -26,6 +26,11 @@
  *     fastvar_select_pivotal_static) and never synchronises: each call validates its
  *     arguments on the host, enqueues its kernels on `stream`
  *     (a hipStream_t passed as void*; NULL = the default stream) and returns.
+ *   - HIP graphs: a call that has run once eagerly on the device (first use
+ *     raises a kernel's LDS limit, which is not a stream operation) may be
+ *     captured into a graph: it only launches kernels (its arrival counters
+ *     are cleared by a kernel, not by a memset node).  fastvar_scale_step_timed
+ *     is the exception: it records events and waits.
  *   - Return value: FASTVAR_OK (0) or a negative FASTVAR_E* code.  Arguments
  *     are checked before anything is launched; on an argument error no output
  *     buffer is touched.

@@ -367,13 +367,9 @@ def _rand_layers(dims, n, B, L0, L_cap, hc, seed):
     return out
 
 
-@pytest.mark.parametrize("case", ["headline_two_blocks", "keep0.25_key_ranges", "structure_step_split_k"])
-def test_same_inputs_give_the_same_bits_every_run(case):
-    """Same inputs, same bits: the stack step run 20 times.  The headline step merges two key ranges per
-    query tile in its attention; the keep 0.25 step three; the structure step (144 tokens at the large
-    model's widths) splits K between workgroups in all four GEMMs.  All of them let the workgroup that
-    arrives last combine the partial results, so a result that depended on arrival order, or a partial
-    result read before it was complete, would show here as a changed bit.  Stops at the first difference."""
+def _two_block_case(case):
+    """A two-block stack step of the large model on one of the paths that merge partial results between
+    workgroups; returns the call, a poisoner of outputs and scratch, and a snapshot of everything it writes."""
     dims = synth.INF2B
     d = fb.make_dims(dims.D, dims.H, dims.dh, dims.F)
     if case == "structure_step_split_k":
@@ -385,7 +381,6 @@ def test_same_inputs_give_the_same_bits_every_run(case):
         B, N, k, L0 = 1, wl.N, wl.k, wl.L0_full
         sides, step, cache_step, hc = list(wl.sides), wl.step, wl.cache_step, wl.hc
     L_cap = (L0 + k + 7) // 8 * 8
-    print(f"[determinism] {case}: N={N} k={k} L0={L0}, 2 blocks, 20 runs", flush=True)
     layers = _rand_layers(dims, 2, B, L0, L_cap, hc, seed=21)
     arr = fb.make_layers(layers)
     x = to_dev_bf16(synth.token_map(17, B, sides[step], sides[step], dims.D))
@@ -393,20 +388,74 @@ def test_same_inputs_give_the_same_bits_every_run(case):
     y = torch.empty((B, N, dims.D), dtype=torch.bfloat16, device=DEV)
     tmp = torch.empty_like(y)
     idx = torch.zeros((B, k), dtype=torch.int32, device=DEV)
-    first = None
-    for run in range(20):
-        ws.fill_(0xFF if run % 2 else 0x00)     # whatever the scratch held before must not matter
+
+    def call():
+        fb.fastvar_scale_step(x, sides, sides, step, cache_step, B, k, d, arr, L0, L_cap, y, tmp, idx, ws)
+
+    def poison(run):
+        ws.fill_(0xFF if run % 2 else 0x00)
         y.fill_(float("nan"))
         tmp.fill_(float("nan"))
-        fb.fastvar_scale_step(x, sides, sides, step, cache_step, B, k, d, arr, L0, L_cap, y, tmp, idx, ws)
-        torch.cuda.synchronize()
+
+    def snapshot():
         got = [y.view(torch.int16).clone(), tmp.view(torch.int16).clone(), idx.clone()]
         for ly in layers:
             got.append(ly["kc"][:, :, L0:L0 + k].view(torch.int16).clone())
             got.append(ly["vc"][:, :, :, L0:L0 + k].view(torch.int16).clone())
+        return got
+
+    return dict(N=N, k=k, L0=L0, y=y, call=call, poison=poison, snapshot=snapshot, keep=(layers, arr, x, ws, tmp, idx))
+
+
+@pytest.mark.parametrize("case", ["headline_two_blocks", "keep0.25_key_ranges", "structure_step_split_k"])
+def test_same_inputs_give_the_same_bits_every_run(case):
+    """Same inputs, same bits: the stack step run 20 times.  The headline step merges two key ranges per
+    query tile in its attention; the keep 0.25 step three; the structure step (144 tokens at the large
+    model's widths) splits K between workgroups in all four GEMMs.  All of them let the workgroup that
+    arrives last combine the partial results, so a result that depended on arrival order, or a partial
+    result read before it was complete, would show here as a changed bit.  Stops at the first difference."""
+    c = _two_block_case(case)
+    print(f"[determinism] {case}: N={c['N']} k={c['k']} L0={c['L0']}, 2 blocks, 20 runs", flush=True)
+    first = None
+    for run in range(20):
+        c["poison"](run)                        # whatever the scratch held before must not matter
+        c["call"]()
+        torch.cuda.synchronize()
+        got = c["snapshot"]()
+        y = c["y"]
         if first is None:
             first = got
             assert not torch.isnan(y.float()).any()
             continue
         for i, (a, b) in enumerate(zip(first, got)):
             assert torch.equal(a, b), f"run {run}: tensor {i} differs from the first run"
+
+
+@pytest.mark.parametrize("case", ["keep0.25_key_ranges", "structure_step_split_k"])
+def test_scale_step_replayed_from_a_hip_graph(case):
+    """A caller may capture the step into a HIP graph: the library allocates nothing, clears its arrival
+    counters with a kernel (not a memset node) and sets function attributes on a first, eager call only.
+    The captured step is replayed three times, with eager calls, fills and synchronisations between the
+    replays, and every replay is compared bit for bit with the eager result."""
+    c = _two_block_case(case)
+    print(f"[graph] {case}: N={c['N']} k={c['k']} L0={c['L0']}, 2 blocks, 3 replays", flush=True)
+    c["poison"](0)
+    c["call"]()
+    torch.cuda.synchronize()
+    ref = c["snapshot"]()
+    assert not torch.isnan(c["y"].float()).any()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        c["call"]()
+    for rep in range(3):
+        c["poison"](rep + 1)
+        g.replay()
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(zip(ref, c["snapshot"]())):
+            assert torch.equal(a, b), f"replay {rep}: tensor {i} differs from the eager result"
+        c["poison"](rep)
+        c["call"]()                              # the program's own eager work between the replays
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(zip(ref, c["snapshot"]())):
+            assert torch.equal(a, b), f"eager call after replay {rep}: tensor {i} differs"
+

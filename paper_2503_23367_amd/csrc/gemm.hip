@@ -768,17 +768,21 @@ void launch_epi(GemmParams& p, hipStream_t stream) {
 
 SplitKPlan gemm_splitk_plan(int M, int N, int K) {
     SplitKPlan sk;
-    sk.small_tiles = M <= 64;
+    // Up to 256 rows the tiles are 64x64 (eight stages): at those row counts the GEMMs stream their weights,
+    // and what counts is how many workgroups pull on them.  Measured inside 32-block steps of the large model
+    // (us per launch, 144 / 256 rows): out-proj 13.1 / 14.1 against 21.0 / 21.1 with 128x128 tiles on four
+    // slices, FC2 23.4 / 28.4 against 31.4 / 35.3.  Above that, 128x128 tiles split K only where K is long
+    // (FC2): with K = 2048 a slice is 8-16 K tiles and the summing costs more than it saves (out-proj at
+    // 400 / 576 rows: 21.3 / 23.8 split, 14.9 / 20.6 whole).
+    sk.small_tiles = M <= 256;
     const int t = sk.small_tiles ? 64 : 128;
     sk.tiles = ((M + t - 1) / t) * ((N + t - 1) / t);
     sk.splits = 1;
     const int KT = K / 64;
     const int min_kt = sk.small_tiles ? 2 : 4;   // K tiles a slice must keep
     // a short K range is over before the slices' summing would pay for itself
-    static_assert(kSplitKMaxTiles >= 128 && (kSplitKMaxTiles * 4) % 256 == 0, "covers both tile-count limits below");
-    // (up to 96 tiles of 128x128 whatever K >= 2048; up to 128, i.e. half the chip, where K is long enough
-    // for the halves to be worth a partial tile each)
-    if (K >= 2048 && sk.tiles <= (sk.small_tiles ? 128 : (K >= 4096 ? 128 : 96)))
+    static_assert(kSplitKMaxTiles >= 128 && (kSplitKMaxTiles * 4) % 256 == 0, "covers the tile-count limit below");
+    if (K >= (sk.small_tiles ? 2048 : 4096) && sk.tiles <= 128)
         while (sk.splits < (sk.small_tiles ? 8 : 4) && sk.tiles * sk.splits * 2 <= 256 &&
                KT % (sk.splits * 2) == 0 && KT / (sk.splits * 2) >= min_kt)
             sk.splits *= 2;   // (more slices than that cost more to sum than they save)

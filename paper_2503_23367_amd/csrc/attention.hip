@@ -46,6 +46,7 @@ struct AttnParams {
     int q_tiles, splits, keys_per_split, full_tiles, tail_tiles;
     float* part;   // [tail tile][split][1 + DB*QB*4 vectors][QG*64 lanes][4] fp32
     int* split_cnt;   // [tail tile] arrival counters, zero between launches
+    int* split_ready; // [tail tile] ranges whose partial result is complete in memory, zero between launches
 };
 
 __device__ __forceinline__ int swap_bits_2_3(int v) {
@@ -997,13 +998,16 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
     }
 #undef FP_PUBLISH
     if (KVS && nsp > 1) {
-        // Every key range leaves its partial result (statistics, then the accumulator) and counts itself in at
-        // the query tile's counter; the workgroup that arrives last combines all ranges exactly, in range
-        // order (its own from registers), normalises and stores.  The partials go out and come back as
+        // A key range first counts itself in at the query tile's counter.  Every range but the last to arrive
+        // then leaves its partial result (statistics, then the accumulator), waits until its stores have been
+        // acknowledged and reports ready; the last to arrive keeps its own part in registers, waits for the
+        // others' reports (they are running and past their key loops, so the wait is short and always ends; it
+        // is bounded all the same) and combines all ranges exactly, in range order, normalises and stores.
+        // Against every range storing before it counts: a range's worth less of traffic, and the last
+        // arriver's own stores are off the launch's critical path.  The partials go out and come back as
         // 16 bytes per lane with the device-scope cache policy (written through to, and read from, the
-        // memory side of the chip's eight L2s, where they are coherent by themselves); the counter is a
-        // device-scope relaxed atomic; every thread waits for its own stores to be acknowledged before the
-        // barrier that precedes the count.  Nobody waits for anybody.
+        // memory side of the chip's eight L2s, where they are coherent by themselves); counter and ready
+        // count are device-scope relaxed atomics.
         // Layout per (query tile, range): [vector][QG*64 lanes][4 floats]; vector 0 holds the statistics
         // (running maxima, then row sums, of the lane's two query blocks), vector 1 + (db*QB + qb)*4 + g
         // the accumulator registers 4g .. 4g+3 of block (db, qb).
@@ -1018,34 +1022,96 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
         float l_tot[QB];
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) l_tot[qb] = l_run[qb] + other_half(l_run[qb]);
-        if (kh == 0) {
-            const uint32_t mine = (uint32_t)split * vstride + lane_off;
-            const f32x4_t st = {m_run[0], m_run[1], l_tot[0], l_tot[1]};
-            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, st), rsrc, mine, 0, kDeviceScope);
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const f32x4_t v = {acc[db][qb][4 * g + 0], acc[db][qb][4 * g + 1], acc[db][qb][4 * g + 2],
-                                           acc[db][qb][4 * g + 3]};
-                        __builtin_amdgcn_raw_buffer_store_b128(
-                            __builtin_bit_cast(u32x4_t, v), rsrc,
-                            mine + (uint32_t)(1 + (db * QB + qb) * 4 + g) * (QG * 64 * 16), 0, kDeviceScope);
-                    }
-        }
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_waitcnt(attn_waitcnt(0, true));   // own stores acknowledged
         int* flag = reinterpret_cast<int*>(smem);
-        __syncthreads();
+        __syncthreads();                 // the flag's LDS word was tile or merge memory
         if (tid == 0)
             *flag = __hip_atomic_fetch_add(p.split_cnt + tile_id, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();
         const int arrived = *flag;
-        if (arrived != p.splits - 1) return;
-        if (tid == 0) __hip_atomic_store(p.split_cnt + tile_id, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (arrived != p.splits - 1) {
+            if (kh == 0) {
+                const uint32_t mine = (uint32_t)split * vstride + lane_off;
+                const f32x4_t st = {m_run[0], m_run[1], l_tot[0], l_tot[1]};
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, st), rsrc, mine, 0, kDeviceScope);
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            const f32x4_t v = {acc[db][qb][4 * g + 0], acc[db][qb][4 * g + 1], acc[db][qb][4 * g + 2],
+                                               acc[db][qb][4 * g + 3]};
+                            __builtin_amdgcn_raw_buffer_store_b128(
+                                __builtin_bit_cast(u32x4_t, v), rsrc,
+                                mine + (uint32_t)(1 + (db * QB + qb) * 4 + g) * (QG * 64 * 16), 0, kDeviceScope);
+                        }
+            }
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_waitcnt(attn_waitcnt(0, true));   // own stores acknowledged
+            __syncthreads();
+            if (tid == 0)
+                __hip_atomic_fetch_add(p.split_ready + tile_id, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return;
+        }
+        if (tid == 0) {
+            // about a microsecond per look; the bound is never reached by a launch that is making progress
+            for (int looks = 0; looks < (1 << 20); ++looks) {
+                if (__hip_atomic_load(p.split_ready + tile_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                    p.splits - 1)
+                    break;
+                __builtin_amdgcn_s_sleep(8);
+            }
+            // ready for the next launch
+            __hip_atomic_store(p.split_cnt + tile_id, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(p.split_ready + tile_id, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
         if (kh != 0) return;
+        if (p.splits == 2) {
+            // Two ranges: the other range's statistics and all 32 accumulator vectors of a lane are fetched
+            // together (one round trip to the memory side, 0.9 us, instead of one per accumulator block), then
+            // summed in range order, r = fma(w1, part1, w0 * part0), whichever of the two this workgroup holds
+            // in registers: the result does not depend on who arrived last.
+            const int other = split ^ 1;
+            f32x4_t pv[VECS];
+#pragma unroll
+            for (int vi = 0; vi < VECS; ++vi)
+                pv[vi] = __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
+                                                         rsrc, (uint32_t)other * vstride + lane_off +
+                                                                   (uint32_t)vi * (QG * 64 * 16), 0, kDeviceScope));
+            __builtin_amdgcn_sched_barrier(0);   // every load is out before the first use
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                const float m_o = pv[0][qb], l_o = pv[0][2 + qb];
+                const float m = fmaxf(m_run[qb], m_o);
+                const float w_me = __builtin_amdgcn_exp2f(m_run[qb] - m), w_o = __builtin_amdgcn_exp2f(m_o - m);
+                const float w0 = split == 0 ? w_me : w_o, w1 = split == 0 ? w_o : w_me;
+                const float l0 = split == 0 ? l_tot[qb] : l_o, l1 = split == 0 ? l_o : l_tot[qb];
+                const float inv = 1.0f / __builtin_fmaf(w1, l1, w0 * l0);
+                const int qrow = q_base + qb * 32 + li;
+                bf16_t* dst = p.o + ((size_t)b * p.k_tokens + min(qrow, p.k_tokens - 1)) * p.D + head * DH + 4 * hf;
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    float o[16];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float mine = acc[db][qb][r], theirs = pv[1 + (db * QB + qb) * 4 + r / 4][r % 4];
+                        const float p0 = split == 0 ? mine : theirs, p1 = split == 0 ? theirs : mine;
+                        o[r] = __builtin_fmaf(w1, p1, w0 * p0);
+                    }
+                    if (qrow < p.k_tokens) {
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            u32x2_t pk;
+                            pk.x = pack_bf16x2(o[4 * g + 0] * inv, o[4 * g + 1] * inv);
+                            pk.y = pack_bf16x2(o[4 * g + 2] * inv, o[4 * g + 3] * inv);
+                            *reinterpret_cast<u32x2_t*>(dst + db * 32 + 8 * g) = pk;
+                        }
+                    }
+                }
+            }
+            return;
+        }
         // statistics of every range (at most four), own from registers
         float ms[4][QB], ls[4][QB];
         for (int s2 = 0; s2 < p.splits; ++s2) {
@@ -1197,7 +1263,8 @@ AttnSplitPlan attention_split_plan(int B, int H, int dh, int k_tokens, int L, si
     const long wg256 = (long)((k_tokens + 255) / 256) * H * B;
     const size_t per_query_row = (size_t)(1 + 4 * 2 * 4) * 64 * 16;   // per wave of 64 queries: 33 vectors of 16 bytes per lane
     // The counters take the same room whichever variant is chosen (one per 128-query tile, the larger count).
-    const size_t counter_bytes = ((size_t)wg128 * 4 + 255) & ~(size_t)255;
+    // (two per tile: arrivals, and ranges whose partial result is complete)
+    const size_t counter_bytes = ((size_t)wg128 * 8 + 511) & ~(size_t)511;
     auto ranges_ok = [&](int s, int bn, int& per) {
         per = (((L + s - 1) / s) + bn - 1) / bn * bn;          // whole key tiles
         return per > 2 * bn && L - (s - 1) * per > 2 * bn;     // every range has at least three tiles
@@ -1280,7 +1347,7 @@ void launch_attention(const AttnArgs& a, hipStream_t stream) {
     p.o = static_cast<bf16_t*>(a.o);
     p.H = a.H; p.k_tokens = a.k_tokens; p.L = a.L; p.L_cap = a.L_cap; p.D = a.H * a.dh;
     p.scale_log2e = a.scale * 1.4426950408889634f;
-    p.q_tiles = (a.k_tokens + 127) / 128; p.splits = 1; p.keys_per_split = 0; p.part = nullptr; p.split_cnt = nullptr;
+    p.q_tiles = (a.k_tokens + 127) / 128; p.splits = 1; p.keys_per_split = 0; p.part = nullptr; p.split_cnt = nullptr; p.split_ready = nullptr;
     p.full_tiles = p.tail_tiles = 0;
     if (a.split_ws && attn_cfg_override() < 0) {
         const AttnSplitPlan sp = attention_split_plan(a.B, a.H, a.dh, a.k_tokens, a.L, a.split_ws_bytes);
@@ -1288,6 +1355,7 @@ void launch_attention(const AttnArgs& a, hipStream_t stream) {
             p.splits = sp.splits; p.keys_per_split = sp.keys_per_split;
             p.full_tiles = sp.full_tiles; p.tail_tiles = sp.tail_tiles;
             p.split_cnt = static_cast<int*>(a.split_ws);
+            p.split_ready = p.split_cnt + sp.counter_bytes / 8;
             p.part = reinterpret_cast<float*>(static_cast<char*>(a.split_ws) + sp.counter_bytes);
             if (sp.wide) {
                 p.q_tiles = (a.k_tokens + 255) / 256;

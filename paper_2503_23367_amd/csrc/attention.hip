@@ -33,6 +33,10 @@ namespace fv {
 
 namespace {
 
+// Every query tile's counters have a 128-byte line of their own: the workgroups of different tiles count and
+// poll at the same time, and atomics on one line are served one after the other.
+constexpr int kCounterStride = 32;
+
 struct AttnParams {
     const bf16_t* q;
     const bf16_t* kc;
@@ -45,8 +49,8 @@ struct AttnParams {
     // one workgroup each; each of the other tail_tiles is shared by `splits` workgroups
     int q_tiles, splits, keys_per_split, full_tiles, tail_tiles;
     float* part;   // [tail tile][split][1 + DB*QB*4 vectors][QG*64 lanes][4] fp32
-    int* split_cnt;   // [tail tile] arrival counters, zero between launches
-    int* split_ready; // [tail tile] ranges whose partial result is complete in memory, zero between launches
+    int* split_cnt;   // [tail tile][kCounterStride] arrival counters, zero between launches
+    int* split_ready; // [tail tile][kCounterStride] ranges whose partial result is complete in memory, zero between launches
 };
 
 __device__ __forceinline__ int swap_bits_2_3(int v) {
@@ -1025,7 +1029,7 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
         int* flag = reinterpret_cast<int*>(smem);
         __syncthreads();                 // the flag's LDS word was tile or merge memory
         if (tid == 0)
-            *flag = __hip_atomic_fetch_add(p.split_cnt + tile_id, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *flag = __hip_atomic_fetch_add(p.split_cnt + tile_id * kCounterStride, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();
         const int arrived = *flag;
         if (arrived != p.splits - 1) {
@@ -1050,20 +1054,20 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(con
             __builtin_amdgcn_s_waitcnt(attn_waitcnt(0, true));   // own stores acknowledged
             __syncthreads();
             if (tid == 0)
-                __hip_atomic_fetch_add(p.split_ready + tile_id, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_fetch_add(p.split_ready + tile_id * kCounterStride, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             return;
         }
         if (tid == 0) {
             // about a microsecond per look; the bound is never reached by a launch that is making progress
             for (int looks = 0; looks < (1 << 20); ++looks) {
-                if (__hip_atomic_load(p.split_ready + tile_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                if (__hip_atomic_load(p.split_ready + tile_id * kCounterStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
                     p.splits - 1)
                     break;
                 __builtin_amdgcn_s_sleep(8);
             }
             // ready for the next launch
-            __hip_atomic_store(p.split_cnt + tile_id, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(p.split_ready + tile_id, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(p.split_cnt + tile_id * kCounterStride, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(p.split_ready + tile_id * kCounterStride, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         __syncthreads();
         if (kh != 0) return;
@@ -1264,7 +1268,7 @@ AttnSplitPlan attention_split_plan(int B, int H, int dh, int k_tokens, int L, si
     const size_t per_query_row = (size_t)(1 + 4 * 2 * 4) * 64 * 16;   // per wave of 64 queries: 33 vectors of 16 bytes per lane
     // The counters take the same room whichever variant is chosen (one per 128-query tile, the larger count).
     // (two per tile: arrivals, and ranges whose partial result is complete)
-    const size_t counter_bytes = ((size_t)wg128 * 8 + 511) & ~(size_t)511;
+    const size_t counter_bytes = (size_t)wg128 * 8 * kCounterStride;
     auto ranges_ok = [&](int s, int bn, int& per) {
         per = (((L + s - 1) / s) + bn - 1) / bn * bn;          // whole key tiles
         return per > 2 * bn && L - (s - 1) * per > 2 * bn;     // every range has at least three tiles

@@ -530,8 +530,8 @@ __global__ __launch_bounds__(QG * KSPLIT * 64, (QB == 1 ? 2 : 1)) void attention
 // reads past L_cap, its leading keys (already seen) and the up to 7 positions past L are masked.
 // KVS: the key range is also split between workgroups (consecutive query-tile ids of the grid's x
 // dimension are the same tile's splits); each works on keys [split*keys_per_split, ...) as if they
-// were the whole cache and leaves its unnormalised output and statistics for the workgroup that
-// arrives last at the tile, which merges the ranges.
+// were the whole cache; the workgroup that arrives last at the tile merges the ranges, the others leave
+// their unnormalised output and statistics for it.
 template <int DH, int QG, int KSPLIT, bool KVS = false>
 __global__ __launch_bounds__(QG * KSPLIT * 64, 1) void attention_pipe_kernel(const AttnParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub

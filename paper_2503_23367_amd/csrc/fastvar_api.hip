@@ -52,7 +52,7 @@ BlockPlan block_plan(const fastvar_dims* d, int B, int k) {
     for (const auto& nk : shapes) {
         const fv::SplitKPlan sk = fv::gemm_splitk_plan((int)M, nk[0], nk[1]);
         if (sk.bytes > p.sk_bytes) p.sk_bytes = sk.bytes;
-        if (sk.splits > 1) p.sk_counters = fv::kSplitKMaxTiles;
+        if (sk.splits > 1) p.sk_counters = (int)(sk.counter_bytes / 4);
     }
     p.off_sk = off; off += round256(p.sk_bytes);
     p.bytes = off;

@@ -64,6 +64,7 @@ struct GemmParams {
     int splits;        // split-K slices (grid.y); 1 unless the kernel is instantiated with SK
     float* sk_part;    // [tile][slice][BM*BN] fp32 partial tiles, accumulator-register order
     int* sk_cnt;       // [tile] arrival counters, zero between launches
+    int* sk_ready;     // [tile] slices whose partial tile is complete in memory (CF kernels), zero between launches
 };
 
 // s_waitcnt immediate (gfx9 encoding): wait until at most `vm` vector-memory
@@ -93,7 +94,7 @@ __device__ __forceinline__ int swz(int row) {
 template <int EPI, int KG, bool SK>
 constexpr bool kPersistent = !SK && KG == 1 && is_qkv(EPI);
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, int KG, int EPI, bool SK = false>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, int KG, int EPI, bool SK = false, bool CF = false>
 __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const GemmParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
     constexpr int NWQ = WGM * WGN;             // waves per k-group
@@ -436,7 +437,80 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void gemm_nt_kernel(const Gemm
         }
         if (kg != 0) return;  // no barrier follows
     }
-    if (SK) {
+    if (SK && CF) {
+        // Large partial tiles (256x128 fp32 = 128 KB): count first, store only if not last.  A slice counts
+        // itself in at the tile's counter; every slice but the last to arrive then leaves its partial tile,
+        // waits until its stores have been acknowledged and reports ready; the last to arrive keeps its own
+        // accumulators, polls the ready count (the others are running and past their K loops: the wait is short
+        // and always ends, and it is bounded all the same), adds the slices up in slice order and runs the
+        // epilogue.  Half the stores of the other order, and none on the last arriver's path.  (For the few-KB
+        // partials of the few-row shapes a poll costs more than the stores it saves: they keep the order below.)
+        float* part = p.sk_part + ((size_t)blockIdx.x * n_splits) * (BM * BN) + wq * 64 + lane;
+        int* flag = reinterpret_cast<int*>(smem);
+        if (tid == 0)
+            *flag = __hip_atomic_fetch_add(p.sk_cnt + blockIdx.x, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        const int arrived = *flag;
+        if (arrived != n_splits - 1) {
+            float* mine = part + (size_t)split * (BM * BN);
+            static_for<0, MI>([&](auto mi_c) {
+                constexpr int mi = decltype(mi_c)::value;
+                if (m0e + wm * WTM + mi * 32 < p.M) {
+                    static_for<0, NI * 16>([&](auto j_c) {
+                        constexpr int j = decltype(j_c)::value;
+                        __hip_atomic_store(mine + (mi * NI * 16 + j) * (NWQ * 64), acc[mi][j / 16][j % 16],
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    });
+                }
+            });
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));   // own stores acknowledged
+            __syncthreads();
+            if (tid == 0)
+                __hip_atomic_fetch_add(p.sk_ready + blockIdx.x, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return;
+        }
+        if (tid == 0) {
+            // about a microsecond per look; the bound is never reached by a launch that is making progress
+            for (int looks = 0; looks < (1 << 20); ++looks) {
+                if (__hip_atomic_load(p.sk_ready + blockIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                    n_splits - 1)
+                    break;
+                __builtin_amdgcn_s_sleep(8);
+            }
+            // ready for the next launch
+            __hip_atomic_store(p.sk_cnt + blockIdx.x, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(p.sk_ready + blockIdx.x, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        // slice order, this workgroup's own slice from its registers
+        static_for<0, MI>([&](auto mi_c) {
+            constexpr int mi = decltype(mi_c)::value;
+            if (m0e + wm * WTM + mi * 32 < p.M) {
+                float sum[NI * 16];
+                _Pragma("unroll") for (int j = 0; j < NI * 16; ++j) sum[j] = 0.f;
+                for (int sl = 0; sl < n_splits; ++sl) {
+                    if (sl == split) {
+                        static_for<0, NI * 16>([&](auto j_c) {
+                            constexpr int j = decltype(j_c)::value;
+                            sum[j] += acc[mi][j / 16][j % 16];
+                        });
+                    } else {
+                        const float* src = part + (size_t)sl * (BM * BN) + (mi * NI * 16) * (NWQ * 64);
+                        float v[NI * 16];
+                        _Pragma("unroll") for (int j = 0; j < NI * 16; ++j)
+                            v[j] = __hip_atomic_load(src + j * (NWQ * 64), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        _Pragma("unroll") for (int j = 0; j < NI * 16; ++j) sum[j] += v[j];
+                    }
+                }
+                static_for<0, NI * 16>([&](auto j_c) {
+                    constexpr int j = decltype(j_c)::value;
+                    acc[mi][j / 16][j % 16] = sum[j];
+                });
+            }
+        });
+    }
+    if (SK && !CF) {
         // Leave this slice's partial tile (register-major, lane contiguous), then count arrivals;
         // 32-row blocks that lie entirely past M (most of the tile at the small scales) are skipped.
         // The partial tiles and the counter are written and read with device-scope atomic accesses
@@ -636,13 +710,13 @@ inline int compute_units() {
     return cus[dev];
 }
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, int KG, int EPI, bool SK = false>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, int KG, int EPI, bool SK = false, bool CF = false>
 void launch_cfg(GemmParams& p, hipStream_t stream) {
     constexpr size_t smem = (size_t)STAGES * (BM + BN) * BK * sizeof(bf16_t);
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
     static std::once_flag once;  // raising the dynamic-LDS limit is per function, once per process
-    raise_lds_limit_once(once, &gemm_nt_kernel<BM, BN, BK, STAGES, WGM, WGN, KG, EPI, SK>, smem);
+    raise_lds_limit_once(once, &gemm_nt_kernel<BM, BN, BK, STAGES, WGM, WGN, KG, EPI, SK, CF>, smem);
     if (!SK) p.splits = 1;
     // one round of workgroups when there are more tiles than the chip holds at a time (the kernel then walks
     // the rest itself); as many workgroups per CU as fit into its 160 KB of LDS
@@ -652,7 +726,7 @@ void launch_cfg(GemmParams& p, hipStream_t stream) {
         const int slots = compute_units() * per_cu;
         if (grid > slots && slots % 8 == 0) grid = slots;
     }
-    gemm_nt_kernel<BM, BN, BK, STAGES, WGM, WGN, KG, EPI, SK>
+    gemm_nt_kernel<BM, BN, BK, STAGES, WGM, WGN, KG, EPI, SK, CF>
         <<<dim3(grid, SK ? p.splits : 1), 64 * WGM * WGN * KG, smem, stream>>>(p);
 }
 
@@ -742,8 +816,9 @@ void launch_epi(GemmParams& p, hipStream_t stream) {
         const SplitKPlan sk = gemm_splitk_plan(p.M, p.N, p.K);
         if (sk.splits > 1) {
             p.splits = sk.splits;
-            if (sk.small_tiles) launch_cfg<64, 64, 64, 8, 2, 2, 1, EPI, true>(p, stream);
-            else launch_cfg<128, 128, 64, 3, 2, 2, 1, EPI, true>(p, stream);
+            if (sk.shape == 0) launch_cfg<64, 64, 64, 8, 2, 2, 1, EPI, true>(p, stream);
+            else if (sk.shape == 1) launch_cfg<128, 128, 64, 3, 2, 2, 1, EPI, true>(p, stream);
+            else launch_cfg<256, 128, 64, 3, 4, 2, 1, EPI, true, true>(p, stream);
             return;
         }
     }
@@ -774,23 +849,40 @@ SplitKPlan gemm_splitk_plan(int M, int N, int K) {
     // slices, FC2 23.4 / 28.4 against 31.4 / 35.3.  Above that, 128x128 tiles split K only where K is long
     // (FC2): with K = 2048 a slice is 8-16 K tiles and the summing costs more than it saves (out-proj at
     // 400 / 576 rows: 21.3 / 23.8 split, 14.9 / 20.6 whole).
-    sk.small_tiles = M <= 256;
-    const int t = sk.small_tiles ? 64 : 128;
+    const bool small = M <= 256;
+    sk.shape = small ? 0 : 1;
+    const int t = small ? 64 : 128;
+    sk.tile_m = sk.tile_n = t;
     sk.tiles = ((M + t - 1) / t) * ((N + t - 1) / t);
     sk.splits = 1;
     const int KT = K / 64;
-    const int min_kt = sk.small_tiles ? 2 : 4;   // K tiles a slice must keep
+    const int min_kt = small ? 2 : 4;   // K tiles a slice must keep
     // a short K range is over before the slices' summing would pay for itself
     static_assert(kSplitKMaxTiles >= 128 && (kSplitKMaxTiles * 4) % 256 == 0, "covers the tile-count limit below");
-    if (K >= (sk.small_tiles ? 2048 : 4096) && sk.tiles <= 128)
-        while (sk.splits < (sk.small_tiles ? 8 : 4) && sk.tiles * sk.splits * 2 <= 256 &&
+    if (K >= (small ? 2048 : 4096) && sk.tiles <= 128)
+        while (sk.splits < (small ? 8 : 4) && sk.tiles * sk.splits * 2 <= 256 &&
                KT % (sk.splits * 2) == 0 && KT / (sk.splits * 2) >= min_kt)
             sk.splits *= 2;   // (more slices than that cost more to sum than they save)
-    // The counter area has one size for every shape (the most tiles the condition above admits): the
+    if (sk.splits == 1 && !small && K >= 8192 && KT % 2 == 0) {
+        // A long K over a narrow output with a few too many rows for the above (FC2 at 1100-1500 rows): 128x128
+        // tiles would fill a little over half of the chip, at the lowest efficiency of the tile shapes; 256x128
+        // tiles on two K slices fill two thirds to three quarters of it and run the main loop a quarter faster,
+        // and with the count-first exchange (see the kernel) their 128 KB partial tiles cost less than that
+        // gain: 1152 rows 68.7 -> 60.2 us.  With more tiles the exchanged bytes win: 1638 rows 70.1 -> 69.1,
+        // 2048 rows 73.1 -> 79.7 (32 MB of partial tiles); those stay on 128x128 tiles unsplit.
+        const int tiles = ((M + 255) / 256) * ((N + 127) / 128);
+        if (tiles * 2 >= 160 && tiles * 2 <= 192) {
+            sk.shape = 2;
+            sk.tile_m = 256; sk.tile_n = 128;
+            sk.tiles = tiles;
+            sk.splits = 2;
+        }
+    }
+    // The counter area has one size for every shape (the most tiles the conditions above admit): the
     // GEMMs of a block share one scratch area, and a partial tile of one must never land on a counter
     // of another.
-    sk.counter_bytes = sk.splits > 1 ? (size_t)kSplitKMaxTiles * 4 : 0;
-    sk.bytes = sk.splits > 1 ? sk.counter_bytes + (size_t)sk.tiles * sk.splits * t * t * 4 : 0;
+    sk.counter_bytes = sk.splits > 1 ? (size_t)kSplitKMaxTiles * 8 : 0;   // arrivals, then ready counts
+    sk.bytes = sk.splits > 1 ? sk.counter_bytes + (size_t)sk.tiles * sk.splits * sk.tile_m * sk.tile_n * 4 : 0;
     return sk;
 }
 
@@ -817,10 +909,12 @@ void launch_gemm(GemmEpilogue epi, const GemmArgs& a, hipStream_t stream) {
     p.splits = 1;
     p.sk_part = nullptr;
     p.sk_cnt = nullptr;
+    p.sk_ready = nullptr;
     if (a.splitk_ws) {
         const SplitKPlan sk = gemm_splitk_plan(a.M, a.N, a.K);
         if (sk.splits > 1) {
             p.sk_cnt = static_cast<int*>(a.splitk_ws);
+            p.sk_ready = p.sk_cnt + kSplitKMaxTiles;
             p.sk_part = reinterpret_cast<float*>(static_cast<char*>(a.splitk_ws) + sk.counter_bytes);
         }
     }

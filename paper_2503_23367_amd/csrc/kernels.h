@@ -106,8 +106,9 @@ constexpr int kSplitKMaxTiles = 128;   // most output tiles a split-K launch has
 struct SplitKPlan {
     int splits;
     int tiles;
-    bool small_tiles;      // 64x64 tiles
-    size_t counter_bytes;  // kSplitKMaxTiles ints whatever the shape: GEMMs that share a scratch area share the counters
+    int shape;             // 0: 64x64 tiles, 1: 128x128, 2: 256x128 (count-first exchange)
+    int tile_m, tile_n;
+    size_t counter_bytes;  // 2 x kSplitKMaxTiles ints (arrivals, ready counts) whatever the shape: GEMMs that share a scratch area share the counters
     size_t bytes;          // counters + partial tiles
 };
 SplitKPlan gemm_splitk_plan(int M, int N, int K);

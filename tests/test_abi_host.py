@@ -74,7 +74,9 @@ def test_workspace_sizes_cover_the_stages():
     assert s > 0 and b >= 2048 * (3 * 2048 + 8192) * 2 and r >= 4096 * 4
     assert fb.fastvar_step_workspace_bytes(d, 1, 4096, 2048) == s + b + r
     assert fb.fastvar_block_workspace_bytes(d, 1, 0) == 0
-    assert fb.fastvar_block_workspace_bytes(d, 2, 2048) > b
+    # (not monotone in the row count: the shapes that split work between workgroups add scratch for partial
+    # results; far enough up the activations dominate)
+    assert fb.fastvar_block_workspace_bytes(d, 8, 2048) > b
     assert fb.fastvar_select_workspace_bytes(0, 16, 64) == 0
 
 

@@ -377,7 +377,8 @@ def _two_block_case(case):
         N = k = side * side
         sides, step, cache_step, hc = [side, 2 * side], 0, 1, side
     else:
-        wl = synth.WORKLOADS[synth.HEADLINE if case == "headline_two_blocks" else "inf2b_1024px_s64_keep0.25"]
+        wl = synth.WORKLOADS[{"headline_two_blocks": synth.HEADLINE, "keep0.25_key_ranges": "inf2b_1024px_s64_keep0.25",
+                              "s48_fc2_two_k_slices": "inf2b_1024px_s48_keep0.5"}[case]]
         B, N, k, L0 = 1, wl.N, wl.k, wl.L0_full
         sides, step, cache_step, hc = list(wl.sides), wl.step, wl.cache_step, wl.hc
     L_cap = (L0 + k + 7) // 8 * 8
@@ -407,11 +408,13 @@ def _two_block_case(case):
     return dict(N=N, k=k, L0=L0, y=y, call=call, poison=poison, snapshot=snapshot, keep=(layers, arr, x, ws, tmp, idx))
 
 
-@pytest.mark.parametrize("case", ["headline_two_blocks", "keep0.25_key_ranges", "structure_step_split_k"])
+@pytest.mark.parametrize("case", ["headline_two_blocks", "keep0.25_key_ranges", "structure_step_split_k",
+                                  "s48_fc2_two_k_slices"])
 def test_same_inputs_give_the_same_bits_every_run(case):
     """Same inputs, same bits: the stack step run 20 times.  The headline step merges two key ranges per
     query tile in its attention; the keep 0.25 step three; the structure step (144 tokens at the large
-    model's widths) splits K between workgroups in all four GEMMs.  All of them let the workgroup that
+    model's widths) splits K between workgroups in all four GEMMs; the 48x48 step at keep 0.5 runs FC2 on
+    two K slices of 256x128 tiles whose last arriver waits for the other's partial tile.  All of them let the workgroup that
     arrives last combine the partial results, so a result that depended on arrival order, or a partial
     result read before it was complete, would show here as a changed bit.  Stops at the first difference."""
     c = _two_block_case(case)

@@ -817,6 +817,9 @@ void launch_epi(GemmParams& p, hipStream_t stream) {
         if (sk.splits > 1) {
             p.splits = sk.splits;
             if (sk.shape == 0) launch_cfg<64, 64, 64, 8, 2, 2, 1, EPI, true>(p, stream);
+            // (128x128: two long slices run best on the eight-wave four-stage tile, four short ones on the
+            // four-wave three-stage one: FC2 at 576 / 960 rows 48.9 -> 46.5 / 49.6 -> 48.0 us, at 400 rows 33.9 vs 35.1)
+            else if (sk.shape == 1 && sk.splits == 2) launch_cfg<128, 128, 64, 4, 2, 4, 1, EPI, true>(p, stream);
             else if (sk.shape == 1) launch_cfg<128, 128, 64, 3, 2, 2, 1, EPI, true>(p, stream);
             else launch_cfg<256, 128, 64, 3, 4, 2, 1, EPI, true, true>(p, stream);
             return;

@@ -91,6 +91,8 @@ __device__ __forceinline__ int swz(int row) {
 // SK: the K range is also split between workgroups (blockIdx.y); every workgroup leaves its partial
 // tile in scratch memory, and the one that arrives last at the tile's counter adds the slices up, in
 // slice order (so the sum does not depend on who was last), and runs the epilogue.  Nobody waits.
+// CF (with SK; large partial tiles): the slices count themselves in first, only the earlier arrivers
+// store, and the last one polls for their stores: see the epilogue.
 template <int EPI, int KG, bool SK>
 constexpr bool kPersistent = !SK && KG == 1 && is_qkv(EPI);
 

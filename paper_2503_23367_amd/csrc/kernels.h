@@ -99,9 +99,10 @@ void launch_gemm(GemmEpilogue epi, const GemmArgs& a, hipStream_t stream);
 // Split-K plan for a GEMM shape with few output tiles (few rows: the small scales of a schedule, where
 // a block is nothing but streaming its weights once): the K range is cut into `splits` slices that run
 // as separate workgroups, so that every CU streams a share of the weights; the workgroup that finishes
-// a tile last sums the slices in slice order and runs the epilogue.  Up to 64 rows use 64x64 tiles with
+// a tile last sums the slices in slice order and runs the epilogue.  Up to 256 rows use 64x64 tiles with
 // an eight-stage ring (a workgroup's whole K slice, or half of it, is in flight at once), more rows
-// 128x128 tiles.  splits == 1: no scratch needed.
+// 128x128 tiles where K is long; FC2-like shapes a little too tall for those, 256x128 tiles on two slices.
+// splits == 1: no scratch needed.
 constexpr int kSplitKMaxTiles = 128;   // most output tiles a split-K launch has
 struct SplitKPlan {
     int splits;

@@ -1264,6 +1264,11 @@ AttnSplitPlan attention_split_plan(int B, int H, int dh, int k_tokens, int L, si
     AttnSplitPlan sp{1, 0, false, 0, 0, 0, 0, 0};
     if (dh != 128 || L <= 256 || k_tokens <= 0) return sp;
     const long wg128 = (long)((k_tokens + 127) / 128) * H * B;
+    // With fewer than 128 workgroups of 128 queries the unsplit launch is the plain kernel's 64-query workgroups
+    // (keys split in two inside the workgroup), which the model below does not describe; over a short cache
+    // they win (400 / 576 queries over 921 / 1497 keys: 22.3 / 29.3 us against 25.5 / 33.7 on two / three
+    // ranges), over a long one the ranges do (410 queries over 6835 keys).
+    if (wg128 < 128 && L < 2048) return sp;
     const long wg256 = (long)((k_tokens + 255) / 256) * H * B;
     const size_t per_query_row = (size_t)(1 + 4 * 2 * 4) * 64 * 16;   // per wave of 64 queries: 33 vectors of 16 bytes per lane
     // The counters take the same room whichever variant is chosen (one per 128-query tile, the larger count).
